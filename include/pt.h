@@ -1,0 +1,166 @@
+/*
+ * pt.h - C ABI of the MI355X (gfx950) Parallel Track (PT) transformer forward library.
+ *
+ * The library computes Algorithm 1 of the paper ("Track Parallelism for PT Transformer",
+ * Section 2.2): n independent transformer tracks of L layers each; after every D-th layer the
+ * per-track activations are all-reduced and every track continues from the reduced activation.
+ * On one GPU all tracks are resident and run as a track-batched prefill and a KV-cached decode;
+ * the all-reduce is an on-device reduction (pt_track_merge).
+ *
+ * The paper does not define the "standard transformer layer" inside a track beyond
+ * grouped-query attention (Section 3.1, Table 1).  This library fixes it as: pre-norm RMSNorm,
+ * rotary position embedding (rotate-half pairing), causal softmax attention with grouped KV
+ * heads, SwiGLU feed-forward, no biases, one shared embedding, one final RMSNorm and an untied
+ * output head applied to the merged activation.
+ *
+ * Conventions
+ *  - Every function returns PT_OK (0) or a negative PT_ERR_* code; none throws, aborts or
+ *    prints.  pt_last_error() returns a thread-local description of the last failure.
+ *  - "dev" pointers are HIP device pointers, "host" pointers are host memory.
+ *  - Ownership: the caller allocates every device buffer and the stream and keeps them alive
+ *    until pt_destroy; the library never allocates or frees device memory.  It sub-allocates
+ *    the three arenas handed to pt_create.
+ *  - All device work is enqueued on the stream given to pt_create (pt_track_merge: on the
+ *    stream argument) and is asynchronous; the caller synchronises.
+ *  - Calls on one handle must not overlap.
+ */
+#ifndef PT_H_
+#define PT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { PT_F32 = 0, PT_BF16 = 1 };
+
+enum {
+  PT_OK = 0,
+  PT_ERR_INVALID_CONFIG = -1,
+  PT_ERR_NULL_POINTER = -2,
+  PT_ERR_ARENA_TOO_SMALL = -3,
+  PT_ERR_CAPACITY = -4,  /* batch or sequence beyond max_batch / max_seq */
+  PT_ERR_BAD_STATE = -5, /* e.g. decode before prefill, forward before weights exist */
+  PT_ERR_HIP = -6,
+  PT_ERR_INVALID_ARGUMENT = -7
+};
+
+/* Which logits pt_prefill writes. */
+enum { PT_LOGITS_NONE = 0, PT_LOGITS_LAST = 1, PT_LOGITS_ALL = 2 };
+
+/* Logical tensors of the model, for pt_set_weight / pt_get_weight.  Logical layouts follow
+ * the "x @ W" convention, row-major:
+ *   WQ [d, H*hd]  WK, WV [d, Hkv*hd]  WO [H*hd, d]  WG, WU [d, f]  WD [f, d]
+ *   G1, G2 [d] (RMSNorm gains before attention / before the FFN)
+ *   EMBED [vocab, d]  HEAD [d, vocab]  GF [d] (final RMSNorm gain)
+ * The numbering of the random tensors equals the stream kinds of the seeded generator. */
+enum {
+  PT_W_EMBED = 1, PT_W_HEAD = 2, PT_W_Q = 3, PT_W_K = 4, PT_W_V = 5, PT_W_O = 6,
+  PT_W_G = 7, PT_W_U = 8, PT_W_D = 9, PT_W_G1 = 10, PT_W_G2 = 11, PT_W_GF = 12
+};
+
+/* Shape of a PT model.  Algorithm 1's n, L, D are n_tracks, n_layers, block_depth; the
+ * remaining fields give the per-track layer (Section 3.1: heads and KV heads are per track). */
+typedef struct pt_config {
+  int32_t n_tracks;    /* n in 1..16 */
+  int32_t n_layers;    /* L per track, L % block_depth == 0 */
+  int32_t block_depth; /* D: layers between two merges */
+  int32_t d_model;     /* per-track width; multiple of 8 */
+  int32_t n_heads;     /* query heads per track */
+  int32_t n_kv_heads;  /* KV heads per track; divides n_heads */
+  int32_t head_dim;    /* multiple of 8 */
+  int32_t d_ffn;       /* multiple of 32 */
+  int32_t vocab;       /* multiple of 8; 0: hidden-state in, hidden-state out (no embedding, no head) */
+  int32_t max_batch;
+  int32_t max_seq;     /* KV-cache capacity per sequence */
+  int32_t dtype;       /* PT_F32 | PT_BF16: weights, KV cache, GEMM/attention operands.
+                          Residual stream, merge, softmax statistics and accumulators are fp32. */
+  float merge_scale;   /* merged h = merge_scale * sum_i h_i; 1 = the literal all-reduce sum */
+  float rms_eps;
+  float rope_theta;
+  float init_std;      /* standard deviation used by pt_init_weights */
+} pt_config;
+
+typedef struct pt_handle pt_handle;
+
+/* Host only.  Validates cfg and reports the bytes of the three device arenas pt_create needs:
+ * weights, KV cache, workspace.  Any out pointer may be NULL. */
+int pt_query_bytes(const pt_config* cfg, size_t* weight_bytes, size_t* kv_bytes, size_t* ws_bytes);
+
+/* Creates a handle over caller-owned arenas (256-byte aligned device pointers) and a caller-
+ * owned hipStream_t (NULL = the default stream).  Touches no device memory.
+ * Errors: INVALID_CONFIG, NULL_POINTER, ARENA_TOO_SMALL. */
+int pt_create(const pt_config* cfg, void* dev_weights, size_t weight_bytes, void* dev_kv,
+              size_t kv_bytes, void* dev_ws, size_t ws_bytes, void* hip_stream, pt_handle** out);
+int pt_destroy(pt_handle* h);
+
+/* Fills every weight on the device from the counter-based generator (stream (seed, kind,
+ * track, layer), Box-Muller normals scaled by init_std, rounded to cfg.dtype); gains = 1. */
+int pt_init_weights(pt_handle* h, uint64_t seed);
+
+/* Copies one logical tensor between a device fp32 buffer in the logical layout above and the
+ * library's physical storage (rounding to cfg.dtype on the way in).  track/layer are ignored
+ * for EMBED, HEAD and GF. */
+int pt_set_weight(pt_handle* h, int32_t tensor, int32_t track, int32_t layer, const float* dev_src);
+int pt_get_weight(pt_handle* h, int32_t tensor, int32_t track, int32_t layer, float* dev_dst);
+
+/* Prefill (Algorithm 1 over B sequences of S tokens starting at position 0; fills the KV cache
+ * and sets every sequence length to S).
+ *   dev_tokens     int32 [B, S]; used when cfg.vocab > 0 and dev_hidden_in == NULL.
+ *   dev_hidden_in  fp32 [hidden_tracks, B*S, d] with hidden_tracks == 1 (the same input x for
+ *                  every track, as in Algorithm 1) or == n_tracks (per-track inputs).
+ *   logits_mode    PT_LOGITS_*; dev_logits fp32 [B, V] (LAST) or [B*S, V] (ALL); needs vocab > 0.
+ *   dev_hidden_out fp32 [B*S, d], the output activation h of Algorithm 1; may be NULL.
+ * Errors: NULL_POINTER, CAPACITY (B > max_batch or S > max_seq), BAD_STATE, INVALID_ARGUMENT. */
+int pt_prefill(pt_handle* h, const int32_t* dev_tokens, const float* dev_hidden_in,
+               int32_t hidden_tracks, int32_t B, int32_t S, int32_t logits_mode,
+               float* dev_logits, float* dev_hidden_out);
+
+/* One KV-cached decode step: one new row per sequence at position len, appended to the cache.
+ *   dev_tokens int32 [B] or dev_hidden_in fp32 [hidden_tracks, B, d]; B must equal the B of the
+ *   preceding prefill.  dev_logits fp32 [B, V], dev_hidden_out fp32 [B, d], dev_argmax int32 [B]
+ *   (lowest id on ties); each may be NULL.
+ * Errors as pt_prefill; CAPACITY when len + 1 > max_seq; BAD_STATE before a prefill. */
+int pt_decode_step(pt_handle* h, const int32_t* dev_tokens, const float* dev_hidden_in,
+                   int32_t hidden_tracks, int32_t B, float* dev_logits, float* dev_hidden_out,
+                   int32_t* dev_argmax);
+
+/* The track merge of Algorithm 1 (the all-reduce, as an on-device reduction), stateless:
+ *   out[t, :] = scale * (tracks[0][t, :] + ... + tracks[n-1][t, :]), fp32 accumulation in track
+ *   order, for t < tokens.  host_tracks is a HOST array of n DEVICE pointers, each [tokens, d]
+ *   of element type dtype (PT_F32 | PT_BF16); dev_out has the same type and may alias
+ *   tracks[0].  n <= 16.  d must be a multiple of 8.  Enqueued on hip_stream. */
+int pt_track_merge(const void* const* host_tracks, int32_t n, int64_t tokens, int32_t d,
+                   int32_t dtype, float scale, void* dev_out, void* hip_stream);
+
+/* Optional observation point: when set (non-NULL), every merge inside pt_prefill /
+ * pt_decode_step also stores the merged activation to dev_taps, fp32
+ * [n_layers / block_depth, rows, d] with rows = B*S (prefill) or B (decode), and the per-track
+ * activations right before the merge to dev_track_taps (may be NULL), fp32
+ * [n_layers / block_depth, n_tracks, rows, d]. */
+int pt_set_taps(pt_handle* h, float* dev_taps, float* dev_track_taps);
+
+/* Kernel selection.  PT_PATH_AUTO (default) uses the MFMA / bandwidth-tuned kernels wherever the
+ * shape allows and the shape-generic kernels elsewhere; PT_PATH_GENERIC forces the shape-generic
+ * kernels everywhere (slow; used to cross-check the tuned kernels). */
+enum { PT_PATH_AUTO = 0, PT_PATH_GENERIC = 1 };
+int pt_set_kernel_path(pt_handle* h, int32_t path);
+
+/* Forgets all sequences (lengths = 0); the KV cache contents become dead. */
+int pt_reset(pt_handle* h);
+
+/* Number of merges executed by forward calls on this handle since pt_create (one per track
+ * block: L/D per forward pass, against 2L sync points of tensor parallelism; Section 2.2). */
+int64_t pt_merge_count(const pt_handle* h);
+
+/* Current sequence length (identical for all sequences of the batch), or a negative error. */
+int32_t pt_seq_len(const pt_handle* h);
+
+const char* pt_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PT_H_ */

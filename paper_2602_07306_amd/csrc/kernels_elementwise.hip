@@ -1,0 +1,257 @@
+// Bandwidth-bound kernels of the PT forward: embedding gather, RMSNorm, the track merge of
+// Algorithm 1 (Section 2.2), argmax, the rotary table, and small copies.
+#include "pt_device.h"
+
+// ------------------------------------------------------------------------------------------
+// Embedding: h[row, :] = E[token[row], :] as fp32.  Out-of-range ids are clamped into the table.
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) embed_kernel(const T* __restrict__ E, const int32_t* __restrict__ tok,
+                                                    int64_t rows, int32_t d, int32_t vocab, float* __restrict__ h) {
+  const int64_t row = blockIdx.x;
+  if (row >= rows) return;
+  int32_t id = tok[row];
+  id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
+  const T* src = E + (int64_t)id * d;
+  float* dst = h + row * d;
+  for (int c = threadIdx.x; c < d; c += 256) dst[c] = elem<T>::ld(src + c);
+}
+
+int pt_launch_embed(const void* embed, int32_t dtype, const int32_t* tokens, int64_t rows, int32_t d,
+                    int32_t vocab, float* h, hipStream_t s) {
+  if (rows <= 0) return PT_OK;
+  if (dtype == PT_F32)
+    hipLaunchKernelGGL(embed_kernel<float>, dim3((unsigned)rows), dim3(256), 0, s, (const float*)embed, tokens, rows, d, vocab, h);
+  else
+    hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3((unsigned)rows), dim3(256), 0, s, (const bf16_t*)embed, tokens, rows, d, vocab, h);
+  PT_HIP_CHECK(hipGetLastError());
+  return PT_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// RMSNorm: out = h * g / sqrt(mean(h^2) + eps); fp32 statistics; one wavefront per row.
+// Row r of track b reads h + b*h_bstride + row_index(r)*d with row_index(r) = r*row_step + row_off.
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) rmsnorm_kernel(const float* __restrict__ h, int64_t h_bstride,
+                                                      const float* __restrict__ gains, int64_t g_bstride,
+                                                      T* __restrict__ out, int64_t out_bstride, int64_t rows,
+                                                      int64_t row_step, int64_t row_off, int32_t d, float eps) {
+  const int lane = threadIdx.x & 63;
+  const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int b = blockIdx.y;
+  if (r >= rows) return;
+  const float4* src = (const float4*)(h + b * h_bstride + (r * row_step + row_off) * d);
+  const float4* g = (const float4*)(gains + b * g_bstride);
+  const int n4 = d >> 2;
+  float ss = 0.f;
+  for (int i = lane; i < n4; i += 64) {
+    float4 v = src[i];
+    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+  ss = wave_sum(ss);
+  const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+  T* dst = out + b * out_bstride + r * d;
+  for (int i = lane; i < n4; i += 64) {
+    float4 v = src[i];
+    float4 w = g[i];
+    elem<T>::st(dst + 4 * i + 0, v.x * inv * w.x);
+    elem<T>::st(dst + 4 * i + 1, v.y * inv * w.y);
+    elem<T>::st(dst + 4 * i + 2, v.z * inv * w.z);
+    elem<T>::st(dst + 4 * i + 3, v.w * inv * w.w);
+  }
+}
+
+static int launch_rmsnorm(const float* h, int64_t h_bstride, const float* gains, int64_t g_bstride, void* out,
+                          int64_t out_bstride, int32_t dtype, int32_t batch, int64_t rows, int64_t row_step,
+                          int64_t row_off, int32_t d, float eps, hipStream_t s) {
+  if (rows <= 0 || batch <= 0) return PT_OK;
+  dim3 grid((unsigned)((rows + 3) / 4), (unsigned)batch);
+  if (dtype == PT_F32)
+    hipLaunchKernelGGL(rmsnorm_kernel<float>, grid, dim3(256), 0, s, h, h_bstride, gains, g_bstride, (float*)out,
+                       out_bstride, rows, row_step, row_off, d, eps);
+  else
+    hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, grid, dim3(256), 0, s, h, h_bstride, gains, g_bstride, (bf16_t*)out,
+                       out_bstride, rows, row_step, row_off, d, eps);
+  PT_HIP_CHECK(hipGetLastError());
+  return PT_OK;
+}
+
+int pt_launch_rmsnorm(const float* h, int64_t h_bstride, const float* gains, int64_t g_bstride, void* out,
+                      int64_t out_bstride, int32_t dtype, int32_t batch, int64_t rows, int32_t d, float eps,
+                      hipStream_t s) {
+  return launch_rmsnorm(h, h_bstride, gains, g_bstride, out, out_bstride, dtype, batch, rows, 1, 0, d, eps, s);
+}
+
+int pt_launch_rmsnorm_rows(const float* h, const float* gain, void* out, int32_t dtype, int64_t rows,
+                           int64_t row_step, int64_t row_off, int32_t d, float eps, hipStream_t s) {
+  return launch_rmsnorm(h, 0, gain, 0, out, 0, dtype, 1, rows, row_step, row_off, d, eps, s);
+}
+
+// ------------------------------------------------------------------------------------------
+// Track merge (the all-reduce of Algorithm 1 on one device):
+//   out = scale * (t_0 + t_1 + ... + t_{n-1}), fp32 accumulation in track order.
+// Each thread owns 8 consecutive elements per step: every track is read exactly once with 16-byte
+// (bf16) or 2 x 16-byte (fp32) loads and the result is written exactly once.
+// ------------------------------------------------------------------------------------------
+struct merge_ptrs {
+  const void* t[16];
+};
+
+template <typename T>
+__global__ void __launch_bounds__(256) merge_kernel(merge_ptrs p, int n, int64_t chunks, float scale,
+                                                    T* __restrict__ out, float* __restrict__ tap);
+
+template <>
+__global__ void __launch_bounds__(256) merge_kernel<float>(merge_ptrs p, int n, int64_t chunks, float scale,
+                                                           float* __restrict__ out, float* __restrict__ tap) {
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x; c < chunks; c += stride) {
+    float4 a0 = ((const float4*)p.t[0])[2 * c], a1 = ((const float4*)p.t[0])[2 * c + 1];
+    for (int i = 1; i < n; ++i) {
+      const float4 b0 = ((const float4*)p.t[i])[2 * c], b1 = ((const float4*)p.t[i])[2 * c + 1];
+      a0.x += b0.x; a0.y += b0.y; a0.z += b0.z; a0.w += b0.w;
+      a1.x += b1.x; a1.y += b1.y; a1.z += b1.z; a1.w += b1.w;
+    }
+    a0.x *= scale; a0.y *= scale; a0.z *= scale; a0.w *= scale;
+    a1.x *= scale; a1.y *= scale; a1.z *= scale; a1.w *= scale;
+    ((float4*)out)[2 * c] = a0;
+    ((float4*)out)[2 * c + 1] = a1;
+    if (tap) {
+      ((float4*)tap)[2 * c] = a0;
+      ((float4*)tap)[2 * c + 1] = a1;
+    }
+  }
+}
+
+template <>
+__global__ void __launch_bounds__(256) merge_kernel<bf16_t>(merge_ptrs p, int n, int64_t chunks, float scale,
+                                                            bf16_t* __restrict__ out, float* __restrict__ tap) {
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x; c < chunks; c += stride) {
+    float acc[8];
+    {
+      const uint4 v = ((const uint4*)p.t[0])[c];
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        acc[2 * k] = __uint_as_float(w[k] << 16);
+        acc[2 * k + 1] = __uint_as_float(w[k] & 0xffff0000u);
+      }
+    }
+    for (int i = 1; i < n; ++i) {
+      const uint4 v = ((const uint4*)p.t[i])[c];
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        acc[2 * k] += __uint_as_float(w[k] << 16);
+        acc[2 * k + 1] += __uint_as_float(w[k] & 0xffff0000u);
+      }
+    }
+    uint4 o;
+    o.x = pack_bf16x2(acc[0] * scale, acc[1] * scale);
+    o.y = pack_bf16x2(acc[2] * scale, acc[3] * scale);
+    o.z = pack_bf16x2(acc[4] * scale, acc[5] * scale);
+    o.w = pack_bf16x2(acc[6] * scale, acc[7] * scale);
+    ((uint4*)out)[c] = o;
+  }
+}
+
+int pt_launch_merge(const void* const* tracks, int32_t n, int64_t elems, int32_t dtype, float scale, void* out,
+                    float* tap, hipStream_t s) {
+  if (elems <= 0) return PT_OK;
+  merge_ptrs p;
+  for (int i = 0; i < 16; ++i) p.t[i] = i < n ? tracks[i] : nullptr;
+  const int64_t chunks = elems / 8;
+  int64_t blocks = (chunks + 255) / 256;
+  if (blocks > 256 * 16) blocks = 256 * 16;
+  if (dtype == PT_F32)
+    hipLaunchKernelGGL(merge_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, s, p, n, chunks, scale, (float*)out, tap);
+  else
+    hipLaunchKernelGGL(merge_kernel<bf16_t>, dim3((unsigned)blocks), dim3(256), 0, s, p, n, chunks, scale, (bf16_t*)out, tap);
+  PT_HIP_CHECK(hipGetLastError());
+  return PT_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) copy_f32_kernel(const float* __restrict__ src, float* __restrict__ dst, int64_t n) {
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
+int pt_launch_copy_f32(const float* src, float* dst, int64_t elems, hipStream_t s) {
+  if (elems <= 0) return PT_OK;
+  int64_t blocks = (elems + 255) / 256;
+  if (blocks > 256 * 32) blocks = 256 * 32;
+  hipLaunchKernelGGL(copy_f32_kernel, dim3((unsigned)blocks), dim3(256), 0, s, src, dst, elems);
+  PT_HIP_CHECK(hipGetLastError());
+  return PT_OK;
+}
+
+__global__ void __launch_bounds__(256) fill_f32_kernel(float* __restrict__ dst, int64_t n, float v) {
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) dst[i] = v;
+}
+
+int pt_launch_fill_f32(float* dst, int64_t n, float v, hipStream_t s) {
+  if (n <= 0) return PT_OK;
+  int64_t blocks = (n + 255) / 256;
+  if (blocks > 256 * 32) blocks = 256 * 32;
+  hipLaunchKernelGGL(fill_f32_kernel, dim3((unsigned)blocks), dim3(256), 0, s, dst, n, v);
+  PT_HIP_CHECK(hipGetLastError());
+  return PT_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Greedy token: argmax over the vocabulary, lowest id on ties.  One workgroup per row.
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) argmax_kernel(const float* __restrict__ logits, int32_t vocab, int32_t* __restrict__ out) {
+  __shared__ float sv[256];
+  __shared__ int32_t si[256];
+  const float* row = logits + (int64_t)blockIdx.x * vocab;
+  float best = -INFINITY;
+  int32_t bi = 0x7fffffff;
+  for (int i = threadIdx.x; i < vocab; i += 256) {
+    const float v = row[i];
+    if (v > best || (v == best && i < bi)) { best = v; bi = i; }
+  }
+  sv[threadIdx.x] = best;
+  si[threadIdx.x] = bi;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) {
+      const float v = sv[threadIdx.x + o];
+      const int32_t i = si[threadIdx.x + o];
+      if (v > sv[threadIdx.x] || (v == sv[threadIdx.x] && i < si[threadIdx.x])) { sv[threadIdx.x] = v; si[threadIdx.x] = i; }
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[blockIdx.x] = si[0] == 0x7fffffff ? 0 : si[0];
+}
+
+int pt_launch_argmax(const float* logits, int32_t rows, int32_t vocab, int32_t* out, hipStream_t s) {
+  if (rows <= 0) return PT_OK;
+  hipLaunchKernelGGL(argmax_kernel, dim3((unsigned)rows), dim3(256), 0, s, logits, vocab, out);
+  PT_HIP_CHECK(hipGetLastError());
+  return PT_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Rotary table: table[p][j] = (cos, sin)(p * theta^(-2j/hd)), angle evaluated in double.
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) rope_table_kernel(float2* __restrict__ table, int32_t max_seq, int32_t half, double theta, int32_t hd) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (int64_t)max_seq * half) return;
+  const int p = (int)(i / half), j = (int)(i % half);
+  const double inv_freq = pow(theta, -2.0 * (double)j / (double)hd);
+  const double ang = (double)p * inv_freq;
+  table[i] = make_float2((float)cos(ang), (float)sin(ang));
+}
+
+int pt_launch_rope_table(float* table, int32_t max_seq, int32_t hd, float theta, hipStream_t s) {
+  const int half = hd / 2;
+  const int64_t n = (int64_t)max_seq * half;
+  hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (float2*)table, max_seq, half, (double)theta, hd);
+  PT_HIP_CHECK(hipGetLastError());
+  return PT_OK;
+}

@@ -1,0 +1,460 @@
+// Host side of libpt: configuration checks, arena layout, and the launch sequence of
+// Algorithm 1 (Section 2.2 of the paper) for prefill and KV-cached decode.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "pt_internal.h"
+
+static thread_local char g_err[512] = "";
+
+int pt_set_error(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+extern "C" const char* pt_last_error(void) { return g_err; }
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int pt_validate_config(const pt_config* c) {
+  if (!c) return pt_set_error(PT_ERR_NULL_POINTER, "config is NULL");
+  if (c->n_tracks < 1 || c->n_tracks > 16)
+    return pt_set_error(PT_ERR_INVALID_CONFIG, "n_tracks = %d, need 1..16", c->n_tracks);
+  if (c->n_layers < 1 || c->block_depth < 1)
+    return pt_set_error(PT_ERR_INVALID_CONFIG, "n_layers and block_depth must be >= 1");
+  if (c->n_layers % c->block_depth != 0)
+    return pt_set_error(PT_ERR_INVALID_CONFIG,
+                        "n_layers (%d) is not a multiple of block_depth (%d): the output of "
+                        "Algorithm 1 is only defined by a merge", c->n_layers, c->block_depth);
+  if (c->d_model < 8 || c->d_model % 8) return pt_set_error(PT_ERR_INVALID_CONFIG, "d_model must be a positive multiple of 8");
+  if (c->head_dim < 8 || c->head_dim % 8 || c->head_dim > 256)
+    return pt_set_error(PT_ERR_INVALID_CONFIG, "head_dim must be a multiple of 8 in 8..256");
+  if (c->n_heads < 1 || c->n_kv_heads < 1 || c->n_heads % c->n_kv_heads)
+    return pt_set_error(PT_ERR_INVALID_CONFIG, "n_kv_heads (%d) must divide n_heads (%d)", c->n_kv_heads, c->n_heads);
+  if (c->d_ffn < 32 || c->d_ffn % 32) return pt_set_error(PT_ERR_INVALID_CONFIG, "d_ffn must be a positive multiple of 32");
+  if (c->vocab < 0 || c->vocab % 8) return pt_set_error(PT_ERR_INVALID_CONFIG, "vocab must be 0 or a positive multiple of 8");
+  if (c->max_batch < 1 || c->max_seq < 1) return pt_set_error(PT_ERR_INVALID_CONFIG, "max_batch and max_seq must be >= 1");
+  if ((int64_t)c->max_batch * c->max_seq > (int64_t)1 << 30)
+    return pt_set_error(PT_ERR_INVALID_CONFIG, "max_batch * max_seq too large");
+  if (c->dtype != PT_F32 && c->dtype != PT_BF16) return pt_set_error(PT_ERR_INVALID_CONFIG, "dtype must be PT_F32 or PT_BF16");
+  if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f) || !(c->init_std >= 0.f) || !(c->merge_scale == c->merge_scale))
+    return pt_set_error(PT_ERR_INVALID_CONFIG, "rms_eps, rope_theta, init_std or merge_scale out of range");
+  return PT_OK;
+}
+
+int pt_compute_layout(const pt_config* c, pt_layout* l) {
+  memset(l, 0, sizeof(*l));
+  const int64_t T = c->n_tracks, L = c->n_layers, d = c->d_model, f = c->d_ffn, hd = c->head_dim;
+  const int64_t es = c->dtype == PT_F32 ? 4 : 2;
+  l->elem_size = (int32_t)es;
+  l->hq = (int64_t)c->n_heads * hd;
+  l->hk = (int64_t)c->n_kv_heads * hd;
+  l->n_qkv = l->hq + 2 * l->hk;
+  auto up = [](int64_t x) { return (x + 127) / 128 * 128; };
+  l->wqkv_elems = up(l->n_qkv * d);
+  l->wo_elems = up(d * l->hq);
+  l->wgu_elems = up(2 * f * d);
+  l->wd_elems = up(d * f);
+  l->layer_w_elems = l->wqkv_elems + l->wo_elems + l->wgu_elems + l->wd_elems;
+  size_t off = 0;
+  l->off_layers = off; off = align_up(off + (size_t)(T * L * l->layer_w_elems * es), 256);
+  l->off_gains = off;  off = align_up(off + (size_t)(T * L * 2 * d * 4), 256);
+  l->off_gf = off;     off = align_up(off + (size_t)(d * 4), 256);
+  l->off_embed = off;  off = align_up(off + (size_t)((int64_t)c->vocab * d * es), 256);
+  l->off_headT = off;  off = align_up(off + (size_t)((int64_t)c->vocab * d * es), 256);
+  l->weight_bytes = off;
+
+  l->s_pad = (c->max_seq + 63) / 64 * 64 + 64;
+  const int64_t B = c->max_batch;
+  const int64_t k_head = (int64_t)c->max_seq * hd, v_head = hd * l->s_pad;
+  l->off_k = 0;
+  l->off_v = align_up((size_t)(T * L * B * c->n_kv_heads * k_head * es), 256);
+  l->kv_bytes = align_up(l->off_v + (size_t)(T * L * B * c->n_kv_heads * v_head * es), 256);
+
+  const int64_t M = B * c->max_seq;
+  l->max_splits = 32;
+  off = 0;
+  l->off_h = off;    off = align_up(off + (size_t)(T * M * d * 4), 256);
+  l->off_hm = off;   off = align_up(off + (size_t)(M * d * 4), 256);
+  l->off_a = off;    off = align_up(off + (size_t)(T * M * d * es), 256);
+  l->off_q = off;    off = align_up(off + (size_t)(T * M * l->hq * es), 256);
+  l->off_o = off;    off = align_up(off + (size_t)(T * M * l->hq * es), 256);
+  l->off_m = off;    off = align_up(off + (size_t)(T * M * f * es), 256);
+  l->off_rope = off; off = align_up(off + (size_t)((int64_t)c->max_seq * hd * 4), 256);
+  l->off_part = off; off = align_up(off + (size_t)(T * B * c->n_heads * l->max_splits * (hd + 2) * 4), 256);
+  l->off_last = off; off = align_up(off + (size_t)(B * d * es), 256);
+  l->ws_bytes = off;
+  return PT_OK;
+}
+
+extern "C" int pt_query_bytes(const pt_config* cfg, size_t* w, size_t* kv, size_t* ws) {
+  int rc = pt_validate_config(cfg);
+  if (rc) return rc;
+  pt_layout l;
+  pt_compute_layout(cfg, &l);
+  if (w) *w = l.weight_bytes;
+  if (kv) *kv = l.kv_bytes;
+  if (ws) *ws = l.ws_bytes;
+  return PT_OK;
+}
+
+extern "C" int pt_create(const pt_config* cfg, void* dev_weights, size_t weight_bytes, void* dev_kv,
+                         size_t kv_bytes, void* dev_ws, size_t ws_bytes, void* hip_stream,
+                         pt_handle** out) {
+  int rc = pt_validate_config(cfg);
+  if (rc) return rc;
+  if (!out) return pt_set_error(PT_ERR_NULL_POINTER, "out is NULL");
+  *out = nullptr;
+  if (!dev_weights || !dev_kv || !dev_ws) return pt_set_error(PT_ERR_NULL_POINTER, "an arena pointer is NULL");
+  if (((uintptr_t)dev_weights | (uintptr_t)dev_kv | (uintptr_t)dev_ws) & 255)
+    return pt_set_error(PT_ERR_INVALID_ARGUMENT, "arena pointers must be 256-byte aligned");
+  pt_layout l;
+  pt_compute_layout(cfg, &l);
+  if (weight_bytes < l.weight_bytes)
+    return pt_set_error(PT_ERR_ARENA_TOO_SMALL, "weight arena: %zu bytes given, %zu needed", weight_bytes, l.weight_bytes);
+  if (kv_bytes < l.kv_bytes)
+    return pt_set_error(PT_ERR_ARENA_TOO_SMALL, "KV arena: %zu bytes given, %zu needed", kv_bytes, l.kv_bytes);
+  if (ws_bytes < l.ws_bytes)
+    return pt_set_error(PT_ERR_ARENA_TOO_SMALL, "workspace arena: %zu bytes given, %zu needed", ws_bytes, l.ws_bytes);
+  pt_handle* h = new (std::nothrow) pt_handle();
+  if (!h) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "out of host memory");
+  h->cfg = *cfg;
+  h->lay = l;
+  h->w = (char*)dev_weights;
+  h->kv = (char*)dev_kv;
+  h->ws = (char*)dev_ws;
+  h->stream = (hipStream_t)hip_stream;
+  h->batch = 0;
+  h->seq_len = 0;
+  h->merges = 0;
+  h->weights_ready = false;
+  h->rope_ready = false;
+  h->taps = nullptr;
+  h->track_taps = nullptr;
+  h->path = PT_PATH_AUTO;
+  *out = h;
+  return PT_OK;
+}
+
+extern "C" int pt_destroy(pt_handle* h) {
+  if (!h) return pt_set_error(PT_ERR_NULL_POINTER, "handle is NULL");
+  delete h;
+  return PT_OK;
+}
+
+extern "C" int pt_reset(pt_handle* h) {
+  if (!h) return pt_set_error(PT_ERR_NULL_POINTER, "handle is NULL");
+  h->batch = 0;
+  h->seq_len = 0;
+  return PT_OK;
+}
+
+extern "C" int64_t pt_merge_count(const pt_handle* h) { return h ? h->merges : (int64_t)PT_ERR_NULL_POINTER; }
+extern "C" int32_t pt_seq_len(const pt_handle* h) { return h ? h->seq_len : (int32_t)PT_ERR_NULL_POINTER; }
+
+extern "C" int pt_set_taps(pt_handle* h, float* dev_taps, float* dev_track_taps) {
+  if (!h) return pt_set_error(PT_ERR_NULL_POINTER, "handle is NULL");
+  h->taps = dev_taps;
+  h->track_taps = dev_track_taps;
+  return PT_OK;
+}
+
+extern "C" int pt_set_kernel_path(pt_handle* h, int32_t path) {
+  if (!h) return pt_set_error(PT_ERR_NULL_POINTER, "handle is NULL");
+  if (path != PT_PATH_AUTO && path != PT_PATH_GENERIC)
+    return pt_set_error(PT_ERR_INVALID_ARGUMENT, "unknown kernel path %d", path);
+  h->path = path;
+  return PT_OK;
+}
+
+extern "C" int pt_init_weights(pt_handle* h, uint64_t seed) {
+  if (!h) return pt_set_error(PT_ERR_NULL_POINTER, "handle is NULL");
+  int rc = pt_launch_weight_init(h, seed);
+  if (rc) return rc;
+  h->weights_ready = true;
+  return PT_OK;
+}
+
+static int check_tensor(const pt_handle* h, int32_t tensor, int32_t track, int32_t layer) {
+  if (tensor < PT_W_EMBED || tensor > PT_W_GF) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "unknown tensor id %d", tensor);
+  const bool global = tensor == PT_W_EMBED || tensor == PT_W_HEAD || tensor == PT_W_GF;
+  if ((tensor == PT_W_EMBED || tensor == PT_W_HEAD) && h->cfg.vocab == 0)
+    return pt_set_error(PT_ERR_INVALID_ARGUMENT, "model has no vocabulary");
+  if (!global && (track < 0 || track >= h->cfg.n_tracks || layer < 0 || layer >= h->cfg.n_layers))
+    return pt_set_error(PT_ERR_INVALID_ARGUMENT, "track %d / layer %d out of range", track, layer);
+  return PT_OK;
+}
+
+extern "C" int pt_set_weight(pt_handle* h, int32_t tensor, int32_t track, int32_t layer, const float* dev_src) {
+  if (!h || !dev_src) return pt_set_error(PT_ERR_NULL_POINTER, "handle or source is NULL");
+  int rc = check_tensor(h, tensor, track, layer);
+  if (rc) return rc;
+  rc = pt_launch_weight_copy(h, tensor, track, layer, const_cast<float*>(dev_src), true);
+  if (rc) return rc;
+  h->weights_ready = true;
+  return PT_OK;
+}
+
+extern "C" int pt_get_weight(pt_handle* h, int32_t tensor, int32_t track, int32_t layer, float* dev_dst) {
+  if (!h || !dev_dst) return pt_set_error(PT_ERR_NULL_POINTER, "handle or destination is NULL");
+  int rc = check_tensor(h, tensor, track, layer);
+  if (rc) return rc;
+  return pt_launch_weight_copy(h, tensor, track, layer, dev_dst, false);
+}
+
+extern "C" int pt_track_merge(const void* const* host_tracks, int32_t n, int64_t tokens, int32_t d,
+                              int32_t dtype, float scale, void* dev_out, void* hip_stream) {
+  if (!host_tracks || !dev_out) return pt_set_error(PT_ERR_NULL_POINTER, "tracks or out is NULL");
+  if (n < 1 || n > 16) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "n = %d, need 1..16", n);
+  if (tokens < 0 || d < 8 || d % 8) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "tokens must be >= 0 and d a positive multiple of 8");
+  if (dtype != PT_F32 && dtype != PT_BF16) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "dtype must be PT_F32 or PT_BF16");
+  for (int i = 0; i < n; ++i) {
+    if (!host_tracks[i]) return pt_set_error(PT_ERR_NULL_POINTER, "tracks[%d] is NULL", i);
+    if ((uintptr_t)host_tracks[i] & 15) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "tracks[%d] is not 16-byte aligned", i);
+  }
+  if ((uintptr_t)dev_out & 15) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "out is not 16-byte aligned");
+  if (tokens == 0) return PT_OK;
+  return pt_launch_merge(host_tracks, n, tokens * d, dtype, scale, dev_out, nullptr, (hipStream_t)hip_stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The forward pass.  rows = B*S rows per track; row m is sequence m / S at position pos0 + m % S.
+// ---------------------------------------------------------------------------------------------
+static int run_gemm(pt_handle* h, const pt_gemm_args& g) {
+  if (h->path == PT_PATH_AUTO) {
+    int r = pt_launch_gemm_mfma(g, h->stream);
+    if (r < 0) return r;
+    if (r == 1) return PT_OK;
+  }
+  return pt_launch_gemm_generic(g, h->stream);
+}
+
+static int run_attention(pt_handle* h, const pt_attn_args& a) {
+  if (h->path == PT_PATH_AUTO) {
+    int r = a.S == 1 ? pt_launch_attn_decode(a, h->stream) : pt_launch_attn_prefill_mfma(a, h->stream);
+    if (r < 0) return r;
+    if (r == 1) return PT_OK;
+  }
+  return pt_launch_attn_generic(a, h->stream);
+}
+
+static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hidden_in,
+                   int32_t hidden_tracks, int32_t B, int32_t S, int32_t pos0, int32_t logits_mode,
+                   float* dev_logits, float* dev_hidden_out, int32_t* dev_argmax) {
+  const pt_config& c = h->cfg;
+  const pt_layout& l = h->lay;
+  const int64_t T = c.n_tracks, L = c.n_layers, d = c.d_model, f = c.d_ffn;
+  const int64_t rows = (int64_t)B * S;
+  const int64_t es = l.elem_size;
+  hipStream_t st = h->stream;
+  int rc;
+
+  if (!h->rope_ready) {
+    rc = pt_launch_rope_table((float*)(h->ws + l.off_rope), c.max_seq, c.head_dim, c.rope_theta, st);
+    if (rc) return rc;
+    h->rope_ready = true;
+  }
+
+  float* hres = (float*)(h->ws + l.off_h);   // [T, rows, d]
+  float* hm = (float*)(h->ws + l.off_hm);    // [rows, d]
+  char* abuf = h->ws + l.off_a;
+  char* qbuf = h->ws + l.off_q;
+  char* obuf = h->ws + l.off_o;
+  char* mbuf = h->ws + l.off_m;
+  const float* gains = (const float*)(h->w + l.off_gains);
+
+  // Algorithm 1, first line: every track starts from the same embedding input x.  x is kept
+  // once; the first layer of a block reads it with a zero track stride.
+  const float* x;
+  int64_t x_bstride;
+  if (dev_hidden_in) {
+    x = dev_hidden_in;
+    x_bstride = hidden_tracks == 1 ? 0 : rows * d;
+  } else {
+    rc = pt_launch_embed(h->w + l.off_embed, c.dtype, dev_tokens, rows, (int32_t)d, c.vocab, hm, st);
+    if (rc) return rc;
+    x = hm;
+    x_bstride = 0;
+  }
+
+  const int64_t kv_head_k = (int64_t)c.max_seq * c.head_dim;
+  const int64_t kv_head_v = (int64_t)c.head_dim * l.s_pad;
+  int merge_idx = 0;
+  for (int64_t layer = 0; layer < L; ++layer) {
+    const bool first = (layer % c.block_depth) == 0;
+    const float* src = first ? x : hres;
+    const int64_t src_bstride = first ? x_bstride : rows * d;
+    const char* wl = h->w + l.off_layers + (size_t)(layer * l.layer_w_elems * es);
+    const int64_t w_bstride = L * l.layer_w_elems;
+
+    // attention half
+    rc = pt_launch_rmsnorm(src, src_bstride, gains + (layer * 2 + 0) * d, L * 2 * d, abuf, rows * d,
+                           c.dtype, (int32_t)T, rows, (int32_t)d, c.rms_eps, st);
+    if (rc) return rc;
+    pt_gemm_args g;
+    memset(&g, 0, sizeof(g));
+    g.A = abuf; g.a_bstride = rows * d; g.lda = (int32_t)d;
+    g.W = wl; g.w_bstride = w_bstride; g.ldb = (int32_t)d;
+    g.M = (int32_t)rows; g.N = (int32_t)l.n_qkv; g.K = (int32_t)d; g.batch = (int32_t)T;
+    g.dtype = c.dtype; g.epi = EPI_QKV;
+    g.olp = qbuf; g.olp_bstride = rows * l.hq;
+    g.kc = h->kv + l.off_k + (size_t)(layer * c.max_batch * c.n_kv_heads * kv_head_k * es);
+    g.vc = h->kv + l.off_v + (size_t)(layer * c.max_batch * c.n_kv_heads * kv_head_v * es);
+    g.rope = (const float*)(h->ws + l.off_rope);
+    g.H = c.n_heads; g.Hkv = c.n_kv_heads; g.hd = c.head_dim; g.S = S; g.pos0 = pos0;
+    g.s_pad = (int32_t)l.s_pad;
+    // cache strides are stated for K; the V^T side uses hd * s_pad per head with the same nesting
+    g.kv_bstride = L * c.max_batch * c.n_kv_heads;   // in heads; kernels scale by the head size
+    g.kv_seq_stride = c.n_kv_heads;                  // in heads
+    g.kv_head_elems = kv_head_k;
+    rc = run_gemm(h, g);
+    if (rc) return rc;
+
+    pt_attn_args a;
+    memset(&a, 0, sizeof(a));
+    a.q = qbuf; a.o = obuf; a.kc = g.kc; a.vc = g.vc;
+    a.q_bstride = rows * l.hq;
+    a.kv_bstride = g.kv_bstride; a.kv_seq_stride = g.kv_seq_stride; a.kv_head_elems = kv_head_k;
+    a.n_tracks = (int32_t)T; a.B = B; a.S = S; a.pos0 = pos0;
+    a.H = c.n_heads; a.Hkv = c.n_kv_heads; a.hd = c.head_dim; a.s_pad = (int32_t)l.s_pad;
+    a.dtype = c.dtype;
+    a.partials = (float*)(h->ws + l.off_part); a.max_splits = l.max_splits;
+    rc = run_attention(h, a);
+    if (rc) return rc;
+
+    memset(&g, 0, sizeof(g));
+    g.A = obuf; g.a_bstride = rows * l.hq; g.lda = (int32_t)l.hq;
+    g.W = wl + (size_t)(l.wqkv_elems * es); g.w_bstride = w_bstride; g.ldb = (int32_t)l.hq;
+    g.M = (int32_t)rows; g.N = (int32_t)d; g.K = (int32_t)l.hq; g.batch = (int32_t)T;
+    g.dtype = c.dtype; g.epi = EPI_RESIDUAL;
+    g.out = hres; g.out_bstride = rows * d; g.ldo = (int32_t)d;
+    g.res = src; g.res_bstride = src_bstride;
+    rc = run_gemm(h, g);
+    if (rc) return rc;
+
+    // feed-forward half
+    rc = pt_launch_rmsnorm(hres, rows * d, gains + (layer * 2 + 1) * d, L * 2 * d, abuf, rows * d,
+                           c.dtype, (int32_t)T, rows, (int32_t)d, c.rms_eps, st);
+    if (rc) return rc;
+    memset(&g, 0, sizeof(g));
+    g.A = abuf; g.a_bstride = rows * d; g.lda = (int32_t)d;
+    g.W = wl + (size_t)((l.wqkv_elems + l.wo_elems) * es); g.w_bstride = w_bstride; g.ldb = (int32_t)d;
+    g.M = (int32_t)rows; g.N = (int32_t)(2 * f); g.K = (int32_t)d; g.batch = (int32_t)T;
+    g.dtype = c.dtype; g.epi = EPI_SWIGLU;
+    g.olp = mbuf; g.olp_bstride = rows * f;
+    rc = run_gemm(h, g);
+    if (rc) return rc;
+    memset(&g, 0, sizeof(g));
+    g.A = mbuf; g.a_bstride = rows * f; g.lda = (int32_t)f;
+    g.W = wl + (size_t)((l.wqkv_elems + l.wo_elems + l.wgu_elems) * es); g.w_bstride = w_bstride; g.ldb = (int32_t)f;
+    g.M = (int32_t)rows; g.N = (int32_t)d; g.K = (int32_t)f; g.batch = (int32_t)T;
+    g.dtype = c.dtype; g.epi = EPI_RESIDUAL;
+    g.out = hres; g.out_bstride = rows * d; g.ldo = (int32_t)d;
+    g.res = hres; g.res_bstride = rows * d;
+    rc = run_gemm(h, g);
+    if (rc) return rc;
+
+    // Algorithm 1: after every D-th layer, all-reduce the track activations; every track
+    // continues from the reduced activation.
+    if ((layer + 1) % c.block_depth == 0) {
+      const void* tr[16];
+      for (int64_t t = 0; t < T; ++t) tr[t] = hres + t * rows * d;
+      if (h->track_taps) {
+        rc = pt_launch_copy_f32(hres, h->track_taps + (int64_t)merge_idx * T * rows * d, T * rows * d, st);
+        if (rc) return rc;
+      }
+      float* tap = h->taps ? h->taps + (int64_t)merge_idx * rows * d : nullptr;
+      rc = pt_launch_merge(tr, (int32_t)T, rows * d, PT_F32, c.merge_scale, hm, tap, st);
+      if (rc) return rc;
+      x = hm;
+      x_bstride = 0;
+      ++merge_idx;
+      ++h->merges;
+    }
+  }
+
+  if (dev_hidden_out) {
+    rc = pt_launch_copy_f32(hm, dev_hidden_out, rows * d, st);
+    if (rc) return rc;
+  }
+  if (logits_mode != PT_LOGITS_NONE && (dev_logits || dev_argmax)) {
+    const int64_t lrows = logits_mode == PT_LOGITS_ALL ? rows : B;
+    const float* gf = (const float*)(h->w + l.off_gf);
+    if (logits_mode == PT_LOGITS_ALL)
+      rc = pt_launch_rmsnorm_rows(hm, gf, abuf, c.dtype, lrows, 1, 0, (int32_t)d, c.rms_eps, st);
+    else
+      rc = pt_launch_rmsnorm_rows(hm, gf, abuf, c.dtype, lrows, S, S - 1, (int32_t)d, c.rms_eps, st);
+    if (rc) return rc;
+    float* lg = dev_logits;
+    if (!lg) return pt_set_error(PT_ERR_NULL_POINTER, "argmax needs a logits buffer");
+    pt_gemm_args g;
+    memset(&g, 0, sizeof(g));
+    g.A = abuf; g.a_bstride = 0; g.lda = (int32_t)d;
+    g.W = h->w + l.off_headT; g.w_bstride = 0; g.ldb = (int32_t)d;
+    g.M = (int32_t)lrows; g.N = c.vocab; g.K = (int32_t)d; g.batch = 1;
+    g.dtype = c.dtype; g.epi = EPI_STORE_F32;
+    g.out = lg; g.out_bstride = 0; g.ldo = c.vocab;
+    rc = run_gemm(h, g);
+    if (rc) return rc;
+    if (dev_argmax) {
+      rc = pt_launch_argmax(lg, (int32_t)lrows, c.vocab, dev_argmax, st);
+      if (rc) return rc;
+    }
+  }
+  return PT_OK;
+}
+
+static int check_inputs(pt_handle* h, const int32_t* dev_tokens, const float* dev_hidden_in,
+                        int32_t hidden_tracks) {
+  if (!h) return pt_set_error(PT_ERR_NULL_POINTER, "handle is NULL");
+  if (!h->weights_ready) return pt_set_error(PT_ERR_BAD_STATE, "weights have not been initialised");
+  if (!dev_tokens && !dev_hidden_in) return pt_set_error(PT_ERR_NULL_POINTER, "neither tokens nor hidden input given");
+  if (!dev_hidden_in && h->cfg.vocab == 0) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "model has no vocabulary: pass hidden states");
+  if (dev_hidden_in && hidden_tracks != 1 && hidden_tracks != h->cfg.n_tracks)
+    return pt_set_error(PT_ERR_INVALID_ARGUMENT, "hidden_tracks = %d, need 1 or n_tracks", hidden_tracks);
+  return PT_OK;
+}
+
+extern "C" int pt_prefill(pt_handle* h, const int32_t* dev_tokens, const float* dev_hidden_in,
+                          int32_t hidden_tracks, int32_t B, int32_t S, int32_t logits_mode,
+                          float* dev_logits, float* dev_hidden_out) {
+  if (!h) return pt_set_error(PT_ERR_NULL_POINTER, "handle is NULL");
+  if (B < 1 || S < 1) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "B and S must be >= 1");
+  if (B > h->cfg.max_batch) return pt_set_error(PT_ERR_CAPACITY, "B = %d exceeds max_batch = %d", B, h->cfg.max_batch);
+  if (S > h->cfg.max_seq) return pt_set_error(PT_ERR_CAPACITY, "S = %d exceeds max_seq = %d", S, h->cfg.max_seq);
+  if (logits_mode < PT_LOGITS_NONE || logits_mode > PT_LOGITS_ALL) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "bad logits_mode");
+  if (logits_mode != PT_LOGITS_NONE) {
+    if (h->cfg.vocab == 0) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "model has no vocabulary: no logits");
+    if (!dev_logits) return pt_set_error(PT_ERR_NULL_POINTER, "logits requested but dev_logits is NULL");
+  }
+  int rc = check_inputs(h, dev_tokens, dev_hidden_in, hidden_tracks);
+  if (rc) return rc;
+  rc = forward(h, dev_tokens, dev_hidden_in, hidden_tracks, B, S, 0, logits_mode, dev_logits, dev_hidden_out, nullptr);
+  if (rc) return rc;
+  h->batch = B;
+  h->seq_len = S;
+  return PT_OK;
+}
+
+extern "C" int pt_decode_step(pt_handle* h, const int32_t* dev_tokens, const float* dev_hidden_in,
+                              int32_t hidden_tracks, int32_t B, float* dev_logits,
+                              float* dev_hidden_out, int32_t* dev_argmax) {
+  int rc = check_inputs(h, dev_tokens, dev_hidden_in, hidden_tracks);
+  if (rc) return rc;
+  if (h->batch == 0) return pt_set_error(PT_ERR_BAD_STATE, "decode before prefill");
+  if (B != h->batch) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "B = %d differs from the prefilled batch %d", B, h->batch);
+  if (h->seq_len + 1 > h->cfg.max_seq) return pt_set_error(PT_ERR_CAPACITY, "sequence length %d + 1 exceeds max_seq = %d", h->seq_len, h->cfg.max_seq);
+  if ((dev_logits || dev_argmax) && h->cfg.vocab == 0) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "model has no vocabulary: no logits");
+  if (dev_argmax && !dev_logits) return pt_set_error(PT_ERR_NULL_POINTER, "argmax needs a logits buffer");
+  rc = forward(h, dev_tokens, dev_hidden_in, hidden_tracks, B, 1, h->seq_len,
+               dev_logits ? PT_LOGITS_LAST : PT_LOGITS_NONE, dev_logits, dev_hidden_out, dev_argmax);
+  if (rc) return rc;
+  h->seq_len += 1;
+  return PT_OK;
+}

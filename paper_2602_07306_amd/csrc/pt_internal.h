@@ -1,0 +1,172 @@
+// Internal declarations shared by the host-side API and the HIP kernels of libpt.
+#ifndef PT_INTERNAL_H_
+#define PT_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "pt.h"
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits
+
+// ---------------------------------------------------------------------------------------------
+// Physical storage (chosen for gfx950; the logical "x @ W" layouts are in pt.h).
+//
+// Every GEMM weight is stored transposed, [N, K] with K contiguous, so that both MFMA operands
+// are read along the contraction dimension:
+//   wqkv [(H + 2*Hkv)*hd, d]   rows: all q columns, then all k columns, then all v columns
+//   wo   [d, H*hd]
+//   wgu  [2f, d]               gate and up interleaved in blocks of 32 rows:
+//                              row (j/32)*64 + j%32 = gate_j, row (j/32)*64 + 32 + j%32 = up_j,
+//                              so a 32-column MFMA tile of gate sits next to the same tile of up
+//   wd   [d, f]
+//   embed [V, d], headT [V, d]
+// KV cache, per (track, layer, sequence, kv head):
+//   K  [max_seq, hd]   (hd contiguous: the contraction dimension of q.k)
+//   Vt [hd, s_pad]     (positions contiguous: the contraction dimension of p.v), row pitch s_pad
+//                      = max_seq rounded up to 64, plus 64 so that rows do not alias HBM channels.
+// ---------------------------------------------------------------------------------------------
+struct pt_layout {
+  // element counts
+  int64_t n_qkv;        // (H + 2*Hkv) * hd
+  int64_t hq;           // H * hd
+  int64_t hk;           // Hkv * hd
+  int64_t wqkv_elems, wo_elems, wgu_elems, wd_elems;  // per (track, layer)
+  int64_t layer_w_elems;                               // sum of the four
+  int64_t s_pad;                                       // Vt row pitch (elements)
+  // byte offsets inside the weight arena
+  size_t off_layers;    // [T][L] blocks of layer_w_elems elements
+  size_t off_gains;     // fp32 [T][L][2][d]
+  size_t off_gf;        // fp32 [d]
+  size_t off_embed;     // dtype [V, d]
+  size_t off_headT;     // dtype [V, d]
+  size_t weight_bytes;
+  // KV arena
+  int64_t kv_seq_elems;  // per (t, l, b, hkv): max_seq*hd (K) ; hd*s_pad (Vt)
+  size_t off_k, off_v, kv_bytes;
+  // workspace arena (M = max_batch * max_seq rows)
+  size_t off_h;       // fp32 [T, M, d] residual streams
+  size_t off_hm;      // fp32 [M, d]    merged activation
+  size_t off_a;       // dtype [T, M, d] normed activations
+  size_t off_q;       // dtype [T, M, hq]
+  size_t off_o;       // dtype [T, M, hq] attention output
+  size_t off_m;       // dtype [T, M, f]  SwiGLU product
+  size_t off_rope;    // fp32 [max_seq, hd/2, 2] cos, sin
+  size_t off_part;    // fp32 split-K decode partials
+  size_t off_last;    // dtype [max_batch, d] normed last rows for the head
+  size_t ws_bytes;
+  int32_t elem_size;  // 4 or 2
+  int32_t max_splits;
+};
+
+struct pt_handle {
+  pt_config cfg;
+  pt_layout lay;
+  char* w;
+  char* kv;
+  char* ws;
+  hipStream_t stream;
+  int32_t batch;      // B of the live sequences (0: none)
+  int32_t seq_len;    // their common length
+  int64_t merges;
+  bool weights_ready;
+  bool rope_ready;
+  float* taps;
+  float* track_taps;
+  int32_t path;
+};
+
+int pt_set_error(int code, const char* fmt, ...);
+int pt_validate_config(const pt_config* c);
+int pt_compute_layout(const pt_config* c, pt_layout* l);
+
+// ---------------------------------------------------------------------------------------------
+// GEMM: C[b] (M x N) = A[b] (M x K, row-major, lda) * W[b]^T, W[b] is [N, K] row-major (ldb),
+// for b < batch (the track dimension), followed by one of the fused epilogues.
+// ---------------------------------------------------------------------------------------------
+enum { EPI_STORE_F32 = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2, EPI_QKV = 3 };
+
+struct pt_gemm_args {
+  const void* A;
+  const void* W;
+  int64_t a_bstride, w_bstride;  // elements between tracks
+  int32_t lda, ldb;
+  int32_t M, N, K, batch;
+  int32_t dtype;                 // operand type
+  int32_t epi;
+  // EPI_STORE_F32: out[b][m][n] = acc                       (out_bstride, ldo)
+  // EPI_RESIDUAL : out[b][m][n] = res[b][m][n] + acc         (res may alias out; res_bstride may be 0)
+  float* out;
+  const float* res;
+  int64_t out_bstride, res_bstride;
+  int32_t ldo;
+  // EPI_SWIGLU   : olp[b][m][j] = silu(gate_j) * up_j, N = 2f in the interleaved order, ld = N/2
+  void* olp;
+  int64_t olp_bstride;
+  // EPI_QKV      : RoPE on q and k columns; q -> olp [b][m][hq]; k, v -> the KV cache.
+  //                Row m is token (m / S) at position pos0 + m % S.
+  void* kc;
+  void* vc;
+  const float* rope;             // [max_seq][hd/2][2]
+  // cache head index = track * kv_bstride + sequence * kv_seq_stride + kv head; a head holds
+  // kv_head_elems = max_seq * hd elements of K and hd * s_pad elements of V^T
+  int64_t kv_bstride, kv_seq_stride, kv_head_elems;
+  int32_t H, Hkv, hd, S, pos0, s_pad;
+};
+
+int pt_launch_gemm_generic(const pt_gemm_args& g, hipStream_t s);
+// Returns 1 if the MFMA kernel family supports this problem (then it has been launched), 0 if not.
+int pt_launch_gemm_mfma(const pt_gemm_args& g, hipStream_t s);
+
+// ---------------------------------------------------------------------------------------------
+// Attention over the KV cache.  q/o: [batch_t][rows][H*hd]; row m is sequence m / S at position
+// pos0 + m % S and sees cache positions <= its own.
+// ---------------------------------------------------------------------------------------------
+struct pt_attn_args {
+  const void* q;
+  void* o;
+  const void* kc;
+  const void* vc;
+  int64_t q_bstride;             // elements between tracks in q / o
+  int64_t kv_bstride, kv_seq_stride, kv_head_elems;
+  int32_t n_tracks, B, S, pos0;
+  int32_t H, Hkv, hd, s_pad;
+  int32_t dtype;
+  float* partials;               // split-K workspace (decode)
+  int32_t max_splits;
+};
+
+int pt_launch_attn_generic(const pt_attn_args& a, hipStream_t s);
+int pt_launch_attn_prefill_mfma(const pt_attn_args& a, hipStream_t s);  // 1 if handled
+int pt_launch_attn_decode(const pt_attn_args& a, hipStream_t s);        // 1 if handled
+
+// ---------------------------------------------------------------------------------------------
+// Elementwise / bandwidth-bound kernels.
+// ---------------------------------------------------------------------------------------------
+int pt_launch_embed(const void* embed, int32_t dtype, const int32_t* tokens, int64_t rows, int32_t d,
+                    int32_t vocab, float* h, hipStream_t s);
+int pt_launch_rmsnorm(const float* h, int64_t h_bstride, const float* gains, int64_t g_bstride,
+                      void* out, int64_t out_bstride, int32_t dtype, int32_t batch, int64_t rows,
+                      int32_t d, float eps, hipStream_t s);
+// rows selected by index: out[r] = norm(h[row_index(r)]), row_index(r) = r * row_step + row_off
+int pt_launch_rmsnorm_rows(const float* h, const float* gain, void* out, int32_t dtype, int64_t rows,
+                           int64_t row_step, int64_t row_off, int32_t d, float eps, hipStream_t s);
+int pt_launch_merge(const void* const* tracks, int32_t n, int64_t elems, int32_t dtype, float scale,
+                    void* out, float* tap, hipStream_t s);
+int pt_launch_copy_f32(const float* src, float* dst, int64_t elems, hipStream_t s);
+int pt_launch_argmax(const float* logits, int32_t rows, int32_t vocab, int32_t* out, hipStream_t s);
+int pt_launch_rope_table(float* table, int32_t max_seq, int32_t hd, float theta, hipStream_t s);
+int pt_launch_fill_f32(float* dst, int64_t n, float v, hipStream_t s);
+// weight access: tensor ids are PT_W_*; phys points at the tensor's physical base
+int pt_launch_weight_init(pt_handle* h, uint64_t seed);
+int pt_launch_weight_copy(pt_handle* h, int32_t tensor, int32_t track, int32_t layer, float* logical,
+                          bool to_device_storage);
+
+#define PT_HIP_CHECK(expr)                                                             \
+  do {                                                                                 \
+    hipError_t e_ = (expr);                                                            \
+    if (e_ != hipSuccess) return pt_set_error(PT_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+#endif  // PT_INTERNAL_H_
