@@ -1,2 +1,209 @@
+// Split-K decode attention over the contiguous KV cache (bf16 cache, fp32 arithmetic).
+//
+// One query row per (track, sequence, head).  The work is HBM-bound: every key and value element is
+// read exactly once with 16-byte loads.  A workgroup owns one key range ("split") of one head:
+//   phase 1  scores: a key row (hd contiguous) is covered by hd/8 lanes, 8 elements each; the partial
+//            dot products are folded with cross-lane exchanges and the score goes to LDS;
+//   phase 2  exact softmax numerators over the range (max, then exp2, then sum) in LDS;
+//   phase 3  values: the cache holds V transposed (positions contiguous), so a lane reads 8
+//            consecutive positions of one hd-row per load and multiplies them with 8 probabilities
+//            from LDS; each wavefront owns hd/4 rows and reduces across lanes once at the end.
+// With more than one split each workgroup writes (max, sum, unnormalised output) and a small kernel
+// combines the splits; with one split the normalised output is written directly.
 #include "pt_device.h"
-int pt_launch_attn_decode(const pt_attn_args& a, hipStream_t s) { (void)a; (void)s; return 0; }
+
+#define DEC_CHUNK 512          // positions one wavefront covers per step of phase 3 (64 lanes x 8)
+#define DEC_MAX_KEYS 8192      // positions per split (32 KB of scores in LDS)
+
+template <int HD>
+__global__ void __launch_bounds__(256) attn_decode_kernel(const pt_attn_args a, int nsplit, int keys_per_split) {
+  constexpr int LPK = HD / 8;       // lanes per key row
+  constexpr int KPI = 64 / LPK;     // key rows per wavefront load
+  constexpr int RPW = HD / 4;       // V^T rows per wavefront
+  extern __shared__ __attribute__((aligned(16))) float sc[];
+  __shared__ float red[8];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int split = blockIdx.x, head = blockIdx.y;
+  const int t = blockIdx.z / a.B, seq = blockIdx.z - t * a.B;
+  const int nkeys = a.pos0 + 1;
+  const int k0 = split * keys_per_split;
+  const int k1 = min(nkeys, k0 + keys_per_split);
+  const int n = k1 - k0;
+  const int kvh = head / (a.H / a.Hkv);
+  const int64_t hidx = t * a.kv_bstride + seq * a.kv_seq_stride + kvh;
+  const bf16_t* K = (const bf16_t*)a.kc + hidx * a.kv_head_elems;
+  const bf16_t* Vt = (const bf16_t*)a.vc + hidx * ((int64_t)HD * a.s_pad);
+  const int64_t qoff = t * a.q_bstride + (int64_t)seq * (a.H * HD) + head * HD;
+  float* part = a.partials + (((int64_t)blockIdx.z * a.H + head) * nsplit + split) * (HD + 2);
+
+  if (n <= 0) {   // empty trailing split: neutral element of the combine
+    if (tid == 0) { part[0] = -INFINITY; part[1] = 0.f; }
+    for (int e = tid; e < HD; e += 256) part[2 + e] = 0.f;
+    return;
+  }
+
+  // ---- phase 1: scores (already in log2 units)
+  const int sub = lane % LPK, kslot = lane / LPK;
+  float qf[8];
+  {
+    const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
+    const uint4 qv = *(const uint4*)((const bf16_t*)a.q + qoff + sub * 8);
+    const uint32_t w[4] = {qv.x, qv.y, qv.z, qv.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      qf[2 * i] = __uint_as_float(w[i] << 16) * scale_log2;
+      qf[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u) * scale_log2;
+    }
+  }
+  float mx = -INFINITY;
+  // key rows of this lane group, relative to k0: kfirst, kfirst + kstep, ... (4 in flight per step)
+  const int kfirst = wave * KPI + kslot, kstep = 4 * KPI;
+  const bf16_t* kp = K + (int64_t)k0 * HD + sub * 8;
+  for (int kb = kfirst; kb < n; kb += 4 * kstep) {
+    uint4 kv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (kb + u * kstep < n) kv[u] = *(const uint4*)(kp + (int64_t)(kb + u * kstep) * HD);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const bool valid = kb + u * kstep < n;
+      float dot = 0.f;
+      if (valid) {
+        const uint32_t w[4] = {kv[u].x, kv[u].y, kv[u].z, kv[u].w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          dot = fmaf(qf[2 * i], __uint_as_float(w[i] << 16), dot);
+          dot = fmaf(qf[2 * i + 1], __uint_as_float(w[i] & 0xffff0000u), dot);
+        }
+      }
+      // the LPK lanes of a key row share kb, so they are active together
+#pragma unroll
+      for (int o = 1; o < LPK; o <<= 1) dot += __shfl_xor(dot, o, 64);
+      if (valid) {
+        if (sub == 0) sc[kb + u * kstep] = dot;
+        mx = fmaxf(mx, dot);
+      }
+    }
+  }
+  mx = wave_max(mx);
+  if (lane == 0) red[wave] = mx;
+  __syncthreads();
+  const float M = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+
+  // ---- phase 2: numerators and their sum; zero the tail up to the next chunk border
+  const int npad = (n + DEC_CHUNK - 1) / DEC_CHUNK * DEC_CHUNK;
+  float ps = 0.f;
+  for (int i = tid; i < npad; i += 256) {
+    float p = 0.f;
+    if (i < n) {
+      p = __builtin_amdgcn_exp2f(sc[i] - M);
+      ps += p;
+    }
+    sc[i] = p;
+  }
+  ps = wave_sum(ps);
+  if (lane == 0) red[4 + wave] = ps;
+  __syncthreads();
+  const float Lsum = red[4] + red[5] + red[6] + red[7];
+
+  // ---- phase 3: values
+  float acc[RPW];
+#pragma unroll
+  for (int r = 0; r < RPW; ++r) acc[r] = 0.f;
+  const bf16_t* vbase = Vt + (int64_t)(wave * RPW) * a.s_pad + k0;
+  for (int c = lane * 8; c < n; c += DEC_CHUNK) {
+    const float4 p0 = *(const float4*)(sc + c), p1 = *(const float4*)(sc + c + 4);
+    const float p[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+    const bool tail = c + 8 > n;   // some of the 8 positions lie beyond the range: their cache bytes are not data
+#pragma unroll
+    for (int r0 = 0; r0 < RPW; r0 += 16) {
+      uint4 vv[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) vv[r] = *(const uint4*)(vbase + (int64_t)(r0 + r) * a.s_pad + c);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const uint32_t w[4] = {vv[r].x, vv[r].y, vv[r].z, vv[r].w};
+        float s = acc[r0 + r];
+        if (!tail) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            s = fmaf(p[2 * i], __uint_as_float(w[i] << 16), s);
+            s = fmaf(p[2 * i + 1], __uint_as_float(w[i] & 0xffff0000u), s);
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            if (c + 2 * i < n) s = fmaf(p[2 * i], __uint_as_float(w[i] << 16), s);
+            if (c + 2 * i + 1 < n) s = fmaf(p[2 * i + 1], __uint_as_float(w[i] & 0xffff0000u), s);
+          }
+        }
+        acc[r0 + r] = s;
+      }
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < RPW; ++r) acc[r] = wave_sum(acc[r]);
+
+  if (nsplit == 1) {
+    const float inv = 1.0f / Lsum;
+    bf16_t* o = (bf16_t*)a.o + qoff + wave * RPW;
+#pragma unroll
+    for (int r = 0; r < RPW; ++r)
+      if (lane == (r & 63)) o[r] = f32_to_bf16(acc[r] * inv);
+  } else {
+    if (tid == 0) { part[0] = M; part[1] = Lsum; }
+#pragma unroll
+    for (int r = 0; r < RPW; ++r)
+      if (lane == (r & 63)) part[2 + wave * RPW + r] = acc[r];
+  }
+}
+
+// Combines the splits of one (track, sequence, head): o = sum_s o_s 2^(m_s - M) / sum_s l_s 2^(m_s - M).
+__global__ void __launch_bounds__(64) attn_decode_combine_kernel(const pt_attn_args a, int nsplit) {
+  const int head = blockIdx.x;
+  const int t = blockIdx.y / a.B, seq = blockIdx.y - t * a.B;
+  const int hd = a.hd;
+  const float* part = a.partials + ((int64_t)blockIdx.y * a.H + head) * nsplit * (hd + 2);
+  float M = -INFINITY;
+  for (int s = 0; s < nsplit; ++s) M = fmaxf(M, part[s * (hd + 2)]);
+  float L = 0.f;
+  for (int s = 0; s < nsplit; ++s) L += part[s * (hd + 2) + 1] * __builtin_amdgcn_exp2f(part[s * (hd + 2)] - M);
+  const float inv = 1.0f / L;
+  bf16_t* o = (bf16_t*)a.o + t * a.q_bstride + (int64_t)seq * (a.H * hd) + head * hd;
+  for (int e = threadIdx.x; e < hd; e += 64) {
+    float acc = 0.f;
+    for (int s = 0; s < nsplit; ++s)
+      acc += part[s * (hd + 2) + 2 + e] * __builtin_amdgcn_exp2f(part[s * (hd + 2)] - M);
+    o[e] = f32_to_bf16(acc * inv);
+  }
+}
+
+int pt_launch_attn_decode(const pt_attn_args& a, hipStream_t s) {
+  if (a.dtype != PT_BF16 || a.S != 1) return 0;
+  if (a.hd != 64 && a.hd != 128) return 0;
+  if ((a.q_bstride & 7) || (((uintptr_t)a.q | (uintptr_t)a.kc | (uintptr_t)a.vc) & 15)) return 0;
+  const int64_t z = (int64_t)a.n_tracks * a.B;
+  if (z > 65535 || a.H > 65535) return 0;
+  const int nkeys = a.pos0 + 1;
+  const int64_t base = z * a.H;
+  int nsplit = (int)((1024 + base - 1) / base);
+  const int by_len = (nkeys + DEC_CHUNK - 1) / DEC_CHUNK;
+  if (nsplit > by_len) nsplit = by_len;
+  const int need = (nkeys + DEC_MAX_KEYS - 1) / DEC_MAX_KEYS;
+  if (nsplit < need) nsplit = need;
+  if (nsplit < 1) nsplit = 1;
+  if (nsplit > a.max_splits) return 0;
+  int kps = (nkeys + nsplit - 1) / nsplit;
+  kps = (kps + DEC_CHUNK - 1) / DEC_CHUNK * DEC_CHUNK;
+  if (kps > DEC_MAX_KEYS) return 0;
+  const size_t lds = (size_t)kps * sizeof(float);
+  dim3 grid((unsigned)nsplit, (unsigned)a.H, (unsigned)z);
+  if (a.hd == 64)
+    hipLaunchKernelGGL(attn_decode_kernel<64>, grid, dim3(256), lds, s, a, nsplit, kps);
+  else
+    hipLaunchKernelGGL(attn_decode_kernel<128>, grid, dim3(256), lds, s, a, nsplit, kps);
+  if (nsplit > 1)
+    hipLaunchKernelGGL(attn_decode_combine_kernel, dim3((unsigned)a.H, (unsigned)z), dim3(64), 0, s, a, nsplit);
+  PT_HIP_CHECK(hipGetLastError());
+  return 1;
+}
