@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""Benchmark of the PT forward hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--skip-decode] [--skip-cpu]
+
+A step is one whole prefill pass (embedding, L layers of T tracks with a merge every D layers,
+final norm and head on the last positions) over one batch of the "Mid PT prefill" workload:
+T=4 tracks, 16 layers/track, merge every 4 layers, d_model 1024, 16 heads x 64, FFN 4096,
+vocab 32000, bf16, batch 4 x 1024 uniform-random tokens (seed 1), weights N(0, 0.02) (seed 1).
+Inputs are resident in HBM before the timed region.  One JSON line is printed on stdout:
+
+  value      prefill tokens/s (whole job, one GPU)
+  roofline   the dominant kernel (gate/up GEMM with the SwiGLU epilogue): algorithmic FLOPs of one
+             launch / its mean duration, measured with HIP events around exactly those launches
+             inside the timed region, against the dense bf16 MFMA peak
+  decode     the "Mid PT decode" workload (same model, batch 32, 2048-token prompts, 128 KV-cached
+             steps): ms per step and the decode-attention kernel's KV bytes / duration against HBM peak
+  cpu_baseline  the CPU oracle (numpy float64) timed on one of the four sequences of the same
+             prefill workload on this host's cores
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def prefill_flops(cfg, B, S, head_rows):
+    """Algorithmic FLOPs of one prefill: GEMMs, causal attention at half the dense S^2 work,
+    and the head on head_rows rows."""
+    T, L, d, f = cfg.n_tracks, cfg.n_layers, cfg.d_model, cfg.d_ffn
+    hq, hk = cfg.n_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
+    rows = B * S
+    per_class = {
+        "gemm_qkv": 2.0 * rows * d * (hq + 2 * hk) * T,
+        "gemm_out": 2.0 * rows * hq * d * T,
+        "gemm_gateup": 2.0 * rows * d * 2 * f * T,
+        "gemm_down": 2.0 * rows * f * d * T,
+        "attn_prefill": 2.0 * S * S * hq * B * T,
+    }
+    total = L * sum(per_class.values()) + 2.0 * head_rows * d * cfg.vocab
+    return total, per_class
+
+
+def decode_bytes(cfg, B, ctx):
+    """Algorithmic HBM bytes of one decode step: every weight once, the KV cache once."""
+    T, L, d, f = cfg.n_tracks, cfg.n_layers, cfg.d_model, cfg.d_ffn
+    hq, hk = cfg.n_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
+    weights = T * L * (d * (hq + 2 * hk) + hq * d + 3 * d * f) * 2.0
+    kv_per_launch = T * B * ctx * 2 * hk * 2.0
+    return weights, kv_per_launch * L, kv_per_launch
+
+
+def run_prefill(args, torch, PB, I):
+    cfg = I.config_mid(max_batch=4, max_seq=1024)
+    B, S = 4, 1024
+    model = PB.PTModel(cfg)
+    model.pt_init_weights(1)
+    tokens = torch.from_numpy(I.make_tokens(1, B, S, cfg.vocab)).cuda()
+    logits = torch.empty((B, cfg.vocab), dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    for _ in range(args.warmup):
+        model.pt_prefill(tokens, logits_mode=PB.PT_LOGITS_LAST, logits_out=logits)
+    torch.cuda.synchronize()
+    model.pt_profile_reset()
+    model.pt_profile_enable(["gemm_gateup"])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        model.pt_prefill(tokens, logits_mode=PB.PT_LOGITS_LAST, logits_out=logits)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_dom, n_dom = model.pt_profile_read("gemm_gateup")
+    total_flops, per_class = prefill_flops(cfg, B, S, B)
+    ms_step = dt / args.steps * 1e3
+    achieved = per_class["gemm_gateup"] / (ms_dom / n_dom * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "gemm_mfma_kernel<..., EPI_SWIGLU> (gate/up GEMM)",
+                "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                "launches": n_dom, "avg_launch_ms": ms_dom / n_dom,
+                "flops_per_launch": per_class["gemm_gateup"]}
+    # per-class breakdown on two extra, untimed steps
+    model.pt_profile_reset()
+    classes = ["embed", "rmsnorm", "gemm_qkv", "attn_prefill", "gemm_out", "gemm_gateup", "gemm_down",
+               "merge", "gemm_head"]
+    model.pt_profile_enable(classes)
+    for _ in range(2):
+        model.pt_prefill(tokens, logits_mode=PB.PT_LOGITS_LAST, logits_out=logits)
+    breakdown = {}
+    for c in classes:
+        ms, n = model.pt_profile_read(c)
+        if n:
+            e = {"ms_per_step": ms / 2, "launches_per_step": n // 2}
+            if c in per_class:
+                e["tflops"] = per_class[c] / (ms / n * 1e-3) / 1e12
+            breakdown[c] = e
+    model.pt_profile_enable([])
+    model.close()
+    del model
+    torch.cuda.empty_cache()
+    return {"cfg": cfg, "B": B, "S": S, "ms_step": ms_step, "tokens_per_s": B * S / (ms_step * 1e-3),
+            "total_flops": total_flops, "roofline": roofline, "breakdown": breakdown}
+
+
+def run_decode(args, torch, PB, I):
+    B, prompt, steps = 32, 2048, 128
+    cfg = I.config_mid(max_batch=B, max_seq=prompt + steps + 64)
+    model = PB.PTModel(cfg)
+    model.pt_init_weights(1)
+    tokens = torch.from_numpy(I.make_tokens(2, B, prompt, cfg.vocab)).cuda()
+    logits = torch.empty((B, cfg.vocab), dtype=torch.float32, device="cuda")
+    nxt = torch.empty((B,), dtype=torch.int32, device="cuda")
+    t0 = time.perf_counter()
+    model.pt_prefill(tokens, logits_mode=PB.PT_LOGITS_LAST, logits_out=logits)
+    nxt.copy_(logits.argmax(dim=-1).to(torch.int32))
+    torch.cuda.synchronize()
+    prefill_s = time.perf_counter() - t0
+    model.pt_profile_reset()
+    model.pt_profile_enable(["attn_decode"])
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    ev[0].record()
+    for i in range(steps):
+        model.pt_decode_step(nxt, logits_out=logits, argmax_out=nxt, want_argmax=True)
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    per = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(steps))
+    ms_attn, n_attn = model.pt_profile_read("attn_decode")
+    wbytes, kv_step, kv_launch = decode_bytes(cfg, B, prompt + steps // 2)
+    gbs = kv_launch / (ms_attn / n_attn * 1e-3) / 1e9
+    med = per[len(per) // 2]
+    out = {"workload": "Mid PT decode: batch 32, 2048-token prompts, 128 KV-cached steps",
+           "ms_per_step_median": med, "ms_per_step_min": per[0], "ms_per_token": med / B,
+           "prompt_prefill_s": prefill_s,
+           "step_bytes_GB": (wbytes + kv_step) / 1e9, "step_GBs": (wbytes + kv_step) / (med * 1e-3) / 1e9,
+           "step_frac_of_hbm_peak": (wbytes + kv_step) / (med * 1e-3) / 1e9 / HBM_PEAK_GBS,
+           "roofline": {"bound": "hbm", "kernel": "attn_decode_kernel<64>", "achieved": gbs,
+                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                        "launches": n_attn, "avg_launch_ms": ms_attn / n_attn,
+                        "bytes_per_launch": kv_launch}}
+    model.close()
+    del model
+    torch.cuda.empty_cache()
+    return out
+
+
+def run_cpu_baseline(I):
+    """The oracle, as it stands, on sequence 0 of the prefill workload (sequences are independent)."""
+    import numpy as np
+    from oracle import pt_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    cfg = I.config_mid(max_batch=1, max_seq=1024)
+    t0 = time.perf_counter()
+    W = I.make_weights(cfg, 1)
+    log("cpu_baseline: weights generated in %.1f s" % (time.perf_counter() - t0))
+    tokens = I.make_tokens(1, 4, 1024, cfg.vocab)[:1]
+    st = O.PTState(cfg, 1, 1024)
+    t0 = time.perf_counter()
+    O.pt_prefill(cfg, W, st, tokens=tokens)
+    dt = time.perf_counter() - t0
+    return {"value": 1024 / dt, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": "sequence 0 of the 4 x 1024-token batch (1024 tokens, full model), %.1f s" % dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--skip-decode", action="store_true")
+    ap.add_argument("--skip-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs the PT forward on ONE GPU (all tracks resident); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2602_07306_amd import binding as PB
+    from paper_2602_07306_amd import inputs as I
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    PB.lib()
+    pre = run_prefill(args, torch, PB, I)
+    log("prefill: %.3f ms/step, %.0f tokens/s, %.1f%% of bf16 MFMA peak end to end" % (
+        pre["ms_step"], pre["tokens_per_s"],
+        100 * pre["total_flops"] / (pre["ms_step"] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS))
+    dec = None if args.skip_decode else run_decode(args, torch, PB, I)
+    if dec:
+        log("decode: %.3f ms/step median, attention %.0f GB/s" % (dec["ms_per_step_median"], dec["roofline"]["achieved"]))
+    cpu = None if args.skip_cpu else run_cpu_baseline(I)
+    cfg = pre["cfg"]
+    e2e_tflops = pre["total_flops"] / (pre["ms_step"] * 1e-3) / 1e12
+    out = {
+        "metric": "PT prefill tokens/s", "value": pre["tokens_per_s"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": pre["ms_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "Mid PT prefill: T=4 tracks, 16 layers/track, merge every 4 layers, d_model 1024, "
+                               "16 heads x 64, FFN 4096, vocab 32000, batch 4 x 1024 tokens, seed 1",
+                   "n_tracks": cfg.n_tracks, "n_layers": cfg.n_layers, "block_depth": cfg.block_depth,
+                   "batch": pre["B"], "seq_len": pre["S"]},
+        "end_to_end": {"algorithmic_TFLOP": pre["total_flops"] / 1e12, "TFLOP/s": e2e_tflops,
+                       "frac_of_mfma_peak": e2e_tflops / MFMA_BF16_PEAK_TFLOPS},
+        "roofline": pre["roofline"],
+        "kernel_breakdown": pre["breakdown"],
+        "decode": dec,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

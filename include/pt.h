@@ -158,6 +158,21 @@ int64_t pt_merge_count(const pt_handle* h);
 /* Current sequence length (identical for all sequences of the batch), or a negative error. */
 int32_t pt_seq_len(const pt_handle* h);
 
+/* Per-kernel timing with HIP events on the handle's stream.  Kernel classes: */
+enum {
+  PT_K_EMBED = 0, PT_K_RMSNORM = 1, PT_K_GEMM_QKV = 2, PT_K_ATTN_PREFILL = 3, PT_K_ATTN_DECODE = 4,
+  PT_K_GEMM_OUT = 5, PT_K_GEMM_GATEUP = 6, PT_K_GEMM_DOWN = 7, PT_K_MERGE = 8, PT_K_GEMM_HEAD = 9,
+  PT_K_OTHER = 10, PT_K_COUNT = 11
+};
+/* class_mask: bit k set = bracket every launch of class k in later forward calls with a pair of
+ * events (0 switches timing off).  Each bracketed launch costs two event records on the stream. */
+int pt_profile_enable(pt_handle* h, uint32_t class_mask);
+/* Synchronises the stream, folds all finished event pairs into the totals and returns, for one
+ * class, the summed kernel time in milliseconds and the number of launches since the last
+ * pt_profile_reset.  Either out pointer may be NULL. */
+int pt_profile_read(pt_handle* h, int32_t kernel_class, double* total_ms, int64_t* launches);
+int pt_profile_reset(pt_handle* h);
+
 const char* pt_last_error(void);
 
 #ifdef __cplusplus

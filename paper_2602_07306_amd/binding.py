@@ -30,8 +30,12 @@ PT_ERR_BAD_STATE, PT_ERR_HIP, PT_ERR_INVALID_ARGUMENT = -5, -6, -7
 EXPORTS = [
     "pt_query_bytes", "pt_create", "pt_destroy", "pt_init_weights", "pt_set_weight", "pt_get_weight",
     "pt_prefill", "pt_decode_step", "pt_track_merge", "pt_set_taps", "pt_set_kernel_path", "pt_reset",
-    "pt_merge_count", "pt_seq_len", "pt_last_error",
+    "pt_merge_count", "pt_seq_len", "pt_last_error", "pt_profile_enable", "pt_profile_read",
+    "pt_profile_reset",
 ]
+
+KERNEL_CLASSES = ["embed", "rmsnorm", "gemm_qkv", "attn_prefill", "attn_decode", "gemm_out",
+                  "gemm_gateup", "gemm_down", "merge", "gemm_head", "other"]
 
 
 class pt_config(C.Structure):
@@ -77,6 +81,9 @@ def lib() -> C.CDLL:
     L.pt_merge_count.restype = i64
     L.pt_seq_len.argtypes = [vp]
     L.pt_seq_len.restype = i32
+    L.pt_profile_enable.argtypes = [vp, C.c_uint32]
+    L.pt_profile_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(i64)]
+    L.pt_profile_reset.argtypes = [vp]
     L.pt_last_error.argtypes = []
     L.pt_last_error.restype = C.c_char_p
     for name in EXPORTS:
@@ -244,6 +251,22 @@ class PTModel:
         _check(lib().pt_decode_step(self.h, _ptr(tokens), _ptr(hidden_in), ht, B, _ptr(logits),
                                     _ptr(hidden), _ptr(amax)))
         return logits, hidden, amax
+
+    def pt_profile_enable(self, classes):
+        """classes: iterable of kernel-class names (KERNEL_CLASSES) to time; empty = off."""
+        mask = 0
+        for c in classes:
+            mask |= 1 << KERNEL_CLASSES.index(c)
+        _check(lib().pt_profile_enable(self.h, mask))
+
+    def pt_profile_read(self, cls: str):
+        """(total milliseconds, launches) of one kernel class since the last reset."""
+        ms, n = C.c_double(), C.c_int64()
+        _check(lib().pt_profile_read(self.h, KERNEL_CLASSES.index(cls), C.byref(ms), C.byref(n)))
+        return ms.value, n.value
+
+    def pt_profile_reset(self):
+        _check(lib().pt_profile_reset(self.h))
 
     def pt_reset(self):
         _check(lib().pt_reset(self.h))

@@ -144,6 +144,8 @@ extern "C" int pt_create(const pt_config* cfg, void* dev_weights, size_t weight_
 
 extern "C" int pt_destroy(pt_handle* h) {
   if (!h) return pt_set_error(PT_ERR_NULL_POINTER, "handle is NULL");
+  for (const pt_prof_pair& p : h->prof.pending) { (void)hipEventDestroy(p.e0); (void)hipEventDestroy(p.e1); }
+  for (hipEvent_t e : h->prof.free_events) (void)hipEventDestroy(e);
   delete h;
   return PT_OK;
 }
@@ -224,9 +226,83 @@ extern "C" int pt_track_merge(const void* const* host_tracks, int32_t n, int64_t
 }
 
 // ---------------------------------------------------------------------------------------------
+// Per-kernel timing: a pair of events around each launch of a selected class.
+// ---------------------------------------------------------------------------------------------
+static hipEvent_t prof_get_event(pt_handle* h) {
+  if (!h->prof.free_events.empty()) {
+    hipEvent_t e = h->prof.free_events.back();
+    h->prof.free_events.pop_back();
+    return e;
+  }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+struct prof_scope {
+  pt_handle* h;
+  int cls;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  prof_scope(pt_handle* h_, int cls_) : h(h_), cls(cls_) {
+    if (h->prof.mask & (1u << cls)) {
+      e0 = prof_get_event(h);
+      e1 = prof_get_event(h);
+      if (e0 && e1) (void)hipEventRecord(e0, h->stream);
+    }
+  }
+  ~prof_scope() {
+    if (e0 && e1) {
+      (void)hipEventRecord(e1, h->stream);
+      h->prof.pending.push_back({cls, e0, e1});
+    }
+  }
+};
+
+static int prof_fold(pt_handle* h) {
+  if (h->prof.pending.empty()) return PT_OK;
+  PT_HIP_CHECK(hipStreamSynchronize(h->stream));
+  for (const pt_prof_pair& p : h->prof.pending) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, p.e0, p.e1) == hipSuccess) {
+      h->prof.ms[p.cls] += ms;
+      h->prof.launches[p.cls] += 1;
+    }
+    h->prof.free_events.push_back(p.e0);
+    h->prof.free_events.push_back(p.e1);
+  }
+  h->prof.pending.clear();
+  return PT_OK;
+}
+
+extern "C" int pt_profile_enable(pt_handle* h, uint32_t class_mask) {
+  if (!h) return pt_set_error(PT_ERR_NULL_POINTER, "handle is NULL");
+  h->prof.mask = class_mask & ((1u << PT_K_COUNT) - 1);
+  return PT_OK;
+}
+
+extern "C" int pt_profile_read(pt_handle* h, int32_t kernel_class, double* total_ms, int64_t* launches) {
+  if (!h) return pt_set_error(PT_ERR_NULL_POINTER, "handle is NULL");
+  if (kernel_class < 0 || kernel_class >= PT_K_COUNT) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "unknown kernel class %d", kernel_class);
+  int rc = prof_fold(h);
+  if (rc) return rc;
+  if (total_ms) *total_ms = h->prof.ms[kernel_class];
+  if (launches) *launches = h->prof.launches[kernel_class];
+  return PT_OK;
+}
+
+extern "C" int pt_profile_reset(pt_handle* h) {
+  if (!h) return pt_set_error(PT_ERR_NULL_POINTER, "handle is NULL");
+  int rc = prof_fold(h);
+  if (rc) return rc;
+  for (int k = 0; k < PT_K_COUNT; ++k) { h->prof.ms[k] = 0; h->prof.launches[k] = 0; }
+  return PT_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
 // The forward pass.  rows = B*S rows per track; row m is sequence m / S at position pos0 + m % S.
 // ---------------------------------------------------------------------------------------------
-static int run_gemm(pt_handle* h, const pt_gemm_args& g) {
+static int run_gemm(pt_handle* h, const pt_gemm_args& g, int cls) {
+  prof_scope ps(h, cls);
   if (h->path == PT_PATH_AUTO) {
     int r = pt_launch_gemm_mfma(g, h->stream);
     if (r < 0) return r;
@@ -236,6 +312,7 @@ static int run_gemm(pt_handle* h, const pt_gemm_args& g) {
 }
 
 static int run_attention(pt_handle* h, const pt_attn_args& a) {
+  prof_scope ps(h, a.S == 1 ? PT_K_ATTN_DECODE : PT_K_ATTN_PREFILL);
   if (h->path == PT_PATH_AUTO) {
     int r = a.S == 1 ? pt_launch_attn_decode(a, h->stream) : pt_launch_attn_prefill_mfma(a, h->stream);
     if (r < 0) return r;
@@ -277,7 +354,7 @@ static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
     x = dev_hidden_in;
     x_bstride = hidden_tracks == 1 ? 0 : rows * d;
   } else {
-    rc = pt_launch_embed(h->w + l.off_embed, c.dtype, dev_tokens, rows, (int32_t)d, c.vocab, hm, st);
+    { prof_scope ps(h, PT_K_EMBED); rc = pt_launch_embed(h->w + l.off_embed, c.dtype, dev_tokens, rows, (int32_t)d, c.vocab, hm, st); }
     if (rc) return rc;
     x = hm;
     x_bstride = 0;
@@ -294,8 +371,11 @@ static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
     const int64_t w_bstride = L * l.layer_w_elems;
 
     // attention half
-    rc = pt_launch_rmsnorm(src, src_bstride, gains + (layer * 2 + 0) * d, L * 2 * d, abuf, rows * d,
-                           c.dtype, (int32_t)T, rows, (int32_t)d, c.rms_eps, st);
+    {
+      prof_scope ps(h, PT_K_RMSNORM);
+      rc = pt_launch_rmsnorm(src, src_bstride, gains + (layer * 2 + 0) * d, L * 2 * d, abuf, rows * d,
+                             c.dtype, (int32_t)T, rows, (int32_t)d, c.rms_eps, st);
+    }
     if (rc) return rc;
     pt_gemm_args g;
     memset(&g, 0, sizeof(g));
@@ -313,7 +393,7 @@ static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
     g.kv_bstride = L * c.max_batch * c.n_kv_heads;   // in heads; kernels scale by the head size
     g.kv_seq_stride = c.n_kv_heads;                  // in heads
     g.kv_head_elems = kv_head_k;
-    rc = run_gemm(h, g);
+    rc = run_gemm(h, g, PT_K_GEMM_QKV);
     if (rc) return rc;
 
     pt_attn_args a;
@@ -335,12 +415,15 @@ static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
     g.dtype = c.dtype; g.epi = EPI_RESIDUAL;
     g.out = hres; g.out_bstride = rows * d; g.ldo = (int32_t)d;
     g.res = src; g.res_bstride = src_bstride;
-    rc = run_gemm(h, g);
+    rc = run_gemm(h, g, PT_K_GEMM_OUT);
     if (rc) return rc;
 
     // feed-forward half
-    rc = pt_launch_rmsnorm(hres, rows * d, gains + (layer * 2 + 1) * d, L * 2 * d, abuf, rows * d,
-                           c.dtype, (int32_t)T, rows, (int32_t)d, c.rms_eps, st);
+    {
+      prof_scope ps(h, PT_K_RMSNORM);
+      rc = pt_launch_rmsnorm(hres, rows * d, gains + (layer * 2 + 1) * d, L * 2 * d, abuf, rows * d,
+                             c.dtype, (int32_t)T, rows, (int32_t)d, c.rms_eps, st);
+    }
     if (rc) return rc;
     memset(&g, 0, sizeof(g));
     g.A = abuf; g.a_bstride = rows * d; g.lda = (int32_t)d;
@@ -348,7 +431,7 @@ static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
     g.M = (int32_t)rows; g.N = (int32_t)(2 * f); g.K = (int32_t)d; g.batch = (int32_t)T;
     g.dtype = c.dtype; g.epi = EPI_SWIGLU;
     g.olp = mbuf; g.olp_bstride = rows * f;
-    rc = run_gemm(h, g);
+    rc = run_gemm(h, g, PT_K_GEMM_GATEUP);
     if (rc) return rc;
     memset(&g, 0, sizeof(g));
     g.A = mbuf; g.a_bstride = rows * f; g.lda = (int32_t)f;
@@ -357,7 +440,7 @@ static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
     g.dtype = c.dtype; g.epi = EPI_RESIDUAL;
     g.out = hres; g.out_bstride = rows * d; g.ldo = (int32_t)d;
     g.res = hres; g.res_bstride = rows * d;
-    rc = run_gemm(h, g);
+    rc = run_gemm(h, g, PT_K_GEMM_DOWN);
     if (rc) return rc;
 
     // Algorithm 1: after every D-th layer, all-reduce the track activations; every track
@@ -370,7 +453,10 @@ static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
         if (rc) return rc;
       }
       float* tap = h->taps ? h->taps + (int64_t)merge_idx * rows * d : nullptr;
-      rc = pt_launch_merge(tr, (int32_t)T, rows * d, PT_F32, c.merge_scale, hm, tap, st);
+      {
+        prof_scope ps(h, PT_K_MERGE);
+        rc = pt_launch_merge(tr, (int32_t)T, rows * d, PT_F32, c.merge_scale, hm, tap, st);
+      }
       if (rc) return rc;
       x = hm;
       x_bstride = 0;
@@ -400,7 +486,7 @@ static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
     g.M = (int32_t)lrows; g.N = c.vocab; g.K = (int32_t)d; g.batch = 1;
     g.dtype = c.dtype; g.epi = EPI_STORE_F32;
     g.out = lg; g.out_bstride = 0; g.ldo = c.vocab;
-    rc = run_gemm(h, g);
+    rc = run_gemm(h, g, PT_K_GEMM_HEAD);
     if (rc) return rc;
     if (dev_argmax) {
       rc = pt_launch_argmax(lg, (int32_t)lrows, c.vocab, dev_argmax, st);

@@ -6,6 +6,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "pt.h"
 
 typedef uint16_t bf16_t;  // raw bfloat16 bits
@@ -60,6 +62,19 @@ struct pt_layout {
   int32_t max_splits;
 };
 
+struct pt_prof_pair {
+  int cls;
+  hipEvent_t e0, e1;
+};
+
+struct pt_prof {
+  uint32_t mask = 0;
+  std::vector<hipEvent_t> free_events;
+  std::vector<pt_prof_pair> pending;
+  double ms[PT_K_COUNT] = {0};
+  int64_t launches[PT_K_COUNT] = {0};
+};
+
 struct pt_handle {
   pt_config cfg;
   pt_layout lay;
@@ -75,6 +90,7 @@ struct pt_handle {
   float* taps;
   float* track_taps;
   int32_t path;
+  pt_prof prof;
 };
 
 int pt_set_error(int code, const char* fmt, ...);
