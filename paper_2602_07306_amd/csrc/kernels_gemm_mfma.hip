@@ -20,8 +20,12 @@
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));   // 16-byte staging register
 
 #define GM_BK 64
+#ifndef GM_SWZ
+#define GM_SWZ(row) (((row) >> 1) & 7)
+#endif
 
 struct tile_coord {
   int b, tm, tn;
@@ -76,19 +80,19 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(const pt_gemm_a
     const int row = ld_row + i * (NT / 8);
     const int gr = min(m0 + row, g.M - 1);
     a_src[i] = A + (int64_t)gr * g.lda + ld_ch * 8;
-    a_dst[i] = row * GM_BK + ((ld_ch ^ (row & 7)) * 8);
+    a_dst[i] = row * GM_BK + ((ld_ch ^ GM_SWZ(row)) * 8);
   }
 #pragma unroll
   for (int i = 0; i < B_CH; ++i) {
     const int row = ld_row + i * (NT / 8);
     const int gr = min(n0 + row, g.N - 1);
     w_src[i] = W + (int64_t)gr * g.ldb + ld_ch * 8;
-    w_dst[i] = row * GM_BK + ((ld_ch ^ (row & 7)) * 8);
+    w_dst[i] = row * GM_BK + ((ld_ch ^ GM_SWZ(row)) * 8);
   }
-  uint4 a_reg[A_CH], w_reg[B_CH];
+  u32x4_t a_reg[A_CH], w_reg[B_CH];
 
   // operand reads: row = tile row + lane%32, chunk = 2*kk + lane/32, swizzled by row%8 = lane%8
-  const int fr_row = lane & 31, fr_half = lane >> 5, fr_sw = lane & 7;
+  const int fr_row = lane & 31, fr_half = lane >> 5, fr_sw = GM_SWZ(lane & 31);
   int a_off[MI], b_off[NI];
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi) a_off[mi] = (wm * TM + mi * 32 + fr_row) * GM_BK;
@@ -104,48 +108,90 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(const pt_gemm_a
       for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
 
   const int KT = g.K / GM_BK;
+  // Software pipeline.  While the MFMAs of K step kt run out of LDS buffer kt&1:
+  //   - the global loads of step kt+2 are in flight into registers,
+  //   - step kt+1 (loaded one iteration earlier) is stored into the other LDS buffer,
+  //   - operand fragments are read one 16-wide sub-step ahead of the MFMAs that use them,
+  //   - the single barrier of the iteration sits before the last sub-step's MFMAs, so the first
+  //     fragments of step kt+1 are fetched in the shadow of those MFMAs.
+  // Steps beyond the end re-read the last one; their copies are never multiplied.
 #pragma unroll
-  for (int i = 0; i < A_CH; ++i) a_reg[i] = *(const uint4*)(a_src[i]);
+  for (int i = 0; i < A_CH; ++i) a_reg[i] = *(const u32x4_t*)(a_src[i]);
 #pragma unroll
-  for (int i = 0; i < B_CH; ++i) w_reg[i] = *(const uint4*)(w_src[i]);
+  for (int i = 0; i < B_CH; ++i) w_reg[i] = *(const u32x4_t*)(w_src[i]);
 #pragma unroll
-  for (int i = 0; i < A_CH; ++i) *(uint4*)(As + a_dst[i]) = a_reg[i];
+  for (int i = 0; i < A_CH; ++i) *(u32x4_t*)(As + a_dst[i]) = a_reg[i];
 #pragma unroll
-  for (int i = 0; i < B_CH; ++i) *(uint4*)(Bs + w_dst[i]) = w_reg[i];
+  for (int i = 0; i < B_CH; ++i) *(u32x4_t*)(Bs + w_dst[i]) = w_reg[i];
+  {
+    const int koff = min(1, KT - 1) * GM_BK;
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i) a_reg[i] = *(const u32x4_t*)(a_src[i] + koff);
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i) w_reg[i] = *(const u32x4_t*)(w_src[i] + koff);
+  }
   __syncthreads();
+
+  bf16x8_t af[2][MI], bfr[2][NI];
+  {
+    const int ch = ((0 + fr_half) ^ fr_sw) * 8;
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) af[0][mi] = *(const bf16x8_t*)(As + a_off[mi] + ch);
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) bfr[0][ni] = *(const bf16x8_t*)(Bs + b_off[ni] + ch);
+  }
 
   for (int kt = 0; kt < KT; ++kt) {
     const int cur = kt & 1;
-    // prefetch the next K step into registers (the last step re-reads itself; its copy is unused)
-    const int koff = min(kt + 1, KT - 1) * GM_BK;
+    u32x4_t a_nxt[A_CH], w_nxt[B_CH];
+    const int koff = min(kt + 2, KT - 1) * GM_BK;
 #pragma unroll
-    for (int i = 0; i < A_CH; ++i) a_reg[i] = *(const uint4*)(a_src[i] + koff);
+    for (int i = 0; i < A_CH; ++i) a_nxt[i] = *(const u32x4_t*)(a_src[i] + koff);
 #pragma unroll
-    for (int i = 0; i < B_CH; ++i) w_reg[i] = *(const uint4*)(w_src[i] + koff);
+    for (int i = 0; i < B_CH; ++i) w_nxt[i] = *(const u32x4_t*)(w_src[i] + koff);
+    __builtin_amdgcn_sched_barrier(0);
     const bf16_t* Ac = As + cur * BM * GM_BK;
     const bf16_t* Bc = Bs + cur * BN * GM_BK;
+    bf16_t* An = As + (cur ^ 1) * BM * GM_BK;
+    bf16_t* Bn = Bs + (cur ^ 1) * BN * GM_BK;
 #pragma unroll
     for (int kk = 0; kk < GM_BK / 16; ++kk) {
-      const int ch = ((kk * 2 + fr_half) ^ fr_sw) * 8;
-      bf16x8_t af[MI], bfr[NI];
+      if (kk + 1 < GM_BK / 16) {
+        const int ch = (((kk + 1) * 2 + fr_half) ^ fr_sw) * 8;
 #pragma unroll
-      for (int mi = 0; mi < MI; ++mi) af[mi] = *(const bf16x8_t*)(Ac + a_off[mi] + ch);
+        for (int mi = 0; mi < MI; ++mi) af[(kk + 1) & 1][mi] = *(const bf16x8_t*)(Ac + a_off[mi] + ch);
 #pragma unroll
-      for (int ni = 0; ni < NI; ++ni) bfr[ni] = *(const bf16x8_t*)(Bc + b_off[ni] + ch);
+        for (int ni = 0; ni < NI; ++ni) bfr[(kk + 1) & 1][ni] = *(const bf16x8_t*)(Bc + b_off[ni] + ch);
+      } else {
+        // every wavefront has finished reading this buffer and storing the next one
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        const int ch = ((0 + fr_half) ^ fr_sw) * 8;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) af[0][mi] = *(const bf16x8_t*)(An + a_off[mi] + ch);
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) bfr[0][ni] = *(const bf16x8_t*)(Bn + b_off[ni] + ch);
+      }
+      if (kk == 0) {
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) *(u32x4_t*)(An + a_dst[i]) = a_reg[i];
+#pragma unroll
+        for (int i = 0; i < B_CH; ++i) *(u32x4_t*)(Bn + w_dst[i]) = w_reg[i];
+      }
+      // fences for the instruction scheduler: keep the LDS traffic of this sub-step ahead of its MFMAs
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][mi], bfr[kk & 1][ni], acc[mi][ni], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    bf16_t* An = As + (cur ^ 1) * BM * GM_BK;
-    bf16_t* Bn = Bs + (cur ^ 1) * BN * GM_BK;
 #pragma unroll
-    for (int i = 0; i < A_CH; ++i) *(uint4*)(An + a_dst[i]) = a_reg[i];
+    for (int i = 0; i < A_CH; ++i) a_reg[i] = a_nxt[i];
 #pragma unroll
-    for (int i = 0; i < B_CH; ++i) *(uint4*)(Bn + w_dst[i]) = w_reg[i];
-    __syncthreads();
+    for (int i = 0; i < B_CH; ++i) w_reg[i] = w_nxt[i];
   }
+  __syncthreads();
 
   // ------------------------------------------------------------------ epilogue
   const int col_l = lane & 31;

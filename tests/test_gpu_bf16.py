@@ -1,0 +1,191 @@
+"""GPU parity, bf16: the tuned HIP path (MFMA GEMMs with fused epilogues, flash-style prefill
+attention, split-K decode attention) against the CPU oracle, on small shapes that span several
+tiles, ragged tails and every kernel-selection branch, and at the full Mid PT sizes."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+from oracle import pt_oracle as O
+from paper_2602_07306_amd import inputs as I
+from tests.helpers import BF16_TOL, argmax_agrees, oracle_prefill, rel_err, small_bf16_config
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+def run_case(cfg, seed, B, S, steps, paths):
+    from paper_2602_07306_amd import binding as PB
+    W = I.make_weights(cfg, seed)
+    tokens = I.make_tokens(seed, B, S, cfg.vocab)
+    ref, st = oracle_prefill(cfg, W, tokens)
+    nxt = np.argmax(ref["logits"][:, -1], -1).astype(np.int32)
+    refs = []
+    for _ in range(steps):
+        r = O.pt_decode_step(cfg, W, st, tokens=nxt)
+        refs.append((nxt.copy(), r))
+        nxt = r["argmax"]
+    model = PB.PTModel(cfg)
+    model.pt_init_weights(seed)
+    outs = {}
+    for path in paths:
+        model.pt_set_kernel_path(path)
+        model.pt_reset()
+        taps, _ = model.pt_set_taps(B * S)
+        lg, hid = model.pt_prefill(torch.from_numpy(tokens).cuda(), logits_mode=PB.PT_LOGITS_ALL,
+                                   want_hidden=True)
+        torch.cuda.synchronize()
+        L = lg.cpu().numpy().reshape(B, S, -1)
+        assert rel_err(L, ref["logits"]) <= BF16_TOL
+        assert rel_err(hid.cpu().numpy(), ref["hidden"]) <= BF16_TOL
+        for b in range(B):
+            for k in range(cfg.n_merges):
+                got = taps[k].cpu().numpy().reshape(B, S, -1)[b]
+                assert rel_err(got, ref["taps"][b][k]) <= BF16_TOL, (b, k)
+            assert argmax_agrees(L[b], ref["logits"][b], BF16_TOL)
+        model.pt_clear_taps()
+        for i, (tok, r) in enumerate(refs):
+            lg, _, am = model.pt_decode_step(torch.from_numpy(tok).cuda(), want_argmax=True)
+            torch.cuda.synchronize()
+            assert rel_err(lg.cpu().numpy(), r["logits"]) <= BF16_TOL, i
+            assert argmax_agrees(lg.cpu().numpy(), r["logits"], BF16_TOL)
+            assert np.array_equal(am.cpu().numpy(), np.argmax(lg.cpu().numpy(), -1))
+        assert model.pt_seq_len() == S + steps
+        outs[path] = L
+    model.close()
+    return outs
+
+
+CASES = {
+    # name: (config overrides, B, S, decode steps)
+    "hd64_tiles": (dict(), 2, 128, 2),
+    "hd128": (dict(head_dim=128, n_heads=2, n_kv_heads=2), 2, 128, 2),
+    "gqa_hd64": (dict(n_kv_heads=2), 2, 96, 2),
+    "gqa_1kv_hd128": (dict(head_dim=128, n_heads=4, n_kv_heads=1, d_model=512), 1, 160, 2),
+    "ragged_rows": (dict(), 2, 100, 2),                  # S not a multiple of any tile: M tail, generic attention
+    "three_tracks": (dict(n_tracks=3, n_layers=3, block_depth=1, merge_scale=1.0 / 3), 1, 64, 1),
+    "split_decode": (dict(max_batch=1, max_seq=1024), 1, 704, 3),   # decode context split in two, ragged tail
+    "one_token_prompt": (dict(), 2, 1, 3),
+}
+
+
+@pytest.mark.parametrize("name", sorted(CASES))
+def test_small_bf16_models_match_the_oracle(name):
+    from paper_2602_07306_amd import binding as PB
+    over, B, S, steps = CASES[name]
+    cfg = small_bf16_config(**over)
+    outs = run_case(cfg, 7 + len(name), B, S, steps, (PB.PT_PATH_AUTO, PB.PT_PATH_GENERIC))
+    # the tuned and the shape-generic kernels agree with each other as well
+    assert rel_err(outs[PB.PT_PATH_AUTO], outs[PB.PT_PATH_GENERIC]) <= BF16_TOL
+
+
+def test_results_are_reproducible_run_to_run():
+    """Two runs of the same forward give bit-identical logits (no races in LDS staging)."""
+    from paper_2602_07306_amd import binding as PB
+    cfg = small_bf16_config()
+    model = PB.PTModel(cfg)
+    model.pt_init_weights(3)
+    tokens = torch.from_numpy(I.make_tokens(3, 2, 256, cfg.vocab)).cuda()
+    a, _ = model.pt_prefill(tokens, logits_mode=PB.PT_LOGITS_ALL)
+    a = a.clone()
+    b, _ = model.pt_prefill(tokens, logits_mode=PB.PT_LOGITS_ALL)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+    model.close()
+
+
+def test_causal_prefix_and_batch_independence_on_the_gpu():
+    from paper_2602_07306_amd import binding as PB
+    cfg = small_bf16_config(max_batch=3)
+    model = PB.PTModel(cfg)
+    model.pt_init_weights(5)
+    tok = I.make_tokens(5, 3, 128, cfg.vocab)
+    full, _ = model.pt_prefill(torch.from_numpy(tok).cuda(), logits_mode=PB.PT_LOGITS_ALL)
+    full = full.cpu().numpy().reshape(3, 128, -1)
+    # appended tokens do not change earlier positions; batch-mates do not change a sequence
+    part, _ = model.pt_prefill(torch.from_numpy(np.ascontiguousarray(tok[1:2, :64])).cuda(),
+                               logits_mode=PB.PT_LOGITS_ALL)
+    part = part.cpu().numpy().reshape(1, 64, -1)
+    assert rel_err(part[0], full[1, :64]) <= 1e-2     # different tile shapes, same mathematics
+    model.close()
+
+
+def test_mid_prefill_full_size_matches_the_oracle_on_sampled_sequences():
+    """Mid PT prefill at the benchmark's sizes and launch configuration (T=4, L=16, D=4, d=1024,
+    16 heads x 64, FFN 4096, vocab 32000, batch 4 x 1024).  The oracle evaluates two of the four
+    sequences (sequences are independent) at every position."""
+    from paper_2602_07306_amd import binding as PB
+    cfg = I.config_mid(max_batch=4, max_seq=1024)
+    B, S = 4, 1024
+    W = I.make_weights(cfg, 1)
+    tokens = I.make_tokens(1, B, S, cfg.vocab)
+    model = PB.PTModel(cfg)
+    model.pt_init_weights(1)
+    got_w = model.pt_get_weight("wd", 3, 15, W["wd"][3, 15].shape)
+    assert np.array_equal(got_w, W["wd"][3, 15])
+    taps, _ = model.pt_set_taps(B * S)
+    lg, _ = model.pt_prefill(torch.from_numpy(tokens).cuda(), logits_mode=PB.PT_LOGITS_ALL)
+    torch.cuda.synchronize()
+    assert model.pt_merge_count() == 4
+    L = lg.cpu().numpy().reshape(B, S, -1)
+    last, _ = model.pt_prefill(torch.from_numpy(tokens).cuda(), logits_mode=PB.PT_LOGITS_LAST)
+    torch.cuda.synchronize()
+    assert np.array_equal(last.cpu().numpy(), L[:, -1])
+    for b in (0, 3):
+        st = O.PTState(cfg, 1, S)
+        ref = O.pt_prefill(cfg, W, st, tokens=tokens[b:b + 1], collect_taps=True)
+        assert rel_err(L[b], ref["logits"][0]) <= BF16_TOL, b
+        for k in range(4):
+            got = taps[k].cpu().numpy().reshape(B, S, -1)[b]
+            assert rel_err(got, ref["taps"][0][k]) <= BF16_TOL, (b, k)
+        assert argmax_agrees(L[b], ref["logits"][0], BF16_TOL)
+    model.close()
+
+
+def test_mid_decode_full_context_matches_the_oracle_on_a_sampled_sequence():
+    """Mid PT decode shape: batch 32, 2048-token prompts (seed 2), then KV-cached steps.  The
+    oracle follows one of the 32 sequences (prefill + the same decode tokens)."""
+    from paper_2602_07306_amd import binding as PB
+    B, prompt, steps, pick = 32, 2048, 3, 17
+    cfg = I.config_mid(max_batch=B, max_seq=prompt + 64)
+    W = I.make_weights(cfg, 1)
+    tokens = I.make_tokens(2, B, prompt, cfg.vocab)
+    feed = I.make_tokens(12, steps, B, cfg.vocab)            # decode inputs, [step, B]
+    model = PB.PTModel(cfg)
+    model.pt_init_weights(1)
+    lg, _ = model.pt_prefill(torch.from_numpy(tokens).cuda(), logits_mode=PB.PT_LOGITS_LAST)
+    torch.cuda.synchronize()
+    st = O.PTState(cfg, 1, prompt + 64)
+    ref = O.pt_prefill(cfg, W, st, tokens=tokens[pick:pick + 1])
+    assert rel_err(lg.cpu().numpy()[pick], ref["logits"][0, -1]) <= BF16_TOL
+    for i in range(steps):
+        r = O.pt_decode_step(cfg, W, st, tokens=feed[i, pick:pick + 1])
+        g, _, _ = model.pt_decode_step(torch.from_numpy(np.ascontiguousarray(feed[i])).cuda())
+        torch.cuda.synchronize()
+        assert rel_err(g.cpu().numpy()[pick], r["logits"][0]) <= BF16_TOL, i
+    assert model.pt_seq_len() == prompt + steps
+    model.close()
+
+
+def test_block_end_merge_at_the_one_gpu_share_shape():
+    """The block-end merge of one GPU's share of a wide 8-track model: own hidden state plus the
+    other 7 tracks' hidden states as seeded N(0,1) bf16 tensors [8192 tokens, 8192]."""
+    from paper_2602_07306_amd import binding as PB
+    tokens, d, n = 8192, 8192, 8
+    hs = [I.make_hidden(4, i, tokens, d) for i in range(n)]
+    dev = [torch.from_numpy(h).cuda().to(torch.bfloat16) for h in hs]
+    out = PB.pt_track_merge(dev, 1.0)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy()
+    rows = np.random.default_rng(0).choice(tokens, 64, replace=False)
+    ref = O.track_merge([h[rows] for h in hs], 1.0)
+    assert rel_err(got[rows], ref) <= 2.0 ** -8
+    acc = hs[0][rows].copy()
+    for h in hs[1:]:
+        acc = acc + h[rows]
+    assert np.array_equal(got[rows], I.round_to_dtype(acc, I.PT_BF16))
+    # every element, against a property that holds at any size: |out| <= sum |h_i| (+ rounding)
+    bound = np.zeros((tokens, d), np.float32)
+    for h in hs:
+        bound += np.abs(h)
+    assert np.all(np.abs(got) <= bound * (1 + 2.0 ** -7) + 1e-6)
