@@ -16,27 +16,49 @@
 //     the weight rows are interleaved in blocks of 32;
 //   - the rotary pair (j, j + hd/2) is (tile ni, tile ni + hd/64) in the same lane and register;
 //   - V is written transposed: 4 consecutive rows of a register group are 4 consecutive positions.
+#include <type_traits>
+
 #include "pt_epilogue.h"
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));   // 16-byte staging register
 
-#define GM_BK 64
-#ifndef GM_SWZ
-#define GM_SWZ(row) (((row) >> 1) & 7)
+__device__ __forceinline__ float silu_fast(float z) {
+  return z * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * z));
+}
+
+#define GM_BK 64   // largest K step; K must be a multiple of 2 * GM_BK
+
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (N > 0) {
+    static_for<N - 1>(f);
+    f(std::integral_constant<int, N - 1>{});
+  }
+}
+
+#ifdef GM_TIMING   // tuning builds only: per-phase clock stamps of workgroup 0
+__device__ long long gm_stamps[64];
+#define GM_STAMP(i) do { if (blockIdx.x == 0 && threadIdx.x == 0 && (i) < 64) gm_stamps[i] = wall_clock64(); } while (0)
+#else
+#define GM_STAMP(i) do { } while (0)
 #endif
 
 struct tile_coord {
   int b, tm, tn;
 };
 
-// Workgroup id -> (track, m-tile, n-tile).  Consecutive ids are dealt round-robin to the 8 XCDs, so
-// ids are first regrouped so that each XCD (own L2) walks a contiguous range; inside a range, tiles
-// are visited in groups of 4 m-tiles x all n-tiles, column-major inside the group, which keeps the
-// A and W slabs of concurrently resident workgroups few.
-__device__ __forceinline__ tile_coord map_tile(int id, int total, int tiles_m, int tiles_n) {
-  if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
+// Workgroup ids are dealt round-robin to the 8 XCDs (XCD = id % 8).  Regrouping them so that each XCD
+// (own L2) walks a contiguous range of logical tile ids keeps the A and W slabs that concurrently
+// resident workgroups of one XCD share few.
+__device__ __forceinline__ int logical_tile(int id, int total) {
+  return (total & 7) == 0 ? (id & 7) * (total >> 3) + (id >> 3) : id;
+}
+
+// Logical id -> (track, m-tile, n-tile): groups of 4 m-tiles x all n-tiles, column-major inside a
+// group, so that concurrently resident workgroups share few A and W slabs.
+__device__ __forceinline__ tile_coord decode_tile(int id, int tiles_m, int tiles_n) {
   const int per_b = tiles_m * tiles_n;
   tile_coord c;
   c.b = id / per_b;
@@ -52,276 +74,365 @@ __device__ __forceinline__ tile_coord map_tile(int id, int total, int tiles_m, i
   return c;
 }
 
-template <int BM, int BN, int WM, int WN, int EPI>
-__global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
+template <int BM, int BN, int WM, int WN, int BK, int EPI>
+__global__ void __launch_bounds__(WM * WN * 64, (2 * (BM + BN) * BK * 2 <= 80 * 1024 && BM * BN <= 256 * 128 && WM * WN == 4) ? 2 : 1)
+gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
   constexpr int NT = WM * WN * 64;
   constexpr int TM = BM / WM, TN = BN / WN, MI = TM / 32, NI = TN / 32;
-  constexpr int A_CH = BM * 8 / NT, B_CH = BN * 8 / NT;  // 16-byte chunks per thread and K step
-  static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile/threads mismatch");
+  constexpr int CPR = BK / 8;        // 16-byte chunks per LDS row
+  constexpr int SS = BK / 16;        // MFMA sub-steps per K step
+  constexpr int A_CH = BM * CPR / NT, B_CH = BN * CPR / NT;  // 16-byte chunks per thread and K step
+  static_assert(BK == 64 || BK == 32, "K step");
+  static_assert(BM * CPR % NT == 0 && BN * CPR % NT == 0, "tile/threads mismatch");
+  // XOR swizzle of the 16-byte chunks: any 16 consecutive rows reading the same logical chunk hit 16
+  // different 16-byte columns of a 256-byte LDS line (gfx950 serves 16 lanes x 16 B per clock)
+  auto SWZ = [](int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); };
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  bf16_t* As = (bf16_t*)smem;            // [2][BM][64]
-  bf16_t* Bs = As + 2 * BM * GM_BK;      // [2][BN][64]
+  bf16_t* As = (bf16_t*)smem;            // [2][BM][BK]
+  bf16_t* Bs = As + 2 * BM * BK;      // [2][BN][BK]
 
+  GM_STAMP(0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
-  const tile_coord tc = map_tile(blockIdx.x, gridDim.x, tiles_m, tiles_n);
+  const tile_coord tc = decode_tile(logical_tile(blockIdx.x, gridDim.x), tiles_m, tiles_n);
   const int m0 = tc.tm * BM, n0 = tc.tn * BN, b = tc.b;
 
-  const bf16_t* A = (const bf16_t*)g.A + b * g.a_bstride;
-  const bf16_t* W = (const bf16_t*)g.W + b * g.w_bstride;
+  // global -> register staging: chunk id = tid + i*NT; row = id/CPR, 16-byte chunk = id%CPR.
+  // Rows of one thread are NT/CPR apart, a multiple of 16, so they share the swizzle and the LDS
+  // destinations differ by a constant.
+  const int ld_row = tid / CPR, ld_ch = tid % CPR;
+  static_assert((NT / CPR) % 16 == 0, "staging rows must keep the swizzle");
+  constexpr int ST_STRIDE = (NT / CPR) * BK;                    // elements between a thread's staging rows
+  const int st_dst = ld_row * BK + ((ld_ch ^ SWZ(ld_row)) * 8);
+  u32x4_t a_reg[2][A_CH], w_reg[2][B_CH];                        // two staging sets: K steps of equal parity
 
-  // global -> register staging: chunk id = tid + i*NT; row = id/8, 16-byte chunk = id%8
-  const int ld_row = tid >> 3, ld_ch = tid & 7;
-  const bf16_t* a_src[A_CH];
-  const bf16_t* w_src[B_CH];
-  int a_dst[A_CH], w_dst[B_CH];
+  const int KT = g.K / BK;   // even, >= 2
+  uint32_t a_voff[A_CH], w_voff[B_CH];   // byte offsets from the tile's first row
 #pragma unroll
   for (int i = 0; i < A_CH; ++i) {
-    const int row = ld_row + i * (NT / 8);
-    const int gr = min(m0 + row, g.M - 1);
-    a_src[i] = A + (int64_t)gr * g.lda + ld_ch * 8;
-    a_dst[i] = row * GM_BK + ((ld_ch ^ GM_SWZ(row)) * 8);
+    const int gr = min(m0 + ld_row + i * (NT / CPR), g.M - 1) - m0;
+    a_voff[i] = (uint32_t)((gr * g.lda + ld_ch * 8) * 2);
   }
 #pragma unroll
   for (int i = 0; i < B_CH; ++i) {
-    const int row = ld_row + i * (NT / 8);
-    const int gr = min(n0 + row, g.N - 1);
-    w_src[i] = W + (int64_t)gr * g.ldb + ld_ch * 8;
-    w_dst[i] = row * GM_BK + ((ld_ch ^ GM_SWZ(row)) * 8);
+    const int gr = min(n0 + ld_row + i * (NT / CPR), g.N - 1) - n0;
+    w_voff[i] = (uint32_t)((gr * g.ldb + ld_ch * 8) * 2);
   }
-  u32x4_t a_reg[A_CH], w_reg[B_CH];
+  const char* a_base = (const char*)((const bf16_t*)g.A + b * g.a_bstride + (int64_t)m0 * g.lda);   // wave-uniform
+  const char* w_base = (const char*)((const bf16_t*)g.W + b * g.w_bstride + (int64_t)n0 * g.ldb);
+  auto load_a = [&](int set, int i, int kstep) { a_reg[set][i] = *(const u32x4_t*)(a_base + (size_t)kstep * (BK * 2) + a_voff[i]); };
+  auto load_w = [&](int set, int i, int kstep) { w_reg[set][i] = *(const u32x4_t*)(w_base + (size_t)kstep * (BK * 2) + w_voff[i]); };
 
-  // operand reads: row = tile row + lane%32, chunk = 2*kk + lane/32, swizzled by row%8 = lane%8
-  const int fr_row = lane & 31, fr_half = lane >> 5, fr_sw = GM_SWZ(lane & 31);
-  int a_off[MI], b_off[NI];
+  // operand reads: row = tile row + lane%32, 16-byte chunk = 2*kk + lane/32, swizzled by the row
+  const int fr_row = lane & 31, fr_half = lane >> 5, fr_sw = SWZ(lane & 31);
+  int a_fr[SS], b_fr[SS];   // element offsets of sub-step kk inside a buffer, first MFMA tile of the wavefront
 #pragma unroll
-  for (int mi = 0; mi < MI; ++mi) a_off[mi] = (wm * TM + mi * 32 + fr_row) * GM_BK;
+  for (int kk = 0; kk < SS; ++kk) {
+    const int ch = ((kk * 2 + fr_half) ^ fr_sw) * 8;
+    a_fr[kk] = (wm * TM + fr_row) * BK + ch;
+    b_fr[kk] = (wn * TN + fr_row) * BK + ch;
+  }
+
+  // Software pipeline (K step = 64).  In every iteration the MFMAs run out of LDS buffer `cur` while
+  //   sub-steps 0,1: the next K step (staging set cur^1, loaded two iterations ago) is stored into the
+  //                  other LDS buffer,
+  //   sub-steps 2,3: the K step three ahead is loaded from global memory into the set just freed,
+  //   every sub-step: the operand fragments of the next sub-step are read from LDS,
+  // and every memory instruction is issued between two MFMAs, so no queue sees a burst.  The one
+  // barrier of the iteration sits in front of sub-step 3: after it the first fragments of the next
+  // K step are fetched in the shadow of the last MFMAs.
 #pragma unroll
-  for (int ni = 0; ni < NI; ++ni) b_off[ni] = (wn * TN + ni * 32 + fr_row) * GM_BK;
+  for (int i = 0; i < A_CH; ++i) load_a(0, i, 0);
+#pragma unroll
+  for (int i = 0; i < B_CH; ++i) load_w(0, i, 0);
+#pragma unroll
+  for (int i = 0; i < A_CH; ++i) load_a(1, i, 1);
+#pragma unroll
+  for (int i = 0; i < B_CH; ++i) load_w(1, i, 1);
+#pragma unroll
+  for (int i = 0; i < A_CH; ++i) *(u32x4_t*)(As + st_dst + i * ST_STRIDE) = a_reg[0][i];
+#pragma unroll
+  for (int i = 0; i < B_CH; ++i) *(u32x4_t*)(Bs + st_dst + i * ST_STRIDE) = w_reg[0][i];
+#pragma unroll
+  for (int i = 0; i < A_CH; ++i) load_a(0, i, min(2, KT - 1));
+#pragma unroll
+  for (int i = 0; i < B_CH; ++i) load_w(0, i, min(2, KT - 1));
+  __syncthreads();
+
+  GM_STAMP(1);
+  bf16x8_t af[2][MI], bfr[2][NI];
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi) af[0][mi] = *(const bf16x8_t*)(As + a_fr[0] + mi * 32 * BK);
+#pragma unroll
+  for (int ni = 0; ni < NI; ++ni) bfr[0][ni] = *(const bf16x8_t*)(Bs + b_fr[0] + ni * 32 * BK);
+
+  constexpr int NM = MI * NI;                  // MFMAs per sub-step
+  constexpr int FR = MI + NI;                  // fragment reads per sub-step
+  constexpr int EX = A_CH + B_CH;              // staging chunks per K step
+  constexpr int HS = SS / 2;                   // sub-steps that store, then as many that load
+  constexpr int EXH = (EX + HS - 1) / HS;      // staging chunks handled per sub-step
 
   f32x16_t acc[MI][NI];
+
+  auto iteration = [&](auto PAR, int kt) {
+    constexpr int cur = decltype(PAR)::value;          // LDS buffer being multiplied
+    constexpr int wset = cur ^ 1;                       // staging set stored, then reloaded
+    const bf16_t* Ac = As + cur * BM * BK;
+    const bf16_t* Bc = Bs + cur * BN * BK;
+    bf16_t* An = As + (cur ^ 1) * BM * BK;
+    bf16_t* Bn = Bs + (cur ^ 1) * BN * BK;
+    const int kload = min(kt + 3, KT - 1);   // K steps past the end re-read the last one (never multiplied)
+    static_for<SS>([&](auto KK) {
+      constexpr int kk = decltype(KK)::value;
+      constexpr int fb = (kk + 1) & 1;                  // fragment buffer being filled
+      constexpr int R = FR + EXH;                       // memory instructions of this sub-step
+      if constexpr (kk == SS - 1) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+      static_for<NM>([&](auto J) {
+        constexpr int j = decltype(J)::value;
+        constexpr int mi = j / NI, ni = j % NI;
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][mi], bfr[kk & 1][ni], acc[mi][ni], 0, 0, 0);
+        constexpr int lo = j * R / NM, hi = (j + 1) * R / NM;
+        static_for<hi - lo>([&](auto RR) {
+          constexpr int r = lo + decltype(RR)::value;
+          if constexpr (r < MI) {
+            const bf16_t* src = kk == SS - 1 ? An + a_fr[0] : Ac + a_fr[(kk + 1) % SS];
+            af[fb][r] = *(const bf16x8_t*)(src + r * 32 * BK);
+          } else if constexpr (r < FR) {
+            const bf16_t* src = kk == SS - 1 ? Bn + b_fr[0] : Bc + b_fr[(kk + 1) % SS];
+            bfr[fb][r - MI] = *(const bf16x8_t*)(src + (r - MI) * 32 * BK);
+          } else {
+            constexpr int e = (kk % HS) * EXH + (r - FR);   // staging chunk
+            if constexpr (e < EX) {
+              if constexpr (kk < HS) {
+                if constexpr (e < A_CH) *(u32x4_t*)(An + st_dst + e * ST_STRIDE) = a_reg[wset][e];
+                else *(u32x4_t*)(Bn + st_dst + (e - A_CH) * ST_STRIDE) = w_reg[wset][e - A_CH];
+              } else {
+                if constexpr (e < A_CH) load_a(wset, e, kload);
+                else load_w(wset, e - A_CH, kload);
+              }
+            }
+          }
+        });
+        __builtin_amdgcn_sched_barrier(0);
+      });
+    });
+  };
+
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
-
-  const int KT = g.K / GM_BK;
-  // Software pipeline.  While the MFMAs of K step kt run out of LDS buffer kt&1:
-  //   - the global loads of step kt+2 are in flight into registers,
-  //   - step kt+1 (loaded one iteration earlier) is stored into the other LDS buffer,
-  //   - operand fragments are read one 16-wide sub-step ahead of the MFMAs that use them,
-  //   - the single barrier of the iteration sits before the last sub-step's MFMAs, so the first
-  //     fragments of step kt+1 are fetched in the shadow of those MFMAs.
-  // Steps beyond the end re-read the last one; their copies are never multiplied.
-#pragma unroll
-  for (int i = 0; i < A_CH; ++i) a_reg[i] = *(const u32x4_t*)(a_src[i]);
-#pragma unroll
-  for (int i = 0; i < B_CH; ++i) w_reg[i] = *(const u32x4_t*)(w_src[i]);
-#pragma unroll
-  for (int i = 0; i < A_CH; ++i) *(u32x4_t*)(As + a_dst[i]) = a_reg[i];
-#pragma unroll
-  for (int i = 0; i < B_CH; ++i) *(u32x4_t*)(Bs + w_dst[i]) = w_reg[i];
-  {
-    const int koff = min(1, KT - 1) * GM_BK;
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) a_reg[i] = *(const u32x4_t*)(a_src[i] + koff);
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) w_reg[i] = *(const u32x4_t*)(w_src[i] + koff);
+  for (int kt = 0; kt < KT; kt += 2) {
+    iteration(std::integral_constant<int, 0>{}, kt);
+    iteration(std::integral_constant<int, 1>{}, kt + 1);
   }
-  __syncthreads();
-
-  bf16x8_t af[2][MI], bfr[2][NI];
-  {
-    const int ch = ((0 + fr_half) ^ fr_sw) * 8;
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi) af[0][mi] = *(const bf16x8_t*)(As + a_off[mi] + ch);
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni) bfr[0][ni] = *(const bf16x8_t*)(Bs + b_off[ni] + ch);
-  }
-
-  for (int kt = 0; kt < KT; ++kt) {
-    const int cur = kt & 1;
-    u32x4_t a_nxt[A_CH], w_nxt[B_CH];
-    const int koff = min(kt + 2, KT - 1) * GM_BK;
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) a_nxt[i] = *(const u32x4_t*)(a_src[i] + koff);
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) w_nxt[i] = *(const u32x4_t*)(w_src[i] + koff);
-    __builtin_amdgcn_sched_barrier(0);
-    const bf16_t* Ac = As + cur * BM * GM_BK;
-    const bf16_t* Bc = Bs + cur * BN * GM_BK;
-    bf16_t* An = As + (cur ^ 1) * BM * GM_BK;
-    bf16_t* Bn = Bs + (cur ^ 1) * BN * GM_BK;
-#pragma unroll
-    for (int kk = 0; kk < GM_BK / 16; ++kk) {
-      if (kk + 1 < GM_BK / 16) {
-        const int ch = (((kk + 1) * 2 + fr_half) ^ fr_sw) * 8;
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi) af[(kk + 1) & 1][mi] = *(const bf16x8_t*)(Ac + a_off[mi] + ch);
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni) bfr[(kk + 1) & 1][ni] = *(const bf16x8_t*)(Bc + b_off[ni] + ch);
-      } else {
-        // every wavefront has finished reading this buffer and storing the next one
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        const int ch = ((0 + fr_half) ^ fr_sw) * 8;
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi) af[0][mi] = *(const bf16x8_t*)(An + a_off[mi] + ch);
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni) bfr[0][ni] = *(const bf16x8_t*)(Bn + b_off[ni] + ch);
-      }
-      if (kk == 0) {
-#pragma unroll
-        for (int i = 0; i < A_CH; ++i) *(u32x4_t*)(An + a_dst[i]) = a_reg[i];
-#pragma unroll
-        for (int i = 0; i < B_CH; ++i) *(u32x4_t*)(Bn + w_dst[i]) = w_reg[i];
-      }
-      // fences for the instruction scheduler: keep the LDS traffic of this sub-step ahead of its MFMAs
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][mi], bfr[kk & 1][ni], acc[mi][ni], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) a_reg[i] = a_nxt[i];
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) w_reg[i] = w_nxt[i];
-  }
-  __syncthreads();
+  __syncthreads();   // LDS is free for the staged epilogues
+  GM_STAMP(2);
 
   // ------------------------------------------------------------------ epilogue
   const int col_l = lane & 31;
   const int row_l = 4 * (lane >> 5);
+  // LDS patch of this wavefront for the staged epilogues (the K loop is over: all of LDS is free)
+  constexpr bool STAGED = BM >= 128 && BN >= 128;
+  constexpr int STAGE_ELEMS = 2 * (BM + BN) * BK / (WM * WN);   // per wavefront
+  bf16_t* stage = (bf16_t*)smem + wave * STAGE_ELEMS;
+  (void)stage;
   const int wave_n = n0 + wn * TN;
   const int wave_m = m0 + wm * TM;
 
   if constexpr (EPI == EPI_STORE_F32 || EPI == EPI_RESIDUAL) {
     float* out = g.out + b * g.out_bstride;
     const float* res = EPI == EPI_RESIDUAL ? g.res + b * g.res_bstride : nullptr;
+    constexpr int FPITCH = TN + 8;   // floats; +8 keeps the two half-waves on disjoint banks
+    if constexpr (STAGED && 32 * FPITCH * 2 <= STAGE_ELEMS) {
+      // 32 rows at a time through the wavefront's LDS patch: the accumulator layout (a lane owns a
+      // column) becomes row pieces of 4 floats, so the residual read-modify-write moves 16 bytes per
+      // lane and whole 128-byte lines per row
+      float* fst = (float*)stage;
+      constexpr int LPR = TN / 4, RPI = 64 / LPR, ITS = 32 / RPI;
+      typedef float f32x4_t __attribute__((ext_vector_type(4)));
+      static_for<MI>([&](auto MI_) {
+        constexpr int mi = decltype(MI_)::value;
+        static_for<16>([&](auto V_) {
+          constexpr int v = decltype(V_)::value;
+          const int row_in = 8 * (v >> 2) + row_l + (v & 3);
+          static_for<NI>([&](auto NI_) {
+            constexpr int ni = decltype(NI_)::value;
+            fst[row_in * FPITCH + ni * 32 + col_l] = acc[mi][ni][v];
+          });
+        });
+        const int c4 = (lane % LPR) * 4, n = wave_n + c4;
+        constexpr int BATCH = ITS < 8 ? ITS : 8;
+        static_for<ITS / BATCH>([&](auto B_) {
+          constexpr int it0 = decltype(B_)::value * BATCH;
+          f32x4_t r4[BATCH];
+          if constexpr (EPI == EPI_RESIDUAL) {
+            static_for<BATCH>([&](auto I_) {
+              constexpr int i = decltype(I_)::value;
+              const int m = wave_m + mi * 32 + (it0 + i) * RPI + lane / LPR;
+              r4[i] = (m < g.M && n < g.N) ? *(const f32x4_t*)(res + (int64_t)m * g.ldo + n) : f32x4_t{0.f, 0.f, 0.f, 0.f};
+            });
+          }
+          static_for<BATCH>([&](auto I_) {
+            constexpr int i = decltype(I_)::value;
+            const int row_in = (it0 + i) * RPI + lane / LPR;
+            const int m = wave_m + mi * 32 + row_in;
+            f32x4_t x = *(const f32x4_t*)(fst + row_in * FPITCH + c4);
+            if constexpr (EPI == EPI_RESIDUAL) x += r4[i];
+            if (m < g.M && n < g.N) *(f32x4_t*)(out + (int64_t)m * g.ldo + n) = x;
+          });
+        });
+      });
+    } else {
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
+      for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int m = wave_m + mi * 32 + 8 * (v >> 2) + row_l + (v & 3);
-        if (m < g.M) {
+        for (int v = 0; v < 16; ++v) {
+          const int m = wave_m + mi * 32 + 8 * (v >> 2) + row_l + (v & 3);
+          if (m < g.M) {
 #pragma unroll
-          for (int ni = 0; ni < NI; ++ni) {
-            const int n = wave_n + ni * 32 + col_l;
-            if (n < g.N) {
-              const int64_t idx = (int64_t)m * g.ldo + n;
-              float x = acc[mi][ni][v];
-              if constexpr (EPI == EPI_RESIDUAL) x += res[idx];
-              out[idx] = x;
+            for (int ni = 0; ni < NI; ++ni) {
+              const int n = wave_n + ni * 32 + col_l;
+              if (n < g.N) {
+                const int64_t idx = (int64_t)m * g.ldo + n;
+                float x = acc[mi][ni][v];
+                if constexpr (EPI == EPI_RESIDUAL) x += res[idx];
+                out[idx] = x;
+              }
             }
           }
         }
-      }
+    }
   } else if constexpr (EPI == EPI_SWIGLU) {
     bf16_t* o = (bf16_t*)g.olp + b * g.olp_bstride;
     const int ldo = g.N >> 1;
+    if constexpr (STAGED) {
+      // 32 rows at a time: products go to the wavefront's LDS patch as bf16, come back as 16-byte
+      // row pieces and leave as full 128-byte lines
+      constexpr int OC = TN / 2, PITCH = OC + 8, LPR = OC / 8, RPI = 64 / LPR;
+      static_assert(32 * PITCH <= STAGE_ELEMS, "staging patch too small");
+      static_for<MI>([&](auto MI_) {
+        constexpr int mi = decltype(MI_)::value;
+        static_for<16>([&](auto V_) {
+          constexpr int v = decltype(V_)::value;
+          const int row_in = 8 * (v >> 2) + row_l + (v & 3);
+          static_for<NI / 2>([&](auto P_) {
+            constexpr int pp = decltype(P_)::value;
+            stage[row_in * PITCH + 32 * pp + col_l] = f32_to_bf16(silu_fast(acc[mi][2 * pp][v]) * acc[mi][2 * pp + 1][v]);
+          });
+          if constexpr ((v & 3) == 3) __builtin_amdgcn_sched_barrier(0);   // bounds the scheduler's window (register pressure)
+        });
+        static_for<32 / RPI>([&](auto IT_) {
+          constexpr int it = decltype(IT_)::value;
+          const int row_in = it * RPI + lane / LPR, chunk = lane % LPR;
+          const u32x4_t val = *(const u32x4_t*)(stage + row_in * PITCH + chunk * 8);
+          const int m = wave_m + mi * 32 + row_in;
+          const int j = (wave_n >> 1) + chunk * 8;
+          if (m < g.M && 2 * j < g.N) *(u32x4_t*)(o + (int64_t)m * ldo + j) = val;
+        });
+      });
+    } else {
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
+      for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int m = wave_m + mi * 32 + 8 * (v >> 2) + row_l + (v & 3);
-        if (m < g.M) {
+        for (int v = 0; v < 16; ++v) {
+          const int m = wave_m + mi * 32 + 8 * (v >> 2) + row_l + (v & 3);
+          if (m < g.M) {
 #pragma unroll
-          for (int ni = 0; ni < NI; ni += 2) {
-            const int j = ((wave_n + ni * 32) >> 1) + col_l;   // (phys/64)*32 + lane column
-            if (2 * j < g.N) o[(int64_t)m * ldo + j] = f32_to_bf16(silu_f(acc[mi][ni][v]) * acc[mi][ni + 1][v]);
+            for (int ni = 0; ni < NI; ni += 2) {
+              const int j = ((wave_n + ni * 32) >> 1) + col_l;   // (phys/64)*32 + lane column
+              if (2 * j < g.N) o[(int64_t)m * ldo + j] = f32_to_bf16(silu_fast(acc[mi][ni][v]) * acc[mi][ni + 1][v]);
+            }
           }
         }
-      }
+    }
   } else {  // EPI_QKV
     const int hd = g.hd, half = hd >> 1, hq = g.H * hd, hk = g.Hkv * hd;
-    const int pstep = hd >> 6;   // partner tile distance: (hd/2)/32
-    const bool s4 = (g.S & 3) == 0;
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-      for (int vg = 0; vg < 4; ++vg) {
-        const int mb = wave_m + mi * 32 + 8 * vg + row_l;   // 4 consecutive rows mb..mb+3
+    const bool wide = hd == 128;     // partner tile distance (hd/2)/32: 1 for hd 64, 2 for hd 128
+    const bool s4 = (g.S & 3) == 0;  // 4 consecutive rows of a register group lie in one sequence
+    static_for<MI>([&](auto MI_) {
+      constexpr int mi = decltype(MI_)::value;
+      static_for<4>([&](auto VG_) {
+        constexpr int vg = decltype(VG_)::value;
+        const int mb = wave_m + mi * 32 + 8 * vg + row_l;   // rows mb .. mb+3
         int seq4 = 0, pos4 = 0;
         if (s4) {
           seq4 = mb / g.S;
           pos4 = g.pos0 + (mb - seq4 * g.S);
         }
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni) {
-          const int nb = wave_n + ni * 32;   // first column of this 32-wide tile
-          if (nb >= g.N) continue;
+        static_for<NI>([&](auto NI_) {
+          constexpr int ni = decltype(NI_)::value;
+          const int nb = wave_n + ni * 32;   // first column of this 32-wide tile (wave-uniform)
           if (nb < hq + hk) {
+            // q or k: rotate (u_j, u_{j+hd/2}); the low half owns the pair
             const bool is_q = nb < hq;
             const int c = is_q ? nb : nb - hq;
             const int head = c / hd, jb = c - head * hd;
-            if (jb >= half) continue;   // written together with its low-half partner
-            const int j = jb + col_l;
-            if (ni + pstep < NI) {
-#pragma unroll
-              for (int r = 0; r < 4; ++r) {
+            if (jb < half && nb < g.N) {
+              const int j = jb + col_l;
+              constexpr int p1 = ni + 1 < NI ? ni + 1 : ni, p2 = ni + 2 < NI ? ni + 2 : ni;
+              static_for<4>([&](auto R_) {
+                constexpr int r = decltype(R_)::value;
                 const int m = mb + r;
-                if (m >= g.M) break;
-                int seq, pos;
-                if (s4) { seq = seq4; pos = pos4 + r; }
-                else { seq = m / g.S; pos = g.pos0 + (m - seq * g.S); }
-                const float2 cs = ((const float2*)g.rope)[(int64_t)pos * half + j];
-                const float lo = acc[mi][ni][vg * 4 + r];
-                const float hi = pstep == 1 ? acc[mi][ni + 1 < NI ? ni + 1 : ni][vg * 4 + r]
-                                            : acc[mi][ni + 2 < NI ? ni + 2 : ni][vg * 4 + r];
-                const bf16_t rlo = f32_to_bf16(lo * cs.x - hi * cs.y);
-                const bf16_t rhi = f32_to_bf16(hi * cs.x + lo * cs.y);
-                if (is_q) {
-                  bf16_t* q = (bf16_t*)g.olp + b * g.olp_bstride + (int64_t)m * hq + nb + col_l;
-                  q[0] = rlo;
-                  q[half] = rhi;
-                } else {
-                  const int64_t hidx = b * g.kv_bstride + seq * g.kv_seq_stride + head;
-                  bf16_t* k = (bf16_t*)g.kc + hidx * g.kv_head_elems + (int64_t)pos * hd + j;
-                  k[0] = rlo;
-                  k[half] = rhi;
+                if (m < g.M) {
+                  int seq, pos;
+                  if (s4) { seq = seq4; pos = pos4 + r; }
+                  else { seq = m / g.S; pos = g.pos0 + (m - seq * g.S); }
+                  const float2 cs = ((const float2*)g.rope)[(int64_t)pos * half + j];
+                  const float lo = acc[mi][ni][vg * 4 + r];
+                  const float hi = wide ? acc[mi][p2][vg * 4 + r] : acc[mi][p1][vg * 4 + r];
+                  const bf16_t rlo = f32_to_bf16(lo * cs.x - hi * cs.y);
+                  const bf16_t rhi = f32_to_bf16(hi * cs.x + lo * cs.y);
+                  if (is_q) {
+                    bf16_t* q = (bf16_t*)g.olp + b * g.olp_bstride + (int64_t)m * hq + nb + col_l;
+                    q[0] = rlo;
+                    q[half] = rhi;
+                  } else {
+                    const int64_t hidx = b * g.kv_bstride + seq * g.kv_seq_stride + head;
+                    bf16_t* k = (bf16_t*)g.kc + hidx * g.kv_head_elems + (int64_t)pos * hd + j;
+                    k[0] = rlo;
+                    k[half] = rhi;
+                  }
                 }
-              }
+              });
             }
-          } else {
+          } else if (nb < g.N) {
+            // v: transposed store, 4 consecutive positions of one head-dim row
             const int c = nb - hq - hk;
             const int head = c / hd, j = c - head * hd + col_l;
-            if (s4 && mb + 3 < g.M) {
+            if (s4 && mb + 3 < g.M && (pos4 & 3) == 0) {
               const int64_t hidx = b * g.kv_bstride + seq4 * g.kv_seq_stride + head;
               bf16_t* v = (bf16_t*)g.vc + hidx * ((int64_t)hd * g.s_pad) + (int64_t)j * g.s_pad + pos4;
               uint2 pk;
               pk.x = pack_bf16x2(acc[mi][ni][vg * 4 + 0], acc[mi][ni][vg * 4 + 1]);
               pk.y = pack_bf16x2(acc[mi][ni][vg * 4 + 2], acc[mi][ni][vg * 4 + 3]);
-              if ((pos4 & 3) == 0) {
-                *(uint2*)v = pk;
-              } else {
-                v[0] = (bf16_t)(pk.x & 0xffff); v[1] = (bf16_t)(pk.x >> 16);
-                v[2] = (bf16_t)(pk.y & 0xffff); v[3] = (bf16_t)(pk.y >> 16);
-              }
+              *(uint2*)v = pk;
             } else {
-#pragma unroll
-              for (int r = 0; r < 4; ++r) {
+              static_for<4>([&](auto R_) {
+                constexpr int r = decltype(R_)::value;
                 const int m = mb + r;
-                if (m >= g.M) break;
-                const int seq = m / g.S, pos = g.pos0 + (m - seq * g.S);
-                const int64_t hidx = b * g.kv_bstride + seq * g.kv_seq_stride + head;
-                ((bf16_t*)g.vc)[hidx * ((int64_t)hd * g.s_pad) + (int64_t)j * g.s_pad + pos] = f32_to_bf16(acc[mi][ni][vg * 4 + r]);
-              }
+                if (m < g.M) {
+                  const int seq = m / g.S, pos = g.pos0 + (m - seq * g.S);
+                  const int64_t hidx = b * g.kv_bstride + seq * g.kv_seq_stride + head;
+                  ((bf16_t*)g.vc)[hidx * ((int64_t)hd * g.s_pad) + (int64_t)j * g.s_pad + pos] = f32_to_bf16(acc[mi][ni][vg * 4 + r]);
+                }
+              });
             }
           }
-        }
-      }
+        });
+      });
+    });
   }
+  GM_STAMP(3);
 }
 
-template <int BM, int BN, int WM, int WN, int EPI>
+template <int BM, int BN, int WM, int WN, int BK, int EPI>
 static int launch_cfg(const pt_gemm_args& g, hipStream_t s) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
-  const size_t lds = (size_t)2 * (BM + BN) * GM_BK * sizeof(bf16_t);
-  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, EPI>;
+  const size_t lds = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t);
+  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, BK, EPI>;
   static bool attr_set = false;
   if (!attr_set) {
     PT_HIP_CHECK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -329,7 +440,8 @@ static int launch_cfg(const pt_gemm_args& g, hipStream_t s) {
   }
   const int64_t total = (int64_t)tiles_m * tiles_n * g.batch;
   if (total > 0x7fffffff) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "GEMM grid too large");
-  hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(WM * WN * 64), lds, s, g, tiles_m, tiles_n);
+  const unsigned grid = (unsigned)total;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), lds, s, g, tiles_m, tiles_n);
   PT_HIP_CHECK(hipGetLastError());
   return 1;
 }
@@ -337,22 +449,24 @@ static int launch_cfg(const pt_gemm_args& g, hipStream_t s) {
 template <int EPI>
 static int launch_epi(const pt_gemm_args& g, hipStream_t s, int cfg) {
   switch (cfg) {
-    case 0: return launch_cfg<256, 256, 2, 2, EPI>(g, s);
-    case 1: return launch_cfg<256, 256, 4, 2, EPI>(g, s);
-    case 2: return launch_cfg<128, 128, 2, 2, EPI>(g, s);
-    case 3: return launch_cfg<64, 256, 1, 4, EPI>(g, s);
-    case 4: return launch_cfg<128, 256, 2, 2, EPI>(g, s);
-    case 5: return launch_cfg<32, 256, 1, 4, EPI>(g, s);
-    case 6: return launch_cfg<64, 256, 1, 2, EPI>(g, s);
-    default: return launch_cfg<32, 256, 1, 2, EPI>(g, s);
+    case 0: return launch_cfg<256, 256, 2, 2, 64, EPI>(g, s);
+    case 1: return launch_cfg<256, 128, 2, 2, 32, EPI>(g, s);
+    case 2: return launch_cfg<128, 128, 2, 2, 64, EPI>(g, s);
+    case 3: return launch_cfg<64, 256, 1, 4, 64, EPI>(g, s);
+    case 4: return launch_cfg<128, 256, 2, 2, 64, EPI>(g, s);
+    case 5: return launch_cfg<32, 256, 1, 4, 64, EPI>(g, s);
+    case 6: return launch_cfg<64, 256, 1, 2, 64, EPI>(g, s);
+    case 7: return launch_cfg<32, 256, 1, 2, 64, EPI>(g, s);
+    case 8: return launch_cfg<128, 256, 2, 2, 32, EPI>(g, s);
+    default: return launch_cfg<128, 128, 2, 2, 32, EPI>(g, s);
   }
 }
 
 // Tile configuration override for tuning runs: -1 = choose by shape.
 int pt_gemm_mfma_force_cfg = -1;
 
-#define GM_NCFG 8
-static const int kWaveN[GM_NCFG] = {128, 128, 64, 64, 128, 64, 128, 128};   // columns per wavefront
+#define GM_NCFG 10
+static const int kWaveN[GM_NCFG] = {128, 64, 64, 64, 128, 64, 128, 128, 128, 64};   // columns per wavefront
 
 static bool cfg_fits(const pt_gemm_args& g, int cfg) {
   const int wn = kWaveN[cfg];
@@ -368,9 +482,12 @@ static bool cfg_fits(const pt_gemm_args& g, int cfg) {
 int pt_launch_gemm_mfma(const pt_gemm_args& g, hipStream_t s) {
   if (g.dtype != PT_BF16) return 0;
   if (g.M <= 0 || g.N <= 0 || g.batch <= 0) return 1;
-  if (g.K < GM_BK || g.K % GM_BK) return 0;
+  if (g.K < 2 * GM_BK || g.K % (2 * GM_BK)) return 0;
   if ((g.lda & 7) || (g.ldb & 7) || (g.a_bstride & 7) || (g.w_bstride & 7)) return 0;
   if (((uintptr_t)g.A | (uintptr_t)g.W) & 15) return 0;
+  if ((g.epi == EPI_STORE_F32 || g.epi == EPI_RESIDUAL) &&
+      ((g.ldo & 3) || (g.N & 3) || (g.out_bstride & 3) || (g.res_bstride & 3) || (((uintptr_t)g.out | (uintptr_t)g.res) & 15))) return 0;
+  if (g.epi == EPI_SWIGLU && ((g.olp_bstride & 7) || ((uintptr_t)g.olp & 15))) return 0;
   static const int big[] = {0, 4, 2, -1}, mid[] = {4, 2, -1}, m64[] = {3, 6, -1}, m32[] = {5, 7, -1};
   const int* cand;
   if (g.M <= 32) cand = m32;
