@@ -134,6 +134,209 @@ __global__ void __launch_bounds__(256) attn_prefill_mfma_kernel(const pt_attn_ar
     }
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// LDS-tiled variant (prefill lengths that are a multiple of 64).  A workgroup of 4 wavefronts owns 128
+// query rows of one (track, sequence, head); each wavefront 32 of them.  Keys and values are walked in
+// tiles of 64 positions that are staged once per workgroup in LDS (K tile [64][hd], V^T tile [hd][64],
+// 16-byte chunks XOR-swizzled so that 16 lanes reading 16 different rows never share a bank) and read by
+// all four wavefronts; the next tile travels from global memory through registers while the current one
+// is multiplied.  Per tile a wavefront issues 2*hd/16 MFMAs for S^T and hd/32*4 for O^T; the softmax
+// uses one fused multiply-add and one exp2 per score.
+// ------------------------------------------------------------------------------------------------
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+template <int HD>
+__global__ void __launch_bounds__(256, 2) attn_prefill_lds_kernel(const pt_attn_args a) {
+  constexpr int KS = HD / 16;          // MFMAs per 32-key block of S^T
+  constexpr int HB = HD / 32;          // 32-row blocks of O^T
+  constexpr int KCPR = HD / 8;         // 16-byte chunks per K row
+  constexpr int KCH = 64 * KCPR / 256; // K chunks per thread and tile
+  constexpr int VCH = HD * 8 / 256;    // V^T chunks per thread and tile (rows of 64 positions = 8 chunks)
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16_t* Ks = (bf16_t*)smem;              // [2][64][HD]
+  bf16_t* Vs = Ks + 2 * 64 * HD;           // [2][HD][64]
+  auto kswz = [](int row) { return HD == 64 ? ((row >> 1) & 7) : (row & 15); };
+  auto vswz = [](int row) { return (row >> 1) & 7; };
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int qb = gridDim.x - 1 - (int)blockIdx.x;   // heavy (late) query blocks first
+  const int q0 = qb * 128 + wave * 32;
+  const int head = blockIdx.y;
+  const int t = blockIdx.z / a.B, seq = blockIdx.z - t * a.B;
+  const int kvh = head / (a.H / a.Hkv);
+  const int64_t hidx = t * a.kv_bstride + seq * a.kv_seq_stride + kvh;
+  const bf16_t* K = (const bf16_t*)a.kc + hidx * a.kv_head_elems;
+  const bf16_t* Vt = (const bf16_t*)a.vc + hidx * ((int64_t)HD * a.s_pad);
+  const bool active = q0 < a.S;            // the last workgroup of a sequence may be partly empty
+  const int64_t row = (int64_t)seq * a.S + min(q0 + l32, a.S - 1);
+  const int64_t qoff = t * a.q_bstride + row * (a.H * HD) + head * HD;
+
+  bf16x8_t qf[KS];
+#pragma unroll
+  for (int kk = 0; kk < KS; ++kk) qf[kk] = *(const bf16x8_t*)((const bf16_t*)a.q + qoff + kk * 16 + half * 8);
+
+  // staging: K tile chunk id = tid + i*256 -> row id / KCPR, chunk id % KCPR; V^T likewise with 8 chunks per row
+  const bf16_t* k_src[KCH];
+  const bf16_t* v_src[VCH];
+  int k_dst[KCH], v_dst[VCH];
+#pragma unroll
+  for (int i = 0; i < KCH; ++i) {
+    const int id = tid + i * 256, r = id / KCPR, c = id % KCPR;
+    k_src[i] = K + (int64_t)r * HD + c * 8;
+    k_dst[i] = r * HD + ((c ^ kswz(r)) * 8);
+  }
+#pragma unroll
+  for (int i = 0; i < VCH; ++i) {
+    const int id = tid + i * 256, r = id >> 3, c = id & 7;
+    v_src[i] = Vt + (int64_t)r * a.s_pad + c * 8;
+    v_dst[i] = r * 64 + ((c ^ vswz(r)) * 8);
+  }
+  u32x4_t k_reg[KCH], v_reg[VCH];
+
+  // fragment addresses inside a tile
+  const int krow = (l32 & ~12) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);   // MFMA row r of S^T holds key pi(r)
+  int k_fr[2][KS];    // [32-key block][hd step]
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) {
+      const int r = rb * 32 + krow;
+      k_fr[rb][kk] = r * HD + (((kk * 2 + half) ^ kswz(r)) * 8);
+    }
+  int v_fr[4];        // [16-key step]: chunk 2*step + half of row l32 (+32*hb rows: same swizzle since 32 % 16 == 0)
+#pragma unroll
+  for (int st = 0; st < 4; ++st) v_fr[st] = l32 * 64 + (((st * 2 + half) ^ vswz(l32)) * 8);
+
+  const float c_log2 = 1.4426950408889634f / sqrtf((float)HD);
+  f32x16_t oacc[HB];
+#pragma unroll
+  for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) oacc[hb][v] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;   // running max of the raw scores, running sum
+
+  const int ntiles = min((qb * 128 + 128), a.S) / 64;      // key tiles this workgroup walks
+#pragma unroll
+  for (int i = 0; i < KCH; ++i) k_reg[i] = *(const u32x4_t*)(k_src[i]);
+#pragma unroll
+  for (int i = 0; i < VCH; ++i) v_reg[i] = *(const u32x4_t*)(v_src[i]);
+#pragma unroll
+  for (int i = 0; i < KCH; ++i) *(u32x4_t*)(Ks + k_dst[i]) = k_reg[i];
+#pragma unroll
+  for (int i = 0; i < VCH; ++i) *(u32x4_t*)(Vs + v_dst[i]) = v_reg[i];
+  __syncthreads();
+
+  for (int kt = 0; kt < ntiles; ++kt) {
+    const int cur = kt & 1;
+    const bf16_t* Kc = Ks + cur * 64 * HD;
+    const bf16_t* Vc = Vs + cur * HD * 64;
+    const int nxt = min(kt + 1, ntiles - 1);   // the last iteration re-reads its own tile; the copy is unused
+#pragma unroll
+    for (int i = 0; i < KCH; ++i) k_reg[i] = *(const u32x4_t*)(k_src[i] + (int64_t)nxt * 64 * HD);
+#pragma unroll
+    for (int i = 0; i < VCH; ++i) v_reg[i] = *(const u32x4_t*)(v_src[i] + nxt * 64);
+    __builtin_amdgcn_sched_barrier(0);
+
+    if (active && kt * 64 <= q0 + 31) {       // wave-uniform: tiles entirely above the diagonal are skipped
+      f32x16_t s[2];
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s[rb][v] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) {
+          const bf16x8_t kf = *(const bf16x8_t*)(Kc + k_fr[rb][kk]);
+          s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s[rb], 0, 0, 0);
+        }
+      }
+      // register v of block rb: key kt*64 + rb*32 + 16*(v/8) + 8*half + v%8, query q0 + l32
+      if (kt * 64 + 63 > q0) {                // the tile touches the diagonal: mask
+        const int qrel = q0 + l32 - kt * 64;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            if (rb * 32 + 16 * (v >> 3) + 8 * half + (v & 7) > qrel) s[rb][v] = -INFINITY;
+      }
+      float mx = -INFINITY;
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[rb][v]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m_run, mx);
+      const float corr = __builtin_amdgcn_exp2f((m_run - m_new) * c_log2);
+      const float mc = m_new * c_log2;
+      float psum = 0.f;
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          s[rb][v] = __builtin_amdgcn_exp2f(fmaf(s[rb][v], c_log2, -mc));
+          psum += s[rb][v];
+        }
+      l_run = l_run * corr + psum;
+      m_run = m_new;
+      if (__any(corr != 1.0f)) {
+#pragma unroll
+        for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) oacc[hb][v] *= corr;
+      }
+      pk8 pf[4];   // 16-key steps: (rb, u) -> rb*2 + u
+#pragma unroll
+      for (int st = 0; st < 4; ++st)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          pf[st].u[i] = pack_bf16x2(s[st >> 1][8 * (st & 1) + 2 * i], s[st >> 1][8 * (st & 1) + 2 * i + 1]);
+#pragma unroll
+      for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+          const bf16x8_t vf = *(const bf16x8_t*)(Vc + hb * 32 * 64 + v_fr[st]);
+          oacc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[st].v, oacc[hb], 0, 0, 0);
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    bf16_t* Kn = Ks + (cur ^ 1) * 64 * HD;
+    bf16_t* Vn = Vs + (cur ^ 1) * HD * 64;
+#pragma unroll
+    for (int i = 0; i < KCH; ++i) *(u32x4_t*)(Kn + k_dst[i]) = k_reg[i];
+#pragma unroll
+    for (int i = 0; i < VCH; ++i) *(u32x4_t*)(Vn + v_dst[i]) = v_reg[i];
+    __syncthreads();
+  }
+  if (!active) return;
+  const float l = l_run + __shfl_xor(l_run, 32, 64);
+  const float inv = 1.0f / l;
+  bf16_t* orow = (bf16_t*)a.o + qoff;
+#pragma unroll
+  for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+    for (int vg = 0; vg < 4; ++vg) {
+      uint2 pk;
+      pk.x = pack_bf16x2(oacc[hb][vg * 4 + 0] * inv, oacc[hb][vg * 4 + 1] * inv);
+      pk.y = pack_bf16x2(oacc[hb][vg * 4 + 2] * inv, oacc[hb][vg * 4 + 3] * inv);
+      *(uint2*)(orow + hb * 32 + 8 * vg + 4 * half) = pk;
+    }
+}
+
+template <int HD>
+static int launch_lds(const pt_attn_args& a, dim3 grid, hipStream_t s) {
+  const size_t lds = (size_t)2 * (64 * HD + HD * 64) * sizeof(bf16_t);
+  auto kern = attn_prefill_lds_kernel<HD>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    PT_HIP_CHECK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, a);
+  PT_HIP_CHECK(hipGetLastError());
+  return 1;
+}
+
 int pt_launch_attn_prefill_mfma(const pt_attn_args& a, hipStream_t s) {
   if (a.dtype != PT_BF16 || a.pos0 != 0) return 0;
   if (a.hd != 64 && a.hd != 128) return 0;
@@ -142,6 +345,7 @@ int pt_launch_attn_prefill_mfma(const pt_attn_args& a, hipStream_t s) {
   const int64_t z = (int64_t)a.n_tracks * a.B;
   if (z > 65535 || a.H > 65535) return 0;
   dim3 grid((unsigned)((a.S + 127) / 128), (unsigned)a.H, (unsigned)z);
+  if (a.S % 64 == 0 && (a.s_pad & 7) == 0) return a.hd == 64 ? launch_lds<64>(a, grid, s) : launch_lds<128>(a, grid, s);
   if (a.hd == 64)
     hipLaunchKernelGGL(attn_prefill_mfma_kernel<64>, grid, dim3(256), 0, s, a);
   else

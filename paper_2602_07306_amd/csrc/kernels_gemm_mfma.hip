@@ -352,6 +352,83 @@ gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
     const int hd = g.hd, half = hd >> 1, hq = g.H * hd, hk = g.Hkv * hd;
     const bool wide = hd == 128;     // partner tile distance (hd/2)/32: 1 for hd 64, 2 for hd 128
     const bool s4 = (g.S & 3) == 0;  // 4 consecutive rows of a register group lie in one sequence
+    constexpr int QPITCH = TN + 8;   // bf16 elements per staged row of q / k
+    constexpr int VPITCH = 32 + 8;   // bf16 elements per staged V^T row (32 positions)
+    constexpr bool CAN_STAGE = STAGED && 32 * QPITCH <= STAGE_ELEMS && TN * VPITCH <= STAGE_ELEMS;
+    bool staged_done = false;
+    if constexpr (CAN_STAGE) {
+      // Aligned prefill (32-row blocks inside one sequence, positions a multiple of 8): 32 rows at a
+      // time go through the wavefront's LDS patch.  q and k are rotated in registers, staged row-major
+      // and leave as 16-byte row pieces; v is staged transposed and leaves as 16-byte pieces of V^T
+      // rows (8 consecutive positions of one head-dim index).
+      if ((g.S & 31) == 0 && (g.pos0 & 7) == 0 && wave_n < g.N) {
+        staged_done = true;
+        const bool is_qk = wave_n < hq + hk, is_q = wave_n < hq;
+        static_for<MI>([&](auto MI_) {
+          constexpr int mi = decltype(MI_)::value;
+          const int mrow0 = wave_m + mi * 32;           // first row of the block
+          if (mrow0 < g.M) {
+            const int seq = mrow0 / g.S, pos0b = g.pos0 + (mrow0 - seq * g.S);
+            if (is_qk) {
+              static_for<16>([&](auto V_) {
+                constexpr int v = decltype(V_)::value;
+                const int row_in = 8 * (v >> 2) + row_l + (v & 3);
+                const float2* rp = (const float2*)g.rope + (int64_t)(pos0b + row_in) * half + col_l;
+                static_for<NI>([&](auto NI_) {
+                  constexpr int ni = decltype(NI_)::value;
+                  constexpr int p1 = ni + 1 < NI ? ni + 1 : ni, p2 = ni + 2 < NI ? ni + 2 : ni;
+                  const int jb = (wave_n + ni * 32) % hd;   // wave-uniform
+                  if (jb < half) {
+                    const float2 cs = rp[jb];
+                    const float lo = acc[mi][ni][v];
+                    const float hi = wide ? acc[mi][p2][v] : acc[mi][p1][v];
+                    stage[row_in * QPITCH + ni * 32 + col_l] = f32_to_bf16(lo * cs.x - hi * cs.y);
+                    stage[row_in * QPITCH + ni * 32 + col_l + half] = f32_to_bf16(hi * cs.x + lo * cs.y);
+                  }
+                });
+              });
+              constexpr int LPR = TN / 8, RPI = 64 / LPR;
+              const int c8 = (lane % LPR) * 8;
+              const int c = (is_q ? wave_n : wave_n - hq) + c8;       // column inside the q or k section
+              const int head = c / hd, j = c - head * hd;
+              static_for<32 / RPI>([&](auto IT_) {
+                constexpr int it = decltype(IT_)::value;
+                const int row_in = it * RPI + lane / LPR;
+                const u32x4_t val = *(const u32x4_t*)(stage + row_in * QPITCH + c8);
+                if (is_q) {
+                  *(u32x4_t*)((bf16_t*)g.olp + b * g.olp_bstride + (int64_t)(mrow0 + row_in) * hq + c) = val;
+                } else {
+                  const int64_t hidx = b * g.kv_bstride + seq * g.kv_seq_stride + head;
+                  *(u32x4_t*)((bf16_t*)g.kc + hidx * g.kv_head_elems + (int64_t)(pos0b + row_in) * hd + j) = val;
+                }
+              });
+            } else {
+              static_for<4>([&](auto VG_) {
+                constexpr int vg = decltype(VG_)::value;
+                static_for<NI>([&](auto NI_) {
+                  constexpr int ni = decltype(NI_)::value;
+                  uint2 pk;
+                  pk.x = pack_bf16x2(acc[mi][ni][vg * 4 + 0], acc[mi][ni][vg * 4 + 1]);
+                  pk.y = pack_bf16x2(acc[mi][ni][vg * 4 + 2], acc[mi][ni][vg * 4 + 3]);
+                  *(uint2*)(stage + (ni * 32 + col_l) * VPITCH + 8 * vg + row_l) = pk;
+                });
+              });
+              const int p8 = (lane & 3) * 8;
+              static_for<TN / 16>([&](auto IT_) {
+                constexpr int it = decltype(IT_)::value;
+                const int col = it * 16 + (lane >> 2);
+                const u32x4_t val = *(const u32x4_t*)(stage + col * VPITCH + p8);
+                const int c = wave_n - hq - hk + col;
+                const int head = c / hd, j = c - head * hd;
+                const int64_t hidx = b * g.kv_bstride + seq * g.kv_seq_stride + head;
+                *(u32x4_t*)((bf16_t*)g.vc + hidx * ((int64_t)hd * g.s_pad) + (int64_t)j * g.s_pad + pos0b + p8) = val;
+              });
+            }
+          }
+        });
+      }
+    }
+    if (!staged_done)
     static_for<MI>([&](auto MI_) {
       constexpr int mi = decltype(MI_)::value;
       static_for<4>([&](auto VG_) {
@@ -488,12 +565,12 @@ int pt_launch_gemm_mfma(const pt_gemm_args& g, hipStream_t s) {
   if ((g.epi == EPI_STORE_F32 || g.epi == EPI_RESIDUAL) &&
       ((g.ldo & 3) || (g.N & 3) || (g.out_bstride & 3) || (g.res_bstride & 3) || (((uintptr_t)g.out | (uintptr_t)g.res) & 15))) return 0;
   if (g.epi == EPI_SWIGLU && ((g.olp_bstride & 7) || ((uintptr_t)g.olp & 15))) return 0;
-  static const int big[] = {0, 4, 2, -1}, mid[] = {4, 2, -1}, m64[] = {3, 6, -1}, m32[] = {5, 7, -1};
+  static const int big[] = {0, 4, 2, -1}, big_qkv[] = {8, 0, 4, 2, -1}, mid[] = {4, 2, -1}, m64[] = {3, 6, -1}, m32[] = {5, 7, -1};
   const int* cand;
   if (g.M <= 32) cand = m32;
   else if (g.M <= 64) cand = m64;
   else if (g.M <= 128 || (int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256) * g.batch < 200) cand = mid;
-  else cand = big;
+  else cand = g.epi == EPI_QKV ? big_qkv : big;
   int cfg = -1;
   if (pt_gemm_mfma_force_cfg >= 0 && pt_gemm_mfma_force_cfg < GM_NCFG) {
     if (cfg_fits(g, pt_gemm_mfma_force_cfg)) cfg = pt_gemm_mfma_force_cfg;
