@@ -24,6 +24,7 @@ SOURCES = [
     "kernels_weights.hip",
     "kernels_gemm_generic.hip",
     "kernels_gemm_mfma.hip",
+    "kernels_gemm_skinny.hip",
     "kernels_attn_generic.hip",
     "kernels_attn_prefill_mfma.hip",
     "kernels_attn_decode.hip",

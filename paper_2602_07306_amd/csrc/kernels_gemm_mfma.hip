@@ -74,190 +74,36 @@ __device__ __forceinline__ tile_coord decode_tile(int id, int tiles_m, int tiles
   return c;
 }
 
-template <int BM, int BN, int WM, int WN, int BK, int EPI>
-__global__ void __launch_bounds__(WM * WN * 64, (2 * (BM + BN) * BK * 2 <= 80 * 1024 && BM * BN <= 256 * 128 && WM * WN == 4) ? 2 : 1)
-gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
-  constexpr int NT = WM * WN * 64;
-  constexpr int TM = BM / WM, TN = BN / WN, MI = TM / 32, NI = TN / 32;
-  constexpr int CPR = BK / 8;        // 16-byte chunks per LDS row
-  constexpr int SS = BK / 16;        // MFMA sub-steps per K step
-  constexpr int A_CH = BM * CPR / NT, B_CH = BN * CPR / NT;  // 16-byte chunks per thread and K step
-  static_assert(BK == 64 || BK == 32, "K step");
-  static_assert(BM * CPR % NT == 0 && BN * CPR % NT == 0, "tile/threads mismatch");
-  // XOR swizzle of the 16-byte chunks: any 16 consecutive rows reading the same logical chunk hit 16
-  // different 16-byte columns of a 256-byte LDS line (gfx950 serves 16 lanes x 16 B per clock)
-  auto SWZ = [](int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); };
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  bf16_t* As = (bf16_t*)smem;            // [2][BM][BK]
-  bf16_t* Bs = As + 2 * BM * BK;      // [2][BN][BK]
-
-  GM_STAMP(0);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / WN, wn = wave % WN;
-  const tile_coord tc = decode_tile(logical_tile(blockIdx.x, gridDim.x), tiles_m, tiles_n);
-  const int m0 = tc.tm * BM, n0 = tc.tn * BN, b = tc.b;
-
-  // global -> register staging: chunk id = tid + i*NT; row = id/CPR, 16-byte chunk = id%CPR.
-  // Rows of one thread are NT/CPR apart, a multiple of 16, so they share the swizzle and the LDS
-  // destinations differ by a constant.
-  const int ld_row = tid / CPR, ld_ch = tid % CPR;
-  static_assert((NT / CPR) % 16 == 0, "staging rows must keep the swizzle");
-  constexpr int ST_STRIDE = (NT / CPR) * BK;                    // elements between a thread's staging rows
-  const int st_dst = ld_row * BK + ((ld_ch ^ SWZ(ld_row)) * 8);
-  u32x4_t a_reg[2][A_CH], w_reg[2][B_CH];                        // two staging sets: K steps of equal parity
-
-  const int KT = g.K / BK;   // even, >= 2
-  uint32_t a_voff[A_CH], w_voff[B_CH];   // byte offsets from the tile's first row
-#pragma unroll
-  for (int i = 0; i < A_CH; ++i) {
-    const int gr = min(m0 + ld_row + i * (NT / CPR), g.M - 1) - m0;
-    a_voff[i] = (uint32_t)((gr * g.lda + ld_ch * 8) * 2);
-  }
-#pragma unroll
-  for (int i = 0; i < B_CH; ++i) {
-    const int gr = min(n0 + ld_row + i * (NT / CPR), g.N - 1) - n0;
-    w_voff[i] = (uint32_t)((gr * g.ldb + ld_ch * 8) * 2);
-  }
-  const char* a_base = (const char*)((const bf16_t*)g.A + b * g.a_bstride + (int64_t)m0 * g.lda);   // wave-uniform
-  const char* w_base = (const char*)((const bf16_t*)g.W + b * g.w_bstride + (int64_t)n0 * g.ldb);
-  auto load_a = [&](int set, int i, int kstep) { a_reg[set][i] = *(const u32x4_t*)(a_base + (size_t)kstep * (BK * 2) + a_voff[i]); };
-  auto load_w = [&](int set, int i, int kstep) { w_reg[set][i] = *(const u32x4_t*)(w_base + (size_t)kstep * (BK * 2) + w_voff[i]); };
-
-  // operand reads: row = tile row + lane%32, 16-byte chunk = 2*kk + lane/32, swizzled by the row
-  const int fr_row = lane & 31, fr_half = lane >> 5, fr_sw = SWZ(lane & 31);
-  int a_fr[SS], b_fr[SS];   // element offsets of sub-step kk inside a buffer, first MFMA tile of the wavefront
-#pragma unroll
-  for (int kk = 0; kk < SS; ++kk) {
-    const int ch = ((kk * 2 + fr_half) ^ fr_sw) * 8;
-    a_fr[kk] = (wm * TM + fr_row) * BK + ch;
-    b_fr[kk] = (wn * TN + fr_row) * BK + ch;
-  }
-
-  // Software pipeline (K step = 64).  In every iteration the MFMAs run out of LDS buffer `cur` while
-  //   sub-steps 0,1: the next K step (staging set cur^1, loaded two iterations ago) is stored into the
-  //                  other LDS buffer,
-  //   sub-steps 2,3: the K step three ahead is loaded from global memory into the set just freed,
-  //   every sub-step: the operand fragments of the next sub-step are read from LDS,
-  // and every memory instruction is issued between two MFMAs, so no queue sees a burst.  The one
-  // barrier of the iteration sits in front of sub-step 3: after it the first fragments of the next
-  // K step are fetched in the shadow of the last MFMAs.
-#pragma unroll
-  for (int i = 0; i < A_CH; ++i) load_a(0, i, 0);
-#pragma unroll
-  for (int i = 0; i < B_CH; ++i) load_w(0, i, 0);
-#pragma unroll
-  for (int i = 0; i < A_CH; ++i) load_a(1, i, 1);
-#pragma unroll
-  for (int i = 0; i < B_CH; ++i) load_w(1, i, 1);
-#pragma unroll
-  for (int i = 0; i < A_CH; ++i) *(u32x4_t*)(As + st_dst + i * ST_STRIDE) = a_reg[0][i];
-#pragma unroll
-  for (int i = 0; i < B_CH; ++i) *(u32x4_t*)(Bs + st_dst + i * ST_STRIDE) = w_reg[0][i];
-#pragma unroll
-  for (int i = 0; i < A_CH; ++i) load_a(0, i, min(2, KT - 1));
-#pragma unroll
-  for (int i = 0; i < B_CH; ++i) load_w(0, i, min(2, KT - 1));
-  __syncthreads();
-
-  GM_STAMP(1);
-  bf16x8_t af[2][MI], bfr[2][NI];
-#pragma unroll
-  for (int mi = 0; mi < MI; ++mi) af[0][mi] = *(const bf16x8_t*)(As + a_fr[0] + mi * 32 * BK);
-#pragma unroll
-  for (int ni = 0; ni < NI; ++ni) bfr[0][ni] = *(const bf16x8_t*)(Bs + b_fr[0] + ni * 32 * BK);
-
-  constexpr int NM = MI * NI;                  // MFMAs per sub-step
-  constexpr int FR = MI + NI;                  // fragment reads per sub-step
-  constexpr int EX = A_CH + B_CH;              // staging chunks per K step
-  constexpr int HS = SS / 2;                   // sub-steps that store, then as many that load
-  constexpr int EXH = (EX + HS - 1) / HS;      // staging chunks handled per sub-step
-
-  f32x16_t acc[MI][NI];
-
-  auto iteration = [&](auto PAR, int kt) {
-    constexpr int cur = decltype(PAR)::value;          // LDS buffer being multiplied
-    constexpr int wset = cur ^ 1;                       // staging set stored, then reloaded
-    const bf16_t* Ac = As + cur * BM * BK;
-    const bf16_t* Bc = Bs + cur * BN * BK;
-    bf16_t* An = As + (cur ^ 1) * BM * BK;
-    bf16_t* Bn = Bs + (cur ^ 1) * BN * BK;
-    const int kload = min(kt + 3, KT - 1);   // K steps past the end re-read the last one (never multiplied)
-    static_for<SS>([&](auto KK) {
-      constexpr int kk = decltype(KK)::value;
-      constexpr int fb = (kk + 1) & 1;                  // fragment buffer being filled
-      constexpr int R = FR + EXH;                       // memory instructions of this sub-step
-      if constexpr (kk == SS - 1) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-      static_for<NM>([&](auto J) {
-        constexpr int j = decltype(J)::value;
-        constexpr int mi = j / NI, ni = j % NI;
-        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][mi], bfr[kk & 1][ni], acc[mi][ni], 0, 0, 0);
-        constexpr int lo = j * R / NM, hi = (j + 1) * R / NM;
-        static_for<hi - lo>([&](auto RR) {
-          constexpr int r = lo + decltype(RR)::value;
-          if constexpr (r < MI) {
-            const bf16_t* src = kk == SS - 1 ? An + a_fr[0] : Ac + a_fr[(kk + 1) % SS];
-            af[fb][r] = *(const bf16x8_t*)(src + r * 32 * BK);
-          } else if constexpr (r < FR) {
-            const bf16_t* src = kk == SS - 1 ? Bn + b_fr[0] : Bc + b_fr[(kk + 1) % SS];
-            bfr[fb][r - MI] = *(const bf16x8_t*)(src + (r - MI) * 32 * BK);
-          } else {
-            constexpr int e = (kk % HS) * EXH + (r - FR);   // staging chunk
-            if constexpr (e < EX) {
-              if constexpr (kk < HS) {
-                if constexpr (e < A_CH) *(u32x4_t*)(An + st_dst + e * ST_STRIDE) = a_reg[wset][e];
-                else *(u32x4_t*)(Bn + st_dst + (e - A_CH) * ST_STRIDE) = w_reg[wset][e - A_CH];
-              } else {
-                if constexpr (e < A_CH) load_a(wset, e, kload);
-                else load_w(wset, e - A_CH, kload);
-              }
-            }
-          }
-        });
-        __builtin_amdgcn_sched_barrier(0);
-      });
-    });
-  };
-
-#pragma unroll
-  for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
-  for (int kt = 0; kt < KT; kt += 2) {
-    iteration(std::integral_constant<int, 0>{}, kt);
-    iteration(std::integral_constant<int, 1>{}, kt + 1);
-  }
-  __syncthreads();   // LDS is free for the staged epilogues
-  GM_STAMP(2);
-
-  // ------------------------------------------------------------------ epilogue
+// ------------------------------------------------------------------------------------------------
+// Fused epilogues on the accumulator layout of 32x32 MFMA tiles (lane l: column l%32; register v: row
+// 8*(v/4) + 4*(l/32) + v%4).  `stage` is the wavefront's private LDS patch (STAGE_ELEMS bf16 elements),
+// usable once the K loop is over; wave_m / wave_n are the first row / column of the wavefront's tile.
+// ------------------------------------------------------------------------------------------------
+template <int MI, int NI, int EPI, bool STAGED, int STAGE_ELEMS>
+__device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&acc)[MI][NI], bf16_t* stage, int b,
+                                              int wave_m, int wave_n, int lane) {
+  constexpr int TN = NI * 32;
   const int col_l = lane & 31;
   const int row_l = 4 * (lane >> 5);
-  // LDS patch of this wavefront for the staged epilogues (the K loop is over: all of LDS is free)
-  constexpr bool STAGED = BM >= 128 && BN >= 128;
-  constexpr int STAGE_ELEMS = 2 * (BM + BN) * BK / (WM * WN);   // per wavefront
-  bf16_t* stage = (bf16_t*)smem + wave * STAGE_ELEMS;
   (void)stage;
-  const int wave_n = n0 + wn * TN;
-  const int wave_m = m0 + wm * TM;
-
   if constexpr (EPI == EPI_STORE_F32 || EPI == EPI_RESIDUAL) {
     float* out = g.out + b * g.out_bstride;
     const float* res = EPI == EPI_RESIDUAL ? g.res + b * g.res_bstride : nullptr;
     constexpr int FPITCH = TN + 8;   // floats; +8 keeps the two half-waves on disjoint banks
-    if constexpr (STAGED && 32 * FPITCH * 2 <= STAGE_ELEMS) {
-      // 32 rows at a time through the wavefront's LDS patch: the accumulator layout (a lane owns a
+    constexpr int RCH = 32 * FPITCH * 2 <= STAGE_ELEMS ? 32 : 16;   // rows staged at a time
+    if constexpr (STAGED && RCH * FPITCH * 2 <= STAGE_ELEMS) {
+      // RCH rows at a time through the wavefront's LDS patch: the accumulator layout (a lane owns a
       // column) becomes row pieces of 4 floats, so the residual read-modify-write moves 16 bytes per
       // lane and whole 128-byte lines per row
       float* fst = (float*)stage;
-      constexpr int LPR = TN / 4, RPI = 64 / LPR, ITS = 32 / RPI;
+      constexpr int LPR = TN / 4, RPI = 64 / LPR, ITS = RCH / RPI;
       typedef float f32x4_t __attribute__((ext_vector_type(4)));
-      static_for<MI>([&](auto MI_) {
-        constexpr int mi = decltype(MI_)::value;
-        static_for<16>([&](auto V_) {
-          constexpr int v = decltype(V_)::value;
-          const int row_in = 8 * (v >> 2) + row_l + (v & 3);
+      static_for<MI * (32 / RCH)>([&](auto C_) {
+        constexpr int mi = decltype(C_)::value / (32 / RCH), rc = decltype(C_)::value % (32 / RCH);
+        constexpr int row0 = rc * RCH;                 // first row of the chunk inside the 32-row block
+        static_for<RCH / 2>([&](auto V_) {
+          constexpr int v = (row0 / 8) * 4 + decltype(V_)::value;     // registers whose rows lie in the chunk
+          const int row_in = 8 * (v >> 2) + row_l + (v & 3) - row0;
           static_for<NI>([&](auto NI_) {
             constexpr int ni = decltype(NI_)::value;
             fst[row_in * FPITCH + ni * 32 + col_l] = acc[mi][ni][v];
@@ -271,14 +117,14 @@ gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
           if constexpr (EPI == EPI_RESIDUAL) {
             static_for<BATCH>([&](auto I_) {
               constexpr int i = decltype(I_)::value;
-              const int m = wave_m + mi * 32 + (it0 + i) * RPI + lane / LPR;
+              const int m = wave_m + mi * 32 + row0 + (it0 + i) * RPI + lane / LPR;
               r4[i] = (m < g.M && n < g.N) ? *(const f32x4_t*)(res + (int64_t)m * g.ldo + n) : f32x4_t{0.f, 0.f, 0.f, 0.f};
             });
           }
           static_for<BATCH>([&](auto I_) {
             constexpr int i = decltype(I_)::value;
             const int row_in = (it0 + i) * RPI + lane / LPR;
-            const int m = wave_m + mi * 32 + row_in;
+            const int m = wave_m + mi * 32 + row0 + row_in;
             f32x4_t x = *(const f32x4_t*)(fst + row_in * FPITCH + c4);
             if constexpr (EPI == EPI_RESIDUAL) x += r4[i];
             if (m < g.M && n < g.N) *(f32x4_t*)(out + (int64_t)m * g.ldo + n) = x;
@@ -502,7 +348,326 @@ gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
       });
     });
   }
+}
+
+template <int BM, int BN, int WM, int WN, int BK, int EPI>
+__global__ void __launch_bounds__(WM * WN * 64, (2 * (BM + BN) * BK * 2 <= 80 * 1024 && BM * BN <= 256 * 128 && WM * WN == 4) ? 2 : 1)
+gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
+  constexpr int NT = WM * WN * 64;
+  constexpr int TM = BM / WM, TN = BN / WN, MI = TM / 32, NI = TN / 32;
+  constexpr int CPR = BK / 8;        // 16-byte chunks per LDS row
+  constexpr int SS = BK / 16;        // MFMA sub-steps per K step
+  constexpr int A_CH = BM * CPR / NT, B_CH = BN * CPR / NT;  // 16-byte chunks per thread and K step
+  static_assert(BK == 64 || BK == 32, "K step");
+  static_assert(BM * CPR % NT == 0 && BN * CPR % NT == 0, "tile/threads mismatch");
+  // XOR swizzle of the 16-byte chunks: any 16 consecutive rows reading the same logical chunk hit 16
+  // different 16-byte columns of a 256-byte LDS line (gfx950 serves 16 lanes x 16 B per clock)
+  auto SWZ = [](int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); };
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16_t* As = (bf16_t*)smem;            // [2][BM][BK]
+  bf16_t* Bs = As + 2 * BM * BK;      // [2][BN][BK]
+
+  GM_STAMP(0);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  const tile_coord tc = decode_tile(logical_tile(blockIdx.x, gridDim.x), tiles_m, tiles_n);
+  const int m0 = tc.tm * BM, n0 = tc.tn * BN, b = tc.b;
+
+  // global -> register staging: chunk id = tid + i*NT; row = id/CPR, 16-byte chunk = id%CPR.
+  // Rows of one thread are NT/CPR apart, a multiple of 16, so they share the swizzle and the LDS
+  // destinations differ by a constant.
+  const int ld_row = tid / CPR, ld_ch = tid % CPR;
+  static_assert((NT / CPR) % 16 == 0, "staging rows must keep the swizzle");
+  constexpr int ST_STRIDE = (NT / CPR) * BK;                    // elements between a thread's staging rows
+  const int st_dst = ld_row * BK + ((ld_ch ^ SWZ(ld_row)) * 8);
+  u32x4_t a_reg[2][A_CH], w_reg[2][B_CH];                        // two staging sets: K steps of equal parity
+
+  const int KT = g.K / BK;   // even, >= 2
+  uint32_t a_voff[A_CH], w_voff[B_CH];   // byte offsets from the tile's first row
+#pragma unroll
+  for (int i = 0; i < A_CH; ++i) {
+    const int gr = min(m0 + ld_row + i * (NT / CPR), g.M - 1) - m0;
+    a_voff[i] = (uint32_t)((gr * g.lda + ld_ch * 8) * 2);
+  }
+#pragma unroll
+  for (int i = 0; i < B_CH; ++i) {
+    const int gr = min(n0 + ld_row + i * (NT / CPR), g.N - 1) - n0;
+    w_voff[i] = (uint32_t)((gr * g.ldb + ld_ch * 8) * 2);
+  }
+  const char* a_base = (const char*)((const bf16_t*)g.A + b * g.a_bstride + (int64_t)m0 * g.lda);   // wave-uniform
+  const char* w_base = (const char*)((const bf16_t*)g.W + b * g.w_bstride + (int64_t)n0 * g.ldb);
+  auto load_a = [&](int set, int i, int kstep) { a_reg[set][i] = *(const u32x4_t*)(a_base + (size_t)kstep * (BK * 2) + a_voff[i]); };
+  auto load_w = [&](int set, int i, int kstep) { w_reg[set][i] = *(const u32x4_t*)(w_base + (size_t)kstep * (BK * 2) + w_voff[i]); };
+
+  // operand reads: row = tile row + lane%32, 16-byte chunk = 2*kk + lane/32, swizzled by the row
+  const int fr_row = lane & 31, fr_half = lane >> 5, fr_sw = SWZ(lane & 31);
+  int a_fr[SS], b_fr[SS];   // element offsets of sub-step kk inside a buffer, first MFMA tile of the wavefront
+#pragma unroll
+  for (int kk = 0; kk < SS; ++kk) {
+    const int ch = ((kk * 2 + fr_half) ^ fr_sw) * 8;
+    a_fr[kk] = (wm * TM + fr_row) * BK + ch;
+    b_fr[kk] = (wn * TN + fr_row) * BK + ch;
+  }
+
+  // Software pipeline (K step = 64).  In every iteration the MFMAs run out of LDS buffer `cur` while
+  //   sub-steps 0,1: the next K step (staging set cur^1, loaded two iterations ago) is stored into the
+  //                  other LDS buffer,
+  //   sub-steps 2,3: the K step three ahead is loaded from global memory into the set just freed,
+  //   every sub-step: the operand fragments of the next sub-step are read from LDS,
+  // and every memory instruction is issued between two MFMAs, so no queue sees a burst.  The one
+  // barrier of the iteration sits in front of sub-step 3: after it the first fragments of the next
+  // K step are fetched in the shadow of the last MFMAs.
+#pragma unroll
+  for (int i = 0; i < A_CH; ++i) load_a(0, i, 0);
+#pragma unroll
+  for (int i = 0; i < B_CH; ++i) load_w(0, i, 0);
+#pragma unroll
+  for (int i = 0; i < A_CH; ++i) load_a(1, i, 1);
+#pragma unroll
+  for (int i = 0; i < B_CH; ++i) load_w(1, i, 1);
+#pragma unroll
+  for (int i = 0; i < A_CH; ++i) *(u32x4_t*)(As + st_dst + i * ST_STRIDE) = a_reg[0][i];
+#pragma unroll
+  for (int i = 0; i < B_CH; ++i) *(u32x4_t*)(Bs + st_dst + i * ST_STRIDE) = w_reg[0][i];
+#pragma unroll
+  for (int i = 0; i < A_CH; ++i) load_a(0, i, min(2, KT - 1));
+#pragma unroll
+  for (int i = 0; i < B_CH; ++i) load_w(0, i, min(2, KT - 1));
+  __syncthreads();
+
+  GM_STAMP(1);
+  bf16x8_t af[2][MI], bfr[2][NI];
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi) af[0][mi] = *(const bf16x8_t*)(As + a_fr[0] + mi * 32 * BK);
+#pragma unroll
+  for (int ni = 0; ni < NI; ++ni) bfr[0][ni] = *(const bf16x8_t*)(Bs + b_fr[0] + ni * 32 * BK);
+
+  constexpr int NM = MI * NI;                  // MFMAs per sub-step
+  constexpr int FR = MI + NI;                  // fragment reads per sub-step
+  constexpr int EX = A_CH + B_CH;              // staging chunks per K step
+  constexpr int HS = SS / 2;                   // sub-steps that store, then as many that load
+  constexpr int EXH = (EX + HS - 1) / HS;      // staging chunks handled per sub-step
+
+  f32x16_t acc[MI][NI];
+
+  auto iteration = [&](auto PAR, int kt) {
+    constexpr int cur = decltype(PAR)::value;          // LDS buffer being multiplied
+    constexpr int wset = cur ^ 1;                       // staging set stored, then reloaded
+    const bf16_t* Ac = As + cur * BM * BK;
+    const bf16_t* Bc = Bs + cur * BN * BK;
+    bf16_t* An = As + (cur ^ 1) * BM * BK;
+    bf16_t* Bn = Bs + (cur ^ 1) * BN * BK;
+    const int kload = min(kt + 3, KT - 1);   // K steps past the end re-read the last one (never multiplied)
+    static_for<SS>([&](auto KK) {
+      constexpr int kk = decltype(KK)::value;
+      constexpr int fb = (kk + 1) & 1;                  // fragment buffer being filled
+      constexpr int R = FR + EXH;                       // memory instructions of this sub-step
+      if constexpr (kk == SS - 1) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+      static_for<NM>([&](auto J) {
+        constexpr int j = decltype(J)::value;
+        constexpr int mi = j / NI, ni = j % NI;
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][mi], bfr[kk & 1][ni], acc[mi][ni], 0, 0, 0);
+        constexpr int lo = j * R / NM, hi = (j + 1) * R / NM;
+        static_for<hi - lo>([&](auto RR) {
+          constexpr int r = lo + decltype(RR)::value;
+          if constexpr (r < MI) {
+            const bf16_t* src = kk == SS - 1 ? An + a_fr[0] : Ac + a_fr[(kk + 1) % SS];
+            af[fb][r] = *(const bf16x8_t*)(src + r * 32 * BK);
+          } else if constexpr (r < FR) {
+            const bf16_t* src = kk == SS - 1 ? Bn + b_fr[0] : Bc + b_fr[(kk + 1) % SS];
+            bfr[fb][r - MI] = *(const bf16x8_t*)(src + (r - MI) * 32 * BK);
+          } else {
+            constexpr int e = (kk % HS) * EXH + (r - FR);   // staging chunk
+            if constexpr (e < EX) {
+              if constexpr (kk < HS) {
+                if constexpr (e < A_CH) *(u32x4_t*)(An + st_dst + e * ST_STRIDE) = a_reg[wset][e];
+                else *(u32x4_t*)(Bn + st_dst + (e - A_CH) * ST_STRIDE) = w_reg[wset][e - A_CH];
+              } else {
+                if constexpr (e < A_CH) load_a(wset, e, kload);
+                else load_w(wset, e - A_CH, kload);
+              }
+            }
+          }
+        });
+        __builtin_amdgcn_sched_barrier(0);
+      });
+    });
+  };
+
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
+  for (int kt = 0; kt < KT; kt += 2) {
+    iteration(std::integral_constant<int, 0>{}, kt);
+    iteration(std::integral_constant<int, 1>{}, kt + 1);
+  }
+  __syncthreads();   // LDS is free for the staged epilogues
+  GM_STAMP(2);
+
+  // ------------------------------------------------------------------ epilogue
+  // LDS patch of this wavefront for the staged epilogues (the K loop is over: all of LDS is free)
+  constexpr bool STAGED = BM >= 128 && BN >= 128;
+  constexpr int STAGE_ELEMS = 2 * (BM + BN) * BK / (WM * WN);   // per wavefront
+  bf16_t* stage = (bf16_t*)smem + wave * STAGE_ELEMS;
+  (void)stage;
+  const int wave_n = n0 + wn * TN;
+  const int wave_m = m0 + wm * TM;
+
+  gemm_epilogue<MI, NI, EPI, STAGED, STAGE_ELEMS>(g, acc, stage, b, wave_m, wave_n, lane);
   GM_STAMP(3);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Variant with direct global -> LDS loads (gfx950 global_load_lds_dwordx4): operand tiles never touch
+// registers on their way in.  K step 32, four LDS stages; the loads of K step kt+3 are issued while
+// step kt is multiplied, so three steps are always in flight.  A wavefront instruction moves 64 x 16
+// bytes into 1024 consecutive LDS bytes = 16 rows of 64 bytes; lane L therefore fetches, for row L/4,
+// the logical chunk (L%4) ^ swizzle(row), which yields the same conflict-free swizzled layout as the
+// register-staged kernel.  With 8 wavefronts (2 per SIMD, 128 accumulator registers each) one
+// wavefront's LDS and barrier waits are covered by the other's MFMAs.
+// ------------------------------------------------------------------------------------------------
+template <int BM, int BN, int WM, int WN, int EPI>
+__global__ void __launch_bounds__(WM * WN * 64, WM * WN == 8 ? 2 : 1)
+gemm_dl_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
+  constexpr int BK = 32, NSTG = 4, NW = WM * WN;
+  constexpr int TM = BM / WM, TN = BN / WN, MI = TM / 32, NI = TN / 32;
+  constexpr int STG = (BM + BN) * BK;                 // elements per stage: A rows then W rows
+  constexpr int LA = BM / 16 / NW, LB = BN / 16 / NW; // 16-row groups (= load instructions) per wavefront and K step
+  static_assert(BM / 16 % NW == 0 && BN / 16 % NW == 0, "tile/wavefront mismatch");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16_t* lds = (bf16_t*)smem;
+  auto SWZ = [](int row) { return (row >> 2) & 3; };
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  const tile_coord tc = decode_tile(logical_tile(blockIdx.x, gridDim.x), tiles_m, tiles_n);
+  const int m0 = tc.tm * BM, n0 = tc.tn * BN, b = tc.b;
+  const int KT = g.K / BK;   // multiple of 4
+
+  // direct loads: group grp covers tile rows grp*16 .. +15; this lane fetches row L/4, logical chunk (L%4)^swz
+  const int rr = lane >> 2, pc = lane & 3;
+  uint32_t a_voff[LA], w_voff[LB];
+#pragma unroll
+  for (int i = 0; i < LA; ++i) {
+    const int row = (wave * LA + i) * 16 + rr;
+    const int gr = min(m0 + row, g.M - 1) - m0;
+    a_voff[i] = (uint32_t)((gr * g.lda + (pc ^ SWZ(row)) * 8) * 2);
+  }
+#pragma unroll
+  for (int i = 0; i < LB; ++i) {
+    const int row = (wave * LB + i) * 16 + rr;
+    const int gr = min(n0 + row, g.N - 1) - n0;
+    w_voff[i] = (uint32_t)((gr * g.ldb + (pc ^ SWZ(row)) * 8) * 2);
+  }
+  const char* a_base = (const char*)((const bf16_t*)g.A + b * g.a_bstride + (int64_t)m0 * g.lda);
+  const char* w_base = (const char*)((const bf16_t*)g.W + b * g.w_bstride + (int64_t)n0 * g.ldb);
+  typedef const __attribute__((address_space(1))) void* gptr_t;
+  typedef __attribute__((address_space(3))) void* lptr_t;
+  auto issue_load = [&](int i, int kstep, int stage) {   // i < LA: A group, else W group
+    if (i < LA)
+      __builtin_amdgcn_global_load_lds((gptr_t)(a_base + (size_t)kstep * (BK * 2) + a_voff[i]),
+                                       (lptr_t)(lds + stage * STG + (wave * LA + i) * 16 * BK), 16, 0, 0);
+    else
+      __builtin_amdgcn_global_load_lds((gptr_t)(w_base + (size_t)kstep * (BK * 2) + w_voff[i - LA]),
+                                       (lptr_t)(lds + stage * STG + BM * BK + (wave * LB + (i - LA)) * 16 * BK), 16, 0, 0);
+  };
+
+  // operand fragments: row = tile row + lane%32, 16-byte chunk = 2*kk + lane/32, swizzled by the row
+  const int fr_row = lane & 31, fr_half = lane >> 5;
+  int a_fr[2], b_fr[2];
+#pragma unroll
+  for (int kk = 0; kk < 2; ++kk) {
+    const int ra = wm * TM + fr_row, rb = wn * TN + fr_row;
+    a_fr[kk] = ra * BK + (((kk * 2 + fr_half) ^ SWZ(ra)) * 8);
+    b_fr[kk] = BM * BK + rb * BK + (((kk * 2 + fr_half) ^ SWZ(rb)) * 8);
+  }
+
+  f32x16_t acc[MI][NI];
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
+
+  constexpr int LPW = LA + LB;   // loads per wavefront and K step
+#pragma unroll
+  for (int st = 0; st < 3; ++st)
+#pragma unroll
+    for (int i = 0; i < LPW; ++i) issue_load(i, min(st, KT - 1), st);
+  // K step 0 has landed once at most the two younger steps are outstanding
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(2 * LPW) : "memory");
+
+  bf16x8_t af[2][MI], bfr[2][NI];
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi) af[0][mi] = *(const bf16x8_t*)(lds + a_fr[0] + mi * 32 * BK);
+#pragma unroll
+  for (int ni = 0; ni < NI; ++ni) bfr[0][ni] = *(const bf16x8_t*)(lds + b_fr[0] + ni * 32 * BK);
+
+  constexpr int NM = MI * NI, FR = MI + NI;
+  auto iteration = [&](auto STAGE, int kt) {
+    constexpr int st = decltype(STAGE)::value;            // stage being multiplied = kt % 4
+    const bf16_t* cur = lds + st * STG;
+    const bf16_t* nxt = lds + ((st + 1) & 3) * STG;
+    const int kload = min(kt + 3, KT - 1);                 // steps past the end re-read the last one into a dead stage
+    static_for<2>([&](auto KK) {
+      constexpr int kk = decltype(KK)::value;
+      constexpr int R = kk == 0 ? FR + LPW : FR;           // memory instructions of this sub-step
+      if constexpr (kk == 1)
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * LPW) : "memory");
+      static_for<NM>([&](auto J) {
+        constexpr int j = decltype(J)::value;
+        constexpr int mi = j / NI, ni = j % NI;
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk][mi], bfr[kk][ni], acc[mi][ni], 0, 0, 0);
+        constexpr int lo = j * R / NM, hi = (j + 1) * R / NM;
+        static_for<hi - lo>([&](auto RR) {
+          constexpr int r = lo + decltype(RR)::value;
+          if constexpr (r < MI) {
+            const bf16_t* src = kk == 1 ? nxt + a_fr[0] : cur + a_fr[1];
+            af[kk ^ 1][r] = *(const bf16x8_t*)(src + r * 32 * BK);
+          } else if constexpr (r < FR) {
+            const bf16_t* src = kk == 1 ? nxt + b_fr[0] : cur + b_fr[1];
+            bfr[kk ^ 1][r - MI] = *(const bf16x8_t*)(src + (r - MI) * 32 * BK);
+          } else {
+            issue_load(r - FR, kload, (st + 3) & 3);
+          }
+        });
+        __builtin_amdgcn_sched_barrier(0);
+      });
+    });
+  };
+  for (int kt = 0; kt < KT; kt += 4) {
+    iteration(std::integral_constant<int, 0>{}, kt);
+    iteration(std::integral_constant<int, 1>{}, kt + 1);
+    iteration(std::integral_constant<int, 2>{}, kt + 2);
+    iteration(std::integral_constant<int, 3>{}, kt + 3);
+  }
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");   // no load may still be landing in LDS
+
+  constexpr bool STAGED = true;
+  constexpr int STAGE_ELEMS = NSTG * STG / NW;   // per wavefront
+  bf16_t* stage = lds + wave * STAGE_ELEMS;
+  gemm_epilogue<MI, NI, EPI, STAGED, STAGE_ELEMS>(g, acc, stage, b, m0 + wm * TM, n0 + wn * TN, lane);
+}
+
+template <int BM, int BN, int WM, int WN, int EPI>
+static int launch_dl(const pt_gemm_args& g, hipStream_t s) {
+  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+  const size_t lds = (size_t)4 * (BM + BN) * 32 * sizeof(bf16_t);
+  auto kern = gemm_dl_kernel<BM, BN, WM, WN, EPI>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    PT_HIP_CHECK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    attr_set = true;
+  }
+  const int64_t total = (int64_t)tiles_m * tiles_n * g.batch;
+  if (total > 0x7fffffff) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "GEMM grid too large");
+  hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(WM * WN * 64), lds, s, g, tiles_m, tiles_n);
+  PT_HIP_CHECK(hipGetLastError());
+  return 1;
 }
 
 template <int BM, int BN, int WM, int WN, int BK, int EPI>
@@ -535,15 +700,17 @@ static int launch_epi(const pt_gemm_args& g, hipStream_t s, int cfg) {
     case 6: return launch_cfg<64, 256, 1, 2, 64, EPI>(g, s);
     case 7: return launch_cfg<32, 256, 1, 2, 64, EPI>(g, s);
     case 8: return launch_cfg<128, 256, 2, 2, 32, EPI>(g, s);
-    default: return launch_cfg<128, 128, 2, 2, 32, EPI>(g, s);
+    case 9: return launch_cfg<128, 128, 2, 2, 32, EPI>(g, s);
+    case 10: return launch_dl<256, 256, 4, 2, EPI>(g, s);
+    default: return launch_dl<256, 256, 2, 2, EPI>(g, s);
   }
 }
 
 // Tile configuration override for tuning runs: -1 = choose by shape.
 int pt_gemm_mfma_force_cfg = -1;
 
-#define GM_NCFG 10
-static const int kWaveN[GM_NCFG] = {128, 64, 64, 64, 128, 64, 128, 128, 128, 64};   // columns per wavefront
+#define GM_NCFG 12
+static const int kWaveN[GM_NCFG] = {128, 64, 64, 64, 128, 64, 128, 128, 128, 64, 128, 128};   // columns per wavefront
 
 static bool cfg_fits(const pt_gemm_args& g, int cfg) {
   const int wn = kWaveN[cfg];
@@ -565,7 +732,7 @@ int pt_launch_gemm_mfma(const pt_gemm_args& g, hipStream_t s) {
   if ((g.epi == EPI_STORE_F32 || g.epi == EPI_RESIDUAL) &&
       ((g.ldo & 3) || (g.N & 3) || (g.out_bstride & 3) || (g.res_bstride & 3) || (((uintptr_t)g.out | (uintptr_t)g.res) & 15))) return 0;
   if (g.epi == EPI_SWIGLU && ((g.olp_bstride & 7) || ((uintptr_t)g.olp & 15))) return 0;
-  static const int big[] = {0, 4, 2, -1}, big_qkv[] = {8, 0, 4, 2, -1}, mid[] = {4, 2, -1}, m64[] = {3, 6, -1}, m32[] = {5, 7, -1};
+  static const int big[] = {0, 4, 2, -1}, big_qkv[] = {10, 8, 0, 4, 2, -1}, mid[] = {4, 2, -1}, m64[] = {3, 6, -1}, m32[] = {5, 7, -1};
   const int* cand;
   if (g.M <= 32) cand = m32;
   else if (g.M <= 64) cand = m64;

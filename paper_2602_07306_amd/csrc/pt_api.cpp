@@ -304,7 +304,10 @@ extern "C" int pt_profile_reset(pt_handle* h) {
 static int run_gemm(pt_handle* h, const pt_gemm_args& g, int cls) {
   prof_scope ps(h, cls);
   if (h->path == PT_PATH_AUTO) {
-    int r = pt_launch_gemm_mfma(g, h->stream);
+    int r = g.M <= 64 ? pt_launch_gemm_skinny(g, h->stream) : 0;
+    if (r < 0) return r;
+    if (r == 1) return PT_OK;
+    r = pt_launch_gemm_mfma(g, h->stream);
     if (r < 0) return r;
     if (r == 1) return PT_OK;
   }

@@ -134,6 +134,8 @@ struct pt_gemm_args {
 int pt_launch_gemm_generic(const pt_gemm_args& g, hipStream_t s);
 // Returns 1 if the MFMA kernel family supports this problem (then it has been launched), 0 if not.
 int pt_launch_gemm_mfma(const pt_gemm_args& g, hipStream_t s);
+// Weight-streaming kernel for M <= 64 (decode); same return convention.
+int pt_launch_gemm_skinny(const pt_gemm_args& g, hipStream_t s);
 
 // ---------------------------------------------------------------------------------------------
 // Attention over the KV cache.  q/o: [batch_t][rows][H*hd]; row m is sequence m / S at position

@@ -189,3 +189,61 @@ def test_block_end_merge_at_the_one_gpu_share_shape():
     for h in hs:
         bound += np.abs(h)
     assert np.all(np.abs(got) <= bound * (1 + 2.0 ** -7) + 1e-6)
+
+
+def _reduced_depth_case(cfg, seed, B, S):
+    """Full layer widths of a large configuration, reduced depth and token count (the oracle cost
+    of the full configuration is hours): logits / hidden and every block tap against the oracle."""
+    from paper_2602_07306_amd import binding as PB
+    W = I.make_weights(cfg, seed)
+    model = PB.PTModel(cfg)
+    model.pt_init_weights(seed)
+    if cfg.vocab:
+        tokens = I.make_tokens(seed, B, S, cfg.vocab)
+        ref, st = oracle_prefill(cfg, W, tokens)
+        taps, _ = model.pt_set_taps(B * S)
+        lg, _ = model.pt_prefill(torch.from_numpy(tokens).cuda(), logits_mode=PB.PT_LOGITS_ALL)
+        torch.cuda.synchronize()
+        assert rel_err(lg.cpu().numpy().reshape(B, S, -1), ref["logits"]) <= BF16_TOL
+        tap_np = taps.cpu().numpy().copy()
+        model.pt_clear_taps()
+        nxt = np.argmax(ref["logits"][:, -1], -1).astype(np.int32)
+        r = O.pt_decode_step(cfg, W, st, tokens=nxt)
+        g, _, _ = model.pt_decode_step(torch.from_numpy(nxt).cuda())
+        torch.cuda.synchronize()
+        assert rel_err(g.cpu().numpy(), r["logits"]) <= BF16_TOL
+    else:
+        x = np.stack([I.make_hidden(seed, 0, S, cfg.d_model) for _ in range(B)])       # [B, S, d], bf16 values
+        ref, st = oracle_prefill(cfg, W, hidden_in=x.astype(np.float64))
+        taps, _ = model.pt_set_taps(B * S)
+        _, hid = model.pt_prefill(hidden_in=torch.from_numpy(x).cuda(), logits_mode=PB.PT_LOGITS_NONE,
+                                  want_hidden=True)
+        torch.cuda.synchronize()
+        assert rel_err(hid.cpu().numpy(), ref["hidden"]) <= BF16_TOL
+        tap_np = taps.cpu().numpy().copy()
+        model.pt_clear_taps()
+        xn = I.make_hidden(seed, 9, B, cfg.d_model)                                     # [B, d]
+        r = O.pt_decode_step(cfg, W, st, hidden_in=xn.astype(np.float64))
+        _, g, _ = model.pt_decode_step(hidden_in=torch.from_numpy(xn).cuda(), want_logits=False,
+                                       want_hidden=True)
+        torch.cuda.synchronize()
+        assert rel_err(g.cpu().numpy(), r["hidden"]) <= BF16_TOL
+    for b in range(B):
+        for k in range(cfg.n_merges):
+            got = tap_np[k].reshape(B, S, -1)[b]
+            assert rel_err(got, ref["taps"][b][k]) <= BF16_TOL, (b, k)
+    model.close()
+
+
+def test_large_config_widths_at_reduced_depth():
+    """Large PT layer shape (T=8, d=2048, 16 heads x 128, FFN 8192, vocab 32000), 2 layers with a
+    merge after each, 1 x 256 tokens."""
+    cfg = dataclasses.replace(I.config_large(max_batch=1, max_seq=320), n_layers=2, block_depth=1)
+    _reduced_depth_case(cfg, 3, 1, 256)
+
+
+def test_share_config_widths_at_reduced_depth():
+    """One GPU's share of the wide model (single track, d=8192, 64 heads x 128, FFN 28672,
+    hidden-state in / out), 2 layers, 1 x 128 tokens."""
+    cfg = dataclasses.replace(I.config_share(max_batch=1, max_seq=192), n_layers=2, block_depth=2)
+    _reduced_depth_case(cfg, 4, 1, 128)
