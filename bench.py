@@ -84,9 +84,13 @@ def run_prefill(args, torch, PB, I):
     total_flops, per_class = prefill_flops(cfg, B, S, B)
     ms_step = dt / args.steps * 1e3
     achieved = per_class["gemm_gateup"] / (ms_dom / n_dom * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "gemm_mfma_kernel<..., EPI_SWIGLU> (gate/up GEMM)",
+    traffic = None   # HBM-side bytes per launch from the rocprofv3 --pmc passes kept under profiles/
+    tpath = os.path.join(ROOT, "profiles", "mid_prefill_gateup_traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get("traffic_bytes_per_launch")
+    roofline = {"bound": "mfma", "kernel": "gemm_mfma_kernel<256, 256, 2, 2, 64, EPI_SWIGLU> (gate/up GEMM)",
                 "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic,
                 "launches": n_dom, "avg_launch_ms": ms_dom / n_dom,
                 "flops_per_launch": per_class["gemm_gateup"]}
     # per-class breakdown on two extra, untimed steps
@@ -182,6 +186,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--skip-decode", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy three times (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs the PT forward on ONE GPU (all tracks resident); "
@@ -194,6 +200,13 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     PB.lib()
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     pre = run_prefill(args, torch, PB, I)
     log("prefill: %.3f ms/step, %.0f tokens/s, %.1f%% of bf16 MFMA peak end to end" % (
         pre["ms_step"], pre["tokens_per_s"],

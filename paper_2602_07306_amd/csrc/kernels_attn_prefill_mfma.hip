@@ -147,7 +147,7 @@ __global__ void __launch_bounds__(256) attn_prefill_mfma_kernel(const pt_attn_ar
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 template <int HD>
-__global__ void __launch_bounds__(256, 2) attn_prefill_lds_kernel(const pt_attn_args a) {
+__global__ void __launch_bounds__(256, HD == 64 ? 3 : 2) attn_prefill_lds_kernel(const pt_attn_args a, int nqb) {
   constexpr int KS = HD / 16;          // MFMAs per 32-key block of S^T
   constexpr int HB = HD / 32;          // 32-row blocks of O^T
   constexpr int KCPR = HD / 8;         // 16-byte chunks per K row
@@ -161,10 +161,23 @@ __global__ void __launch_bounds__(256, 2) attn_prefill_lds_kernel(const pt_attn_
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
-  const int qb = gridDim.x - 1 - (int)blockIdx.x;   // heavy (late) query blocks first
+  // Workgroup ids are dealt round-robin to the 8 XCDs.  A (track, sequence, head) combination keeps
+  // all its query blocks on one XCD (its K/V stay in that L2) and every XCD gets the same mix of
+  // long (late) and short (early) query blocks; long ones first.
+  const int combos = a.n_tracks * a.B * a.H;
+  int combo, qb;
+  if ((combos & 7) == 0) {
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    combo = xcd + 8 * (j / nqb);
+    qb = nqb - 1 - (j % nqb);
+  } else {
+    combo = blockIdx.x / nqb;
+    qb = nqb - 1 - (blockIdx.x % nqb);
+  }
   const int q0 = qb * 128 + wave * 32;
-  const int head = blockIdx.y;
-  const int t = blockIdx.z / a.B, seq = blockIdx.z - t * a.B;
+  const int head = combo % a.H;
+  const int tb = combo / a.H;
+  const int t = tb / a.B, seq = tb - t * a.B;
   const int kvh = head / (a.H / a.Hkv);
   const int64_t hidx = t * a.kv_bstride + seq * a.kv_seq_stride + kvh;
   const bf16_t* K = (const bf16_t*)a.kc + hidx * a.kv_head_elems;
@@ -324,7 +337,11 @@ __global__ void __launch_bounds__(256, 2) attn_prefill_lds_kernel(const pt_attn_
 }
 
 template <int HD>
-static int launch_lds(const pt_attn_args& a, dim3 grid, hipStream_t s) {
+static int launch_lds(const pt_attn_args& a, hipStream_t s) {
+  const int nqb = (a.S + 127) / 128;
+  const int64_t total = (int64_t)a.n_tracks * a.B * a.H * nqb;
+  if (total > 0x7fffffff) return 0;
+  const dim3 grid((unsigned)total);
   const size_t lds = (size_t)2 * (64 * HD + HD * 64) * sizeof(bf16_t);
   auto kern = attn_prefill_lds_kernel<HD>;
   static bool attr_set = false;
@@ -332,7 +349,7 @@ static int launch_lds(const pt_attn_args& a, dim3 grid, hipStream_t s) {
     PT_HIP_CHECK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, a);
+  hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, a, nqb);
   PT_HIP_CHECK(hipGetLastError());
   return 1;
 }
@@ -345,7 +362,7 @@ int pt_launch_attn_prefill_mfma(const pt_attn_args& a, hipStream_t s) {
   const int64_t z = (int64_t)a.n_tracks * a.B;
   if (z > 65535 || a.H > 65535) return 0;
   dim3 grid((unsigned)((a.S + 127) / 128), (unsigned)a.H, (unsigned)z);
-  if (a.S % 64 == 0 && (a.s_pad & 7) == 0) return a.hd == 64 ? launch_lds<64>(a, grid, s) : launch_lds<128>(a, grid, s);
+  if (a.S % 64 == 0 && (a.s_pad & 7) == 0) return a.hd == 64 ? launch_lds<64>(a, s) : launch_lds<128>(a, s);
   if (a.hd == 64)
     hipLaunchKernelGGL(attn_prefill_mfma_kernel<64>, grid, dim3(256), 0, s, a);
   else

@@ -130,7 +130,9 @@ def test_mid_prefill_full_size_matches_the_oracle_on_sampled_sequences():
     L = lg.cpu().numpy().reshape(B, S, -1)
     last, _ = model.pt_prefill(torch.from_numpy(tokens).cuda(), logits_mode=PB.PT_LOGITS_LAST)
     torch.cuda.synchronize()
-    assert np.array_equal(last.cpu().numpy(), L[:, -1])
+    # last-row logits come from the weight-streaming GEMM (M = 4 rows), all-row logits from the
+    # tiled one: same inputs, different summation order
+    np.testing.assert_allclose(last.cpu().numpy(), L[:, -1], rtol=0, atol=1e-5 * np.max(np.abs(L[:, -1])))
     for b in (0, 3):
         st = O.PTState(cfg, 1, S)
         ref = O.pt_prefill(cfg, W, st, tokens=tokens[b:b + 1], collect_taps=True)
