@@ -67,19 +67,30 @@ __global__ void __launch_bounds__(256) gemm_skinny_kernel(const pt_gemm_args g, 
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[mi][v] = 0.f;
 
-  for (int k = 0; k < kq; k += 16 * SK_UNROLL) {
-    bf16x8_t wf[SK_UNROLL], af[SK_UNROLL][MI];
+  // two register batches of SK_UNROLL K steps: the loads of batch i+1 are in flight while batch i is multiplied
+  bf16x8_t wf[2][SK_UNROLL], af[2][SK_UNROLL][MI];
+  auto load_batch = [&](int buf, int k) {
 #pragma unroll
-    for (int u = 0; u < SK_UNROLL; ++u) wf[u] = *(const bf16x8_t*)(wp + k + 16 * u);
+    for (int u = 0; u < SK_UNROLL; ++u) wf[buf][u] = *(const bf16x8_t*)(wp + k + 16 * u);
 #pragma unroll
     for (int u = 0; u < SK_UNROLL; ++u)
 #pragma unroll
-      for (int mi = 0; mi < MI; ++mi) af[u][mi] = *(const bf16x8_t*)(ap[mi] + k + 16 * u);
+      for (int mi = 0; mi < MI; ++mi) af[buf][u][mi] = *(const bf16x8_t*)(ap[mi] + k + 16 * u);
+  };
+  auto mul_batch = [&](int buf) {
 #pragma unroll
     for (int u = 0; u < SK_UNROLL; ++u)
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi)
-        acc[mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[u], af[u][mi], acc[mi], 0, 0, 0);
+        acc[mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][u], af[buf][u][mi], acc[mi], 0, 0, 0);
+  };
+  constexpr int KB = 16 * SK_UNROLL;
+  load_batch(0, 0);
+  for (int k = 0; k < kq; k += 2 * KB) {          // kq is a multiple of 2 * KB
+    load_batch(1, k + KB);
+    mul_batch(0);
+    load_batch(0, min(k + 2 * KB, kq - KB));      // past the end: re-read the last batch (unused)
+    mul_batch(1);
   }
 
   // reduce the four K quarters: register v of a lane is C^T row 8*(v/4) + 4*half + v%4, column l32
@@ -160,9 +171,9 @@ __global__ void __launch_bounds__(256) gemm_skinny_kernel(const pt_gemm_args g, 
 template <int MI, int EPI>
 static int launch_skinny(const pt_gemm_args& g, int tiles, hipStream_t s) {
   if (g.K % (4 * 16 * 8) == 0)
-    hipLaunchKernelGGL((gemm_skinny_kernel<MI, EPI, 8>), dim3((unsigned)(tiles * g.batch)), dim3(256), 0, s, g, tiles);
-  else
     hipLaunchKernelGGL((gemm_skinny_kernel<MI, EPI, 4>), dim3((unsigned)(tiles * g.batch)), dim3(256), 0, s, g, tiles);
+  else
+    hipLaunchKernelGGL((gemm_skinny_kernel<MI, EPI, 2>), dim3((unsigned)(tiles * g.batch)), dim3(256), 0, s, g, tiles);
   PT_HIP_CHECK(hipGetLastError());
   return 1;
 }
