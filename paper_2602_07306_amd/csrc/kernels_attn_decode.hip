@@ -178,6 +178,167 @@ __global__ void __launch_bounds__(64) attn_decode_combine_kernel(const pt_attn_a
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Grouped-query variant on the matrix cores: the G = H / Hkv query heads that share a KV head are
+// processed together, so every key and value element is still read exactly once.
+//
+//   S^T [32 keys x G] = K_blk [32 x hd] . Q^T       (A = key rows straight from the cache, B = the G queries)
+//   O^T [hd x G]     += V^T_blk [hd x 32] . P^T     (A = rows of the V^T cache, B = P^T from the S^T registers)
+//
+// which is the prefill formulation with the query heads of a group in place of query positions (MFMA
+// column = query head, padded to 32).  A workgroup owns one key range of one (track, sequence, KV head);
+// its 4 wavefronts take the 32-key blocks of the range round-robin, each with its own online-softmax
+// state, and merge the four states through LDS.  Operands go from global memory directly into the MFMA
+// register layout (16 bytes per lane); nothing is staged because nothing is reused.
+// ------------------------------------------------------------------------------------------------
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+
+union dpk8 {
+  bf16x8_t v;
+  uint32_t u[4];
+};
+
+#define DEC_GMAX 16
+
+template <int HD>
+__global__ void __launch_bounds__(256) attn_decode_gqa_kernel(const pt_attn_args a, int nsplit, int keys_per_split) {
+  constexpr int KS = HD / 16, HB = HD / 32;
+  __shared__ float red_o[4][HD][DEC_GMAX];
+  __shared__ float red_m[4][32], red_l[4][32];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int split = blockIdx.x, kvh = blockIdx.y;
+  const int t = blockIdx.z / a.B, seq = blockIdx.z - t * a.B;
+  const int G = a.H / a.Hkv;
+  const int nkeys = a.pos0 + 1;
+  const int k0 = split * keys_per_split;
+  const int k1 = min(nkeys, k0 + keys_per_split);
+  const int64_t hidx = t * a.kv_bstride + seq * a.kv_seq_stride + kvh;
+  const bf16_t* K = (const bf16_t*)a.kc + hidx * a.kv_head_elems;
+  const bf16_t* Vt = (const bf16_t*)a.vc + hidx * ((int64_t)HD * a.s_pad);
+  const int64_t qbase = t * a.q_bstride + (int64_t)seq * (a.H * HD) + (int64_t)kvh * G * HD;
+
+  // B operand of S^T: query head l32 of the group (zero beyond G)
+  bf16x8_t qf[KS];
+#pragma unroll
+  for (int kk = 0; kk < KS; ++kk) {
+    dpk8 z;
+    z.u[0] = z.u[1] = z.u[2] = z.u[3] = 0u;
+    if (l32 < G) z.v = *(const bf16x8_t*)((const bf16_t*)a.q + qbase + (int64_t)l32 * HD + kk * 16 + half * 8);
+    qf[kk] = z.v;
+  }
+  const int krow = (l32 & ~12) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);   // MFMA row r of S^T holds key pi(r)
+  const float c_log2 = 1.4426950408889634f / sqrtf((float)HD);
+
+  f32x16_t oacc[HB];
+#pragma unroll
+  for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) oacc[hb][v] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  for (int kb = k0 + wave * 32; kb < k1; kb += 128) {
+    const bool tail = kb + 32 > k1;   // wave-uniform: some keys of the block lie beyond the range
+    f32x16_t s;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s[v] = 0.f;
+    // rows beyond the range are clamped to a valid row; their scores are masked below
+    const bf16_t* kp = K + (int64_t)min(kb + krow, k1 - 1) * HD + half * 8;
+    bf16x8_t kf[KS];
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) kf[kk] = *(const bf16x8_t*)(kp + kk * 16);
+    dpk8 vf[HB][2];
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+        vf[hb][u].v = *(const bf16x8_t*)(Vt + (int64_t)(hb * 32 + l32) * a.s_pad + kb + 16 * u + 8 * half);
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], s, 0, 0, 0);
+    // register v: key kb + 16*(v/8) + 8*half + v%8, query head l32
+    if (tail) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        if (kb + 16 * (v >> 3) + 8 * half + (v & 7) >= k1) s[v] = -INFINITY;
+      // cache bytes beyond the range are not data: zero them so that 0 * x stays 0
+#pragma unroll
+      for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int key = kb + 16 * u + 8 * half + 2 * i;
+            uint32_t w = vf[hb][u].u[i];
+            if (key >= k1) w &= 0xffff0000u;
+            if (key + 1 >= k1) w &= 0x0000ffffu;
+            vf[hb][u].u[i] = w;
+          }
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[v]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx);
+    const float corr = __builtin_amdgcn_exp2f((m_run - m_new) * c_log2);
+    const float mc = m_new * c_log2;
+    float psum = 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      s[v] = __builtin_amdgcn_exp2f(fmaf(s[v], c_log2, -mc));
+      psum += s[v];
+    }
+    l_run = l_run * corr + psum;
+    m_run = m_new;
+    if (__any(corr != 1.0f)) {
+#pragma unroll
+      for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) oacc[hb][v] *= corr;
+    }
+    dpk8 pf[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) pf[u].u[i] = pack_bf16x2(s[8 * u + 2 * i], s[8 * u + 2 * i + 1]);
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+        oacc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[hb][u].v, pf[u].v, oacc[hb], 0, 0, 0);
+  }
+  // the two half-waves of a query head hold disjoint key subsets with a common running max
+  l_run += __shfl_xor(l_run, 32, 64);
+  // merge the four wavefront states: row (hd index) of register v in block hb = hb*32 + 8*(v/4) + 4*half + v%4
+  if (half == 0) { red_m[wave][l32] = m_run; red_l[wave][l32] = l_run; }
+  __syncthreads();
+  float M = fmaxf(fmaxf(red_m[0][l32], red_m[1][l32]), fmaxf(red_m[2][l32], red_m[3][l32]));
+  const float sc = m_run == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((m_run - M) * c_log2);   // a wavefront may have had no block
+  if (l32 < G) {
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) red_o[wave][hb * 32 + 8 * (v >> 2) + 4 * half + (v & 3)][l32] = oacc[hb][v] * sc;
+  }
+  __syncthreads();
+  for (int e = tid; e < HD * G; e += 256) {
+    const int g = e / HD, r = e - g * HD;
+    float Mg = fmaxf(fmaxf(red_m[0][g], red_m[1][g]), fmaxf(red_m[2][g], red_m[3][g]));
+    float L = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) L += red_m[w][g] == -INFINITY ? 0.f : red_l[w][g] * __builtin_amdgcn_exp2f((red_m[w][g] - Mg) * c_log2);
+    const float o = red_o[0][r][g] + red_o[1][r][g] + red_o[2][r][g] + red_o[3][r][g];
+    const int head = kvh * G + g;
+    if (nsplit == 1) {
+      ((bf16_t*)a.o)[qbase + (int64_t)g * HD + r] = f32_to_bf16(o / L);
+    } else {
+      float* part = a.partials + (((int64_t)blockIdx.z * a.H + head) * nsplit + split) * (HD + 2);
+      if (r == 0) { part[0] = Mg * c_log2; part[1] = L; }
+      part[2 + r] = o;
+    }
+  }
+}
+
 int pt_launch_attn_decode(const pt_attn_args& a, hipStream_t s) {
   if (a.dtype != PT_BF16 || a.S != 1) return 0;
   if (a.hd != 64 && a.hd != 128) return 0;
@@ -185,6 +346,27 @@ int pt_launch_attn_decode(const pt_attn_args& a, hipStream_t s) {
   const int64_t z = (int64_t)a.n_tracks * a.B;
   if (z > 65535 || a.H > 65535) return 0;
   const int nkeys = a.pos0 + 1;
+  const int G = a.H / a.Hkv;
+  if (G > 1 && G <= DEC_GMAX && (a.s_pad & 7) == 0) {
+    const int64_t gbase = z * a.Hkv;
+    int nsplit = (int)((1024 + gbase - 1) / gbase);
+    const int by_len = (nkeys + 511) / 512;
+    if (nsplit > by_len) nsplit = by_len;
+    if (nsplit < 1) nsplit = 1;
+    if (nsplit > a.max_splits) nsplit = a.max_splits;
+    int kps = (nkeys + nsplit - 1) / nsplit;
+    kps = (kps + 127) / 128 * 128;
+    nsplit = (nkeys + kps - 1) / kps;      // no empty split
+    dim3 grid((unsigned)nsplit, (unsigned)a.Hkv, (unsigned)z);
+    if (a.hd == 64)
+      hipLaunchKernelGGL(attn_decode_gqa_kernel<64>, grid, dim3(256), 0, s, a, nsplit, kps);
+    else
+      hipLaunchKernelGGL(attn_decode_gqa_kernel<128>, grid, dim3(256), 0, s, a, nsplit, kps);
+    if (nsplit > 1)
+      hipLaunchKernelGGL(attn_decode_combine_kernel, dim3((unsigned)a.H, (unsigned)z), dim3(64), 0, s, a, nsplit);
+    PT_HIP_CHECK(hipGetLastError());
+    return 1;
+  }
   const int64_t base = z * a.H;
   int nsplit = (int)((1024 + base - 1) / base);
   const int by_len = (nkeys + DEC_CHUNK - 1) / DEC_CHUNK;
