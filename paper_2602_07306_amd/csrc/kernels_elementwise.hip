@@ -32,6 +32,16 @@ int pt_launch_embed(const void* embed, int32_t dtype, const int32_t* tokens, int
 // RMSNorm: out = h * g / sqrt(mean(h^2) + eps); fp32 statistics; one wavefront per row.
 // Row r of track b reads h + b*h_bstride + row_index(r)*d with row_index(r) = r*row_step + row_off.
 // ------------------------------------------------------------------------------------------
+__device__ __forceinline__ void store4(float* p, float a, float b, float c, float d) {
+  *(float4*)p = make_float4(a, b, c, d);
+}
+__device__ __forceinline__ void store4(bf16_t* p, float a, float b, float c, float d) {
+  uint2 v;
+  v.x = pack_bf16x2(a, b);
+  v.y = pack_bf16x2(c, d);
+  *(uint2*)p = v;
+}
+
 template <typename T>
 __global__ void __launch_bounds__(256) rmsnorm_kernel(const float* __restrict__ h, int64_t h_bstride,
                                                       const float* __restrict__ gains, int64_t g_bstride,
@@ -55,17 +65,119 @@ __global__ void __launch_bounds__(256) rmsnorm_kernel(const float* __restrict__ 
   for (int i = lane; i < n4; i += 64) {
     float4 v = src[i];
     float4 w = g[i];
-    elem<T>::st(dst + 4 * i + 0, v.x * inv * w.x);
-    elem<T>::st(dst + 4 * i + 1, v.y * inv * w.y);
-    elem<T>::st(dst + 4 * i + 2, v.z * inv * w.z);
-    elem<T>::st(dst + 4 * i + 3, v.w * inv * w.w);
+    store4(dst + 4 * i, v.x * inv * w.x, v.y * inv * w.y, v.z * inv * w.z, v.w * inv * w.w);
   }
+}
+
+// Few rows (decode): one workgroup per row, so that a long row is not read by a single wavefront.
+template <typename T>
+__global__ void __launch_bounds__(256) rmsnorm_row_kernel(const float* __restrict__ h, int64_t h_bstride,
+                                                          const float* __restrict__ gains, int64_t g_bstride,
+                                                          T* __restrict__ out, int64_t out_bstride, int64_t rows,
+                                                          int64_t row_step, int64_t row_off, int32_t d, float eps) {
+  __shared__ float s_part[4];
+  const int64_t r = blockIdx.x;
+  const int b = blockIdx.y;
+  const float4* src = (const float4*)(h + b * h_bstride + (r * row_step + row_off) * d);
+  const float4* g = (const float4*)(gains + b * g_bstride);
+  const int n4 = d >> 2;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < n4; i += 256) {
+    float4 v = src[i];
+    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+  ss = wave_sum(ss);
+  if ((threadIdx.x & 63) == 0) s_part[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  ss = (s_part[0] + s_part[1]) + (s_part[2] + s_part[3]);
+  const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+  T* dst = out + b * out_bstride + r * d;
+  for (int i = threadIdx.x; i < n4; i += 256) {
+    float4 v = src[i];
+    float4 w = g[i];
+    store4(dst + 4 * i, v.x * inv * w.x, v.y * inv * w.y, v.z * inv * w.z, v.w * inv * w.w);
+  }
+}
+
+// Decode residual GEMMs with K split over workgroups leave `slices` partial products; this kernel adds them
+// to the residual stream, stores the stream and (when out is given) its RMSNorm for the next GEMM.
+// One workgroup per row; a thread keeps its <= 32 elements in registers between the two passes.
+__global__ void __launch_bounds__(256) resnorm_kernel(const float* __restrict__ part, int32_t slices,
+                                                      const float* res, int64_t res_bstride, float* h,
+                                                      int64_t h_bstride, const float* __restrict__ gains,
+                                                      int64_t g_bstride, bf16_t* __restrict__ out,
+                                                      int64_t out_bstride, int32_t batch, int64_t rows, int32_t d,
+                                                      float eps) {
+  __shared__ float s_part[4];
+  const int64_t r = blockIdx.x;
+  const int b = blockIdx.y;
+  const int n4 = d >> 2;
+  const float4* rsrc = (const float4*)(res + b * res_bstride + r * d);
+  float4* hdst = (float4*)(h + b * h_bstride + r * d);
+  const int64_t slice_stride4 = ((int64_t)batch * rows * d) >> 2;
+  const float4* p0 = (const float4*)part + (((int64_t)b * rows + r) * d >> 2);
+  float4 x[8];
+  float ss = 0.f;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    const int i = threadIdx.x + c * 256;
+    if (i < n4) {
+      float4 acc = p0[i];
+      for (int q = 1; q < slices; ++q) {
+        const float4 v = p0[q * slice_stride4 + i];
+        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+      }
+      const float4 rv = rsrc[i];
+      acc.x += rv.x; acc.y += rv.y; acc.z += rv.z; acc.w += rv.w;
+      hdst[i] = acc;
+      x[c] = acc;
+      ss += acc.x * acc.x + acc.y * acc.y + acc.z * acc.z + acc.w * acc.w;
+    }
+  }
+  if (!out) return;
+  ss = wave_sum(ss);
+  if ((threadIdx.x & 63) == 0) s_part[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  ss = (s_part[0] + s_part[1]) + (s_part[2] + s_part[3]);
+  const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+  const float4* g = (const float4*)(gains + b * g_bstride);
+  bf16_t* dst = out + b * out_bstride + r * d;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    const int i = threadIdx.x + c * 256;
+    if (i < n4) {
+      const float4 w = g[i];
+      store4(dst + 4 * i, x[c].x * inv * w.x, x[c].y * inv * w.y, x[c].z * inv * w.z, x[c].w * inv * w.w);
+    }
+  }
+}
+
+int pt_launch_resnorm(const float* part, int32_t slices, const float* res, int64_t res_bstride, float* h,
+                      int64_t h_bstride, const float* gains, int64_t g_bstride, void* out, int64_t out_bstride,
+                      int32_t batch, int64_t rows, int32_t d, float eps, hipStream_t s) {
+  if (rows <= 0 || batch <= 0) return PT_OK;
+  if (d > 8192 || (d & 3) || slices < 1) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "resnorm: d = %d, slices = %d not covered", d, slices);
+  hipLaunchKernelGGL(resnorm_kernel, dim3((unsigned)rows, (unsigned)batch), dim3(256), 0, s, part, slices, res,
+                     res_bstride, h, h_bstride, gains, g_bstride, (bf16_t*)out, out_bstride, batch, rows, d, eps);
+  PT_HIP_CHECK(hipGetLastError());
+  return PT_OK;
 }
 
 static int launch_rmsnorm(const float* h, int64_t h_bstride, const float* gains, int64_t g_bstride, void* out,
                           int64_t out_bstride, int32_t dtype, int32_t batch, int64_t rows, int64_t row_step,
                           int64_t row_off, int32_t d, float eps, hipStream_t s) {
   if (rows <= 0 || batch <= 0) return PT_OK;
+  if (rows * batch <= 2048 && d >= 1024) {
+    dim3 grid((unsigned)rows, (unsigned)batch);
+    if (dtype == PT_F32)
+      hipLaunchKernelGGL(rmsnorm_row_kernel<float>, grid, dim3(256), 0, s, h, h_bstride, gains, g_bstride, (float*)out,
+                         out_bstride, rows, row_step, row_off, d, eps);
+    else
+      hipLaunchKernelGGL(rmsnorm_row_kernel<bf16_t>, grid, dim3(256), 0, s, h, h_bstride, gains, g_bstride, (bf16_t*)out,
+                         out_bstride, rows, row_step, row_off, d, eps);
+    PT_HIP_CHECK(hipGetLastError());
+    return PT_OK;
+  }
   dim3 grid((unsigned)((rows + 3) / 4), (unsigned)batch);
   if (dtype == PT_F32)
     hipLaunchKernelGGL(rmsnorm_kernel<float>, grid, dim3(256), 0, s, h, h_bstride, gains, g_bstride, (float*)out,

@@ -2,13 +2,12 @@
 // token per sequence).  The work is reading W once from HBM; the matrix cores only keep the arithmetic
 // out of the way.
 //
-// A workgroup owns 32 weight rows (output columns) of one track and all M rows of A; its 4 wavefronts
-// split K into four contiguous quarters, so 4 x 32 row streams are in flight per workgroup and even a
-// [1024 x 1024] projection spreads over 128 workgroups per track.  The product is formed transposed,
-// C^T tile (32 n x 32 m) = W rows (A operand, 16-byte global loads straight into the MFMA layout) times
-// A rows (B operand), so a lane owns one row m of C and 4 consecutive columns n per register group.
-// The four partial tiles meet in LDS; the fused epilogues (residual add, SwiGLU, RoPE + KV-cache append)
-// run on the reduced tile.
+// A workgroup owns one to four tiles of 32 weight rows (output columns) of one track and all M rows of A; its
+// 4 wavefronts split K (or the workgroup's K slice) into four contiguous ranges.  The product is formed
+// transposed, C^T tile (32 n x 32 m) = W rows (MFMA A operand) times A rows (B operand), so a lane owns one
+// row m of C and 4 consecutive columns n per register group.  The four partial tiles meet in LDS; the fused
+// epilogues (residual add, SwiGLU, RoPE + KV-cache append) run on the reduced tile.  Residual GEMMs with few
+// tiles may also split K over workgroups; those leave fp32 slices that the following kernel adds up.
 //
 // The 32 weight rows are two segments of 16: for the paired epilogues the second segment holds the
 // partners (up rows of the gate rows; rotary column j + hd/2 of column j), which lands a pair in the
@@ -18,6 +17,7 @@
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 
 struct sk_tile {
@@ -55,27 +55,80 @@ __device__ __forceinline__ sk_tile sk_decode_tile(const pt_gemm_args& g, int til
   return t;
 }
 
-// MI: 32-row blocks of A (M <= 32*MI); RB: 32-row blocks of W per workgroup (the A fragments of a K batch are
-// loaded once and multiplied with RB blocks of weight rows); SK_UNROLL: 16-wide K steps per register batch.
-template <int MI, int RB, int EPI, int SK_UNROLL>
-__global__ void __launch_bounds__(256) gemm_skinny_kernel(const pt_gemm_args g, int wgs_per_track) {
-  __shared__ float red[4][MI][16][64];
+// MI: 32-row blocks of A (M <= 32*MI); RB: 32-row blocks of W per workgroup (each A fragment is multiplied
+// with RB blocks of weight rows).
+//
+// K advances in steps of 64 per wavefront.  Both operands are read from global memory as whole 128-byte row
+// pieces (8 lanes per row, 8 rows per load instruction): lane-per-row loads in the MFMA operand layout touch
+// 32 cache lines per instruction and hold the vector-memory path below what HBM delivers.  The pieces are
+// parked in LDS private to the wavefront and picked up from there as MFMA fragments.  Row r of a parked
+// block holds its 16-byte chunk c at position c ^ swizzle(r): writes and fragment reads are conflict-free.
+// Weight rows use two rotating register sets, refilled with step s+2 as soon as step s is parked, so two
+// steps of weights are in flight per wavefront; A uses one register set and two LDS slots.
+template <int MI, int RB, int EPI>
+__device__ __forceinline__ void skinny_body(const pt_gemm_args& g, int b, int first_tile, int ks, int ksn) {
+  constexpr int A_STEP = MI * 32 * 128;                 // bytes of A per K step
+  constexpr int W_STEP = RB * 32 * 128;                 // bytes of W per K step
+  constexpr int RING = 2 * A_STEP + W_STEP;             // per wavefront
+  extern __shared__ __attribute__((aligned(1024))) char smem[];   // max(4 * RING, reduction buffer) bytes
+  float (*red)[MI][16][64] = (float (*)[MI][16][64])smem;         // reuses the rings after the K loop
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
-  const int b = blockIdx.x / wgs_per_track, wg = blockIdx.x - b * wgs_per_track;
+  const int kq = g.K / (4 * ksn);   // K range of this wavefront, a multiple of 128
+  const int k_first = (ks * 4 + wave) * kq;
+  const int nsteps = kq >> 6;
 
-  const int kq = g.K >> 2;   // K quarter of this wavefront
-  const bf16_t* wp[RB];
+  // staging: load i of a 32-row block brings rows 8i .. 8i+7, lane L the chunk L%8 of row 8i + L/8
+  auto swz = [](int row) { return (row >> 1) & 7; };
+  char* a_ring = smem + wave * RING;
+  char* w_slot = a_ring + 2 * A_STEP;
+  int dst[4];   // position inside a parked 32-row block
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = i * 8 + (lane >> 3);
+    dst[i] = row * 128 + (((lane & 7) ^ swz(row)) * 16);
+  }
+  const bf16_t* w_src[RB][4];
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
-    const sk_tile tl = sk_decode_tile<EPI>(g, wg * RB + rb);
-    const int wrow = l32 < 16 ? tl.n_a + l32 : tl.n_b + (l32 - 16);
-    wp[rb] = (const bf16_t*)g.W + b * g.w_bstride + (int64_t)wrow * g.ldb + wave * kq + half * 8;
-  }
-  const bf16_t* ap[MI];
+    const sk_tile tl = sk_decode_tile<EPI>(g, first_tile + rb);
 #pragma unroll
-  for (int mi = 0; mi < MI; ++mi)
-    ap[mi] = (const bf16_t*)g.A + b * g.a_bstride + (int64_t)min(mi * 32 + l32, g.M - 1) * g.lda + wave * kq + half * 8;
+    for (int i = 0; i < 4; ++i) {
+      const int r = i * 8 + (lane >> 3);
+      const int wrow = r < 16 ? tl.n_a + r : tl.n_b + (r - 16);
+      w_src[rb][i] = (const bf16_t*)g.W + b * g.w_bstride + (int64_t)wrow * g.ldb + k_first + (lane & 7) * 8;
+    }
+  }
+  const bf16_t* a_src[4 * MI];
+#pragma unroll
+  for (int j = 0; j < 4 * MI; ++j) {
+    const int row = j * 8 + (lane >> 3);
+    a_src[j] = (const bf16_t*)g.A + b * g.a_bstride + (int64_t)min(row, g.M - 1) * g.lda + k_first + (lane & 7) * 8;
+  }
+  u32x4_t areg[4 * MI], wreg[2][RB][4];
+  auto load_a = [&](int step) {
+#pragma unroll
+    for (int j = 0; j < 4 * MI; ++j) areg[j] = *(const u32x4_t*)(a_src[j] + step * 64);
+  };
+  auto park_a = [&](int step) {
+    char* slot = a_ring + (step & 1) * A_STEP;
+#pragma unroll
+    for (int j = 0; j < 4 * MI; ++j) *(u32x4_t*)(slot + (j >> 2) * 4096 + dst[j & 3]) = areg[j];
+  };
+  auto load_w = [&](int buf, int step) {
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) wreg[buf][rb][i] = *(const u32x4_t*)(w_src[rb][i] + step * 64);
+  };
+  auto park_w = [&](int buf) {
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) *(u32x4_t*)(w_slot + rb * 4096 + dst[i]) = wreg[buf][rb][i];
+  };
+  // fragment of a 32-row block for K sub-step u (16 wide): row l32, chunk 2u + half
+  const int fr_row = l32 * 128, fr_sw = swz(l32);
 
   f32x16_t acc[RB][MI];
 #pragma unroll
@@ -85,42 +138,126 @@ __global__ void __launch_bounds__(256) gemm_skinny_kernel(const pt_gemm_args g, 
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[rb][mi][v] = 0.f;
 
-  // two register batches of SK_UNROLL K steps: the loads of batch i+1 are in flight while batch i is multiplied
-  bf16x8_t wf[2][RB][SK_UNROLL], af[2][SK_UNROLL][MI];
-  auto load_batch = [&](int buf, int k) {
+  auto mul_step = [&](int step) {
+    const char* a_slot = a_ring + (step & 1) * A_STEP;
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
+    for (int u = 0; u < 4; ++u) {
+      const int fo = fr_row + (((2 * u + half) ^ fr_sw) * 16);
+      bf16x8_t af[MI], wfr[RB];
 #pragma unroll
-      for (int u = 0; u < SK_UNROLL; ++u) wf[buf][rb][u] = *(const bf16x8_t*)(wp[rb] + k + 16 * u);
+      for (int mi = 0; mi < MI; ++mi) af[mi] = *(const bf16x8_t*)(a_slot + mi * 4096 + fo);
 #pragma unroll
-    for (int u = 0; u < SK_UNROLL; ++u)
-#pragma unroll
-      for (int mi = 0; mi < MI; ++mi) af[buf][u][mi] = *(const bf16x8_t*)(ap[mi] + k + 16 * u);
-  };
-  auto mul_batch = [&](int buf) {
-#pragma unroll
-    for (int u = 0; u < SK_UNROLL; ++u)
+      for (int rb = 0; rb < RB; ++rb) wfr[rb] = *(const bf16x8_t*)(w_slot + rb * 4096 + fo);
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
-          acc[rb][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][rb][u], af[buf][u][mi], acc[rb][mi], 0, 0, 0);
+          acc[rb][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[rb], af[mi], acc[rb][mi], 0, 0, 0);
+    }
   };
-  constexpr int KB = 16 * SK_UNROLL;
-  load_batch(0, 0);
-  for (int k = 0; k < kq; k += 2 * KB) {          // kq is a multiple of 2 * KB
-    load_batch(1, k + KB);
-    mul_batch(0);
-    load_batch(0, min(k + 2 * KB, kq - KB));      // past the end: re-read the last batch (unused)
-    mul_batch(1);
-  }
 
-  // per block of weight rows: reduce the four K quarters through LDS, then the fused epilogue.
+  // Loads past the last step re-read it (never used).  The prologue issues its loads in the order of the
+  // loop body, so that the waits the compiler derives for the loop need not cover a different order on entry.
+  load_w(0, 0);
+  __builtin_amdgcn_sched_barrier(0);
+  load_a(0);
+  __builtin_amdgcn_sched_barrier(0);
+  park_a(0);
+  __builtin_amdgcn_sched_barrier(0);
+  load_w(1, min(1, nsteps - 1));
+  __builtin_amdgcn_sched_barrier(0);
+  load_a(min(1, nsteps - 1));
+  for (int s0 = 0; s0 < nsteps; s0 += 2) {   // nsteps is even
+#pragma unroll
+    for (int par = 0; par < 2; ++par) {
+      const int st = s0 + par;
+      __builtin_amdgcn_sched_barrier(0);
+      park_w(par);                                // step st; the fragments of step st-1 have been read
+      __builtin_amdgcn_sched_barrier(0);
+      load_w(par, min(st + 2, nsteps - 1));
+      __builtin_amdgcn_sched_barrier(0);
+      park_a(st + 1);                             // into the slot of step st-1
+      __builtin_amdgcn_sched_barrier(0);
+      load_a(min(st + 2, nsteps - 1));
+      __builtin_amdgcn_sched_barrier(0);
+      mul_step(st);
+    }
+  }
+  __syncthreads();   // the rings become the reduction buffer
+
   // Register v of a lane is C^T row 8*(v/4) + 4*half + v%4, column l32.  Wavefront w finishes m-block w/2,
   // register groups (w%2) and (w%2)+2: rows 8*(w%2)+4*half+i of each segment.
   const int mi_e = wave >> 1, vg = wave & 1;
   const int m = mi_e * 32 + l32;
   const int off = 8 * vg + 4 * half;   // column offset inside a segment
+  const bool owner = mi_e < MI && m < g.M;
+
+  // fused epilogue on the reduced values of one block of weight rows
+  auto finish = [&](int rb, const float (&lo)[4], const float (&hi)[4]) {
+    const sk_tile tl = sk_decode_tile<EPI>(g, first_tile + rb);
+    const int n_a = tl.n_a, n_b = tl.n_b, j0 = tl.j0, qk_head = tl.qk_head;
+    (void)n_a; (void)n_b; (void)j0; (void)qk_head;
+    if constexpr (EPI == EPI_STORE_F32 || EPI == EPI_RESIDUAL) {
+      // K split over workgroups: slice ks leaves its partial product in sk_part[ks][b][m][n]; the kernel that
+      // consumes the residual stream adds the slices and the residual
+      const bool split = EPI == EPI_RESIDUAL && ksn > 1;
+      float* out = split ? g.sk_part + (((int64_t)ks * g.batch + b) * g.M + m) * g.N
+                         : g.out + b * g.out_bstride + (int64_t)m * g.ldo;
+      const float* res = EPI == EPI_RESIDUAL ? g.res + b * g.res_bstride + (int64_t)m * g.ldo : nullptr;
+#pragma unroll
+      for (int sgm = 0; sgm < 2; ++sgm) {
+        const int n = (sgm ? n_b : n_a) + off;
+        const float* x = sgm ? hi : lo;
+        if (n < g.N) {
+          f32x4_t v4 = {x[0], x[1], x[2], x[3]};
+          if constexpr (EPI == EPI_RESIDUAL) if (!split) v4 += *(const f32x4_t*)(res + n);
+          *(f32x4_t*)(out + n) = v4;
+        }
+      }
+    } else if constexpr (EPI == EPI_SWIGLU) {
+      bf16_t* o = (bf16_t*)g.olp + b * g.olp_bstride + (int64_t)m * (g.N >> 1) + j0 + off;
+      uint2 pk;
+      pk.x = pack_bf16x2(silu_f(lo[0]) * hi[0], silu_f(lo[1]) * hi[1]);
+      pk.y = pack_bf16x2(silu_f(lo[2]) * hi[2], silu_f(lo[3]) * hi[3]);
+      *(uint2*)o = pk;
+    } else {  // EPI_QKV
+      const int seq = m / g.S, pos = g.pos0 + (m - seq * g.S);
+      const int hd = g.hd, half_hd = hd >> 1, hq = g.H * hd;
+      if (tl.rot) {
+        const int j = j0 + off;
+        const float4* rp = (const float4*)((const float2*)g.rope + (int64_t)pos * half_hd + j);
+        const float4 cs01 = rp[0], cs23 = rp[1];
+        const float c[4] = {cs01.x, cs01.z, cs23.x, cs23.z}, sn[4] = {cs01.y, cs01.w, cs23.y, cs23.w};
+        uint2 plo, phi;
+        plo.x = pack_bf16x2(lo[0] * c[0] - hi[0] * sn[0], lo[1] * c[1] - hi[1] * sn[1]);
+        plo.y = pack_bf16x2(lo[2] * c[2] - hi[2] * sn[2], lo[3] * c[3] - hi[3] * sn[3]);
+        phi.x = pack_bf16x2(hi[0] * c[0] + lo[0] * sn[0], hi[1] * c[1] + lo[1] * sn[1]);
+        phi.y = pack_bf16x2(hi[2] * c[2] + lo[2] * sn[2], hi[3] * c[3] + lo[3] * sn[3]);
+        bf16_t* dst;
+        if (qk_head < g.H) {
+          dst = (bf16_t*)g.olp + b * g.olp_bstride + (int64_t)m * hq + qk_head * hd + j;
+        } else {
+          const int64_t hidx = b * g.kv_bstride + seq * g.kv_seq_stride + (qk_head - g.H);
+          dst = (bf16_t*)g.kc + hidx * g.kv_head_elems + (int64_t)pos * hd + j;
+        }
+        *(uint2*)dst = plo;
+        *(uint2*)(dst + half_hd) = phi;
+      } else {
+#pragma unroll
+        for (int sgm = 0; sgm < 2; ++sgm) {
+          const int cbase = (sgm ? n_b : n_a) - (g.H + g.Hkv) * hd + off;   // column inside the v section
+          const float* x = sgm ? hi : lo;
+          const int head = cbase / hd, j = cbase - head * hd;
+          const int64_t hidx = b * g.kv_bstride + seq * g.kv_seq_stride + head;
+          bf16_t* vt = (bf16_t*)g.vc + hidx * ((int64_t)hd * g.s_pad) + (int64_t)j * g.s_pad + pos;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) vt[(int64_t)i * g.s_pad] = f32_to_bf16(x[i]);
+        }
+      }
+    }
+  };
+
+  // per block of weight rows: the four wavefronts' partial tiles meet in LDS
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
     if (rb > 0) __syncthreads();
@@ -129,113 +266,165 @@ __global__ void __launch_bounds__(256) gemm_skinny_kernel(const pt_gemm_args g, 
 #pragma unroll
       for (int v = 0; v < 16; ++v) red[wave][mi][v][lane] = acc[rb][mi][v];
     __syncthreads();
-    if (mi_e < MI && m < g.M) {
-      const sk_tile tl = sk_decode_tile<EPI>(g, wg * RB + rb);
-      const int n_a = tl.n_a, n_b = tl.n_b, j0 = tl.j0, qk_head = tl.qk_head;
+    if (owner) {
       float lo[4], hi[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         lo[i] = red[0][mi_e][vg * 4 + i][lane] + red[1][mi_e][vg * 4 + i][lane] + red[2][mi_e][vg * 4 + i][lane] + red[3][mi_e][vg * 4 + i][lane];
         hi[i] = red[0][mi_e][vg * 4 + 8 + i][lane] + red[1][mi_e][vg * 4 + 8 + i][lane] + red[2][mi_e][vg * 4 + 8 + i][lane] + red[3][mi_e][vg * 4 + 8 + i][lane];
       }
-      if constexpr (EPI == EPI_STORE_F32 || EPI == EPI_RESIDUAL) {
-        float* out = g.out + b * g.out_bstride + (int64_t)m * g.ldo;
-        const float* res = EPI == EPI_RESIDUAL ? g.res + b * g.res_bstride + (int64_t)m * g.ldo : nullptr;
-#pragma unroll
-        for (int sgm = 0; sgm < 2; ++sgm) {
-          const int n = (sgm ? n_b : n_a) + off;
-          const float* x = sgm ? hi : lo;
-          if (n < g.N) {
-            f32x4_t v4 = {x[0], x[1], x[2], x[3]};
-            if constexpr (EPI == EPI_RESIDUAL) v4 += *(const f32x4_t*)(res + n);
-            *(f32x4_t*)(out + n) = v4;
-          }
-        }
-      } else if constexpr (EPI == EPI_SWIGLU) {
-        bf16_t* o = (bf16_t*)g.olp + b * g.olp_bstride + (int64_t)m * (g.N >> 1) + j0 + off;
-        uint2 pk;
-        pk.x = pack_bf16x2(silu_f(lo[0]) * hi[0], silu_f(lo[1]) * hi[1]);
-        pk.y = pack_bf16x2(silu_f(lo[2]) * hi[2], silu_f(lo[3]) * hi[3]);
-        *(uint2*)o = pk;
-      } else {  // EPI_QKV
-        const int seq = m / g.S, pos = g.pos0 + (m - seq * g.S);
-        const int hd = g.hd, half_hd = hd >> 1, hq = g.H * hd;
-        if (tl.rot) {
-          const int j = j0 + off;
-          const float4* rp = (const float4*)((const float2*)g.rope + (int64_t)pos * half_hd + j);
-          const float4 cs01 = rp[0], cs23 = rp[1];
-          const float c[4] = {cs01.x, cs01.z, cs23.x, cs23.z}, sn[4] = {cs01.y, cs01.w, cs23.y, cs23.w};
-          uint2 plo, phi;
-          plo.x = pack_bf16x2(lo[0] * c[0] - hi[0] * sn[0], lo[1] * c[1] - hi[1] * sn[1]);
-          plo.y = pack_bf16x2(lo[2] * c[2] - hi[2] * sn[2], lo[3] * c[3] - hi[3] * sn[3]);
-          phi.x = pack_bf16x2(hi[0] * c[0] + lo[0] * sn[0], hi[1] * c[1] + lo[1] * sn[1]);
-          phi.y = pack_bf16x2(hi[2] * c[2] + lo[2] * sn[2], hi[3] * c[3] + lo[3] * sn[3]);
-          bf16_t* dst;
-          if (qk_head < g.H) {
-            dst = (bf16_t*)g.olp + b * g.olp_bstride + (int64_t)m * hq + qk_head * hd + j;
-          } else {
-            const int64_t hidx = b * g.kv_bstride + seq * g.kv_seq_stride + (qk_head - g.H);
-            dst = (bf16_t*)g.kc + hidx * g.kv_head_elems + (int64_t)pos * hd + j;
-          }
-          *(uint2*)dst = plo;
-          *(uint2*)(dst + half_hd) = phi;
-        } else {
-#pragma unroll
-          for (int sgm = 0; sgm < 2; ++sgm) {
-            const int cbase = (sgm ? n_b : n_a) - (g.H + g.Hkv) * hd + off;   // column inside the v section
-            const float* x = sgm ? hi : lo;
-            const int head = cbase / hd, j = cbase - head * hd;
-            const int64_t hidx = b * g.kv_bstride + seq * g.kv_seq_stride + head;
-            bf16_t* vt = (bf16_t*)g.vc + hidx * ((int64_t)hd * g.s_pad) + (int64_t)j * g.s_pad + pos;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) vt[(int64_t)i * g.s_pad] = f32_to_bf16(x[i]);
-          }
-        }
-      }
+      finish(rb, lo, hi);
     }
   }
 }
 
-template <int MI, int RB, int EPI>
-static int launch_skinny_rb(const pt_gemm_args& g, int tiles, hipStream_t s) {
-  const int wgs = tiles / RB;
-  if (g.K % (4 * 16 * 8) == 0)
-    hipLaunchKernelGGL((gemm_skinny_kernel<MI, RB, EPI, 4>), dim3((unsigned)(wgs * g.batch)), dim3(256), 0, s, g, wgs);
-  else
-    hipLaunchKernelGGL((gemm_skinny_kernel<MI, RB, EPI, 2>), dim3((unsigned)(wgs * g.batch)), dim3(256), 0, s, g, wgs);
+// The tiles (blocks of 32 weight rows) of a track are dealt out to wgs_per_track workgroups as evenly as
+// possible: `rem` workgroups take RBHI tiles, the others RBHI - 1 (all take RBHI when rem == 0).  The grid
+// lists the larger workgroups of all tracks first, so that a second round of workgroups fills up evenly.
+// Workgroups that share output tiles (one per K slice, EPI_RESIDUAL only) are neighbours in the grid.
+template <int MI, int RBHI, int EPI>
+__global__ void __launch_bounds__(256) gemm_skinny_kernel(const pt_gemm_args g, int wgs_per_track, int rem, int ksn) {
+  const int unit = blockIdx.x / ksn, ks = blockIdx.x - unit * ksn;
+  if (rem == 0) {
+    const int b = unit / wgs_per_track, wg = unit - b * wgs_per_track;
+    skinny_body<MI, RBHI, EPI>(g, b, wg * RBHI, ks, ksn);
+    return;
+  }
+  const int n_big = rem * g.batch;
+  if (unit < n_big) {
+    const int b = unit / rem, wg = unit - b * rem;
+    skinny_body<MI, RBHI, EPI>(g, b, wg * RBHI, ks, ksn);
+  } else {
+    if constexpr (RBHI > 1) {
+      const int small = wgs_per_track - rem, u2 = unit - n_big;
+      const int b = u2 / small, wg = u2 - b * small;
+      skinny_body<MI, RBHI - 1, EPI>(g, b, rem * RBHI + wg * (RBHI - 1), ks, ksn);
+    }
+  }
+}
+
+// Tuning knob for benchmarks: 0 = automatic, else 256 * workgroups per track + K slices (where the shape allows).
+int pt_gemm_skinny_force = 0;
+
+struct sk_plan { int wpt, ks; };
+
+template <int MI, int RBHI, int EPI>
+static int launch_skinny_rb(const pt_gemm_args& g, int tiles, sk_plan p, hipStream_t s) {
+  const unsigned grid = (unsigned)((int64_t)p.wpt * g.batch * p.ks);
+  constexpr int RING = 4 * (2 * MI + RBHI) * 32 * 128, RED = 4 * MI * 16 * 64 * 4;
+  constexpr int LDS = RING > RED ? RING : RED;
+  auto kern = gemm_skinny_kernel<MI, RBHI, EPI>;
+  static bool configured = false;
+  if (!configured) {
+    PT_HIP_CHECK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS));
+    configured = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), LDS, s, g, p.wpt, tiles % p.wpt, p.ks);
   PT_HIP_CHECK(hipGetLastError());
   return 1;
 }
 
-template <int MI, int EPI>
-static int launch_skinny(const pt_gemm_args& g, int tiles, hipStream_t s) {
-  // more weight-row blocks per workgroup reuse each A fragment more often, as long as enough workgroups remain
-  const int64_t wgs1 = (int64_t)tiles * g.batch;
-  if (tiles % 4 == 0 && wgs1 / 4 >= 256) return launch_skinny_rb<MI, 4, EPI>(g, tiles, s);
-  if (tiles % 2 == 0 && wgs1 / 2 >= 256) return launch_skinny_rb<MI, 2, EPI>(g, tiles, s);
-  return launch_skinny_rb<MI, 1, EPI>(g, tiles, s);
+static int device_cus() {
+  static int n = 0;
+  if (!n) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      n = v;
+    else
+      n = 256;
+  }
+  return n;
 }
 
-// Returns 1 if launched, 0 if the shape is not covered.
-int pt_launch_gemm_skinny(const pt_gemm_args& g, hipStream_t s) {
-  if (g.dtype != PT_BF16 || g.M < 1 || g.M > 64) return 0;
-  if (g.K % (4 * 16 * 4) || g.N % 32) return 0;
-  if ((g.lda & 7) || (g.ldb & 7) || (g.a_bstride & 7) || (g.w_bstride & 7) || (((uintptr_t)g.A | (uintptr_t)g.W) & 15)) return 0;
-  int tiles = g.N / 32;
-  if (g.epi == EPI_SWIGLU) {
-    if (g.N % 64 || (g.olp_bstride & 3) || ((uintptr_t)g.olp & 7)) return 0;
-  } else if (g.epi == EPI_QKV) {
-    if (g.hd % 32 || ((g.H + 2 * g.Hkv) * g.hd) != g.N || (g.olp_bstride & 3) || (g.s_pad & 3)) return 0;
-  } else {
-    if ((g.ldo & 3) || (g.out_bstride & 3) || (g.res_bstride & 3) || (((uintptr_t)g.out | (uintptr_t)g.res) & 15)) return 0;
+// Workgroups per track and K slices.  One workgroup is resident per compute unit (LDS), so the grid runs in
+// rounds of n_cu workgroups; a workgroup's time grows with its K steps (plus a fixed start-up and reduction
+// cost of about six steps) and with the rows it loads per step (its tiles of W plus the shared A rows).
+// K slices (ks_max > 1: residual GEMMs whose caller adds the slices) shorten the rounds of shapes with few tiles.
+static sk_plan plan_skinny(const pt_gemm_args& g, int tiles, int ks_max) {
+  const int n_cu = device_cus();
+  const double a_rows = g.M > 32 ? 0.6 : 0.3;
+  sk_plan best = {(tiles + 3) / 4, 1};
+  double best_cost = 1e30;
+  for (int ks = 1; ks <= ks_max; ++ks) {
+    if (g.K % (ks * 4 * 128)) continue;                          // an even number of K steps per wavefront
+    if (ks > 1 && (int64_t)ks * g.batch * g.M * g.N > (int64_t)PT_SK_PART_FLOATS) break;
+    const double steps = g.K / (ks * 256) + 6.0;
+    const int wpt_min = (tiles + 3) / 4;
+    // candidates: the fewest workgroups, and the grids that fill whole rounds
+    int cand[6], nc = 0;
+    cand[nc++] = wpt_min;
+    cand[nc++] = (tiles + 1) / 2;
+    cand[nc++] = tiles;
+    const int64_t per_round = n_cu;   // workgroups of all tracks and slices in a round
+    for (int rounds = 1; rounds <= 3; ++rounds) {
+      const int64_t w = per_round * rounds / ((int64_t)g.batch * ks);
+      if (w >= wpt_min && w <= tiles && w * g.batch * ks == per_round * rounds) cand[nc++] = (int)w;
+    }
+    for (int i = 0; i < nc; ++i) {
+      const int wpt = cand[i];
+      const int rb_hi = (tiles + wpt - 1) / wpt;
+      const int64_t wgs = (int64_t)wpt * g.batch * ks;
+      const int64_t rounds = (wgs + n_cu - 1) / n_cu;
+      const double cost = rounds * steps * (rb_hi + a_rows);
+      if (cost < best_cost * 0.999) { best_cost = cost; best.wpt = wpt; best.ks = ks; }
+    }
   }
-  if ((int64_t)tiles * g.batch > 0x7fffffff) return 0;
+  if (pt_gemm_skinny_force > 0) {
+    const int fw = pt_gemm_skinny_force >> 8, fks = pt_gemm_skinny_force & 255;
+    if (fw >= (tiles + 3) / 4 && fw <= tiles) best.wpt = fw;
+    best.ks = 1;
+    if (fks > 1 && fks <= ks_max && g.K % (fks * 4 * 128) == 0 && (int64_t)fks * g.batch * g.M * g.N <= (int64_t)PT_SK_PART_FLOATS)
+      best.ks = fks;
+  }
+  return best;
+}
+
+template <int MI, int EPI>
+static int launch_skinny(const pt_gemm_args& g, int tiles, int ks_max, hipStream_t s) {
+  const sk_plan p = plan_skinny(g, tiles, ks_max);
+  switch ((tiles + p.wpt - 1) / p.wpt) {
+    case 4: return launch_skinny_rb<MI, 4, EPI>(g, tiles, p, s);
+    case 3: return launch_skinny_rb<MI, 3, EPI>(g, tiles, p, s);
+    case 2: return launch_skinny_rb<MI, 2, EPI>(g, tiles, p, s);
+    default: return launch_skinny_rb<MI, 1, EPI>(g, tiles, p, s);
+  }
+}
+
+static bool skinny_covers(const pt_gemm_args& g) {
+  if (g.dtype != PT_BF16 || g.M < 1 || g.M > 64) return false;
+  if (g.K % (4 * 128) || g.N % 32) return false;
+  if ((g.lda & 7) || (g.ldb & 7) || (g.a_bstride & 7) || (g.w_bstride & 7) || (((uintptr_t)g.A | (uintptr_t)g.W) & 15)) return false;
+  const int tiles = g.N / 32;
+  if (g.epi == EPI_SWIGLU) {
+    if (g.N % 64 || (g.olp_bstride & 3) || ((uintptr_t)g.olp & 7)) return false;
+  } else if (g.epi == EPI_QKV) {
+    if (g.hd % 32 || ((g.H + 2 * g.Hkv) * g.hd) != g.N || (g.olp_bstride & 3) || (g.s_pad & 3)) return false;
+  } else {
+    if ((g.ldo & 3) || (g.out_bstride & 3) || (g.res_bstride & 3) || (((uintptr_t)g.out | (uintptr_t)g.res) & 15)) return false;
+  }
+  return (int64_t)tiles * g.batch * 16 <= 0x7fffffff;
+}
+
+// Number of K slices the decode kernel would use for this residual GEMM when the caller is ready to add the
+// slices itself (0: the kernel does not cover the shape; 1: no split).
+int pt_gemm_skinny_ksplit(const pt_gemm_args& g) {
+  if (!skinny_covers(g)) return 0;
+  if (g.epi != EPI_RESIDUAL || !g.sk_part || (g.N & 3)) return 1;
+  return plan_skinny(g, g.N / 32, 16).ks;
+}
+
+// Returns 1 if launched, 0 if the shape is not covered.  With allow_split the K slices chosen by
+// pt_gemm_skinny_ksplit are left in g.sk_part instead of the finished residual stream.
+int pt_launch_gemm_skinny(const pt_gemm_args& g, bool allow_split, hipStream_t s) {
+  if (!skinny_covers(g)) return 0;
+  const int tiles = g.N / 32;
+  const int ks_max = allow_split && g.epi == EPI_RESIDUAL && g.sk_part && !(g.N & 3) ? 16 : 1;
   const bool two = g.M > 32;
   switch (g.epi) {
-    case EPI_STORE_F32: return two ? launch_skinny<2, EPI_STORE_F32>(g, tiles, s) : launch_skinny<1, EPI_STORE_F32>(g, tiles, s);
-    case EPI_RESIDUAL: return two ? launch_skinny<2, EPI_RESIDUAL>(g, tiles, s) : launch_skinny<1, EPI_RESIDUAL>(g, tiles, s);
-    case EPI_SWIGLU: return two ? launch_skinny<2, EPI_SWIGLU>(g, tiles, s) : launch_skinny<1, EPI_SWIGLU>(g, tiles, s);
-    case EPI_QKV: return two ? launch_skinny<2, EPI_QKV>(g, tiles, s) : launch_skinny<1, EPI_QKV>(g, tiles, s);
+    case EPI_STORE_F32: return two ? launch_skinny<2, EPI_STORE_F32>(g, tiles, ks_max, s) : launch_skinny<1, EPI_STORE_F32>(g, tiles, ks_max, s);
+    case EPI_RESIDUAL: return two ? launch_skinny<2, EPI_RESIDUAL>(g, tiles, ks_max, s) : launch_skinny<1, EPI_RESIDUAL>(g, tiles, ks_max, s);
+    case EPI_SWIGLU: return two ? launch_skinny<2, EPI_SWIGLU>(g, tiles, ks_max, s) : launch_skinny<1, EPI_SWIGLU>(g, tiles, ks_max, s);
+    case EPI_QKV: return two ? launch_skinny<2, EPI_QKV>(g, tiles, ks_max, s) : launch_skinny<1, EPI_QKV>(g, tiles, ks_max, s);
   }
   return 0;
 }

@@ -89,6 +89,7 @@ int pt_compute_layout(const pt_config* c, pt_layout* l) {
   l->off_rope = off; off = align_up(off + (size_t)((int64_t)c->max_seq * hd * 4), 256);
   l->off_part = off; off = align_up(off + (size_t)(T * B * c->n_heads * l->max_splits * (hd + 2) * 4), 256);
   l->off_last = off; off = align_up(off + (size_t)(B * d * es), 256);
+  l->off_skp = off;  off = align_up(off + (size_t)PT_SK_PART_FLOATS * 4, 256);
   l->ws_bytes = off;
   return PT_OK;
 }
@@ -301,10 +302,12 @@ extern "C" int pt_profile_reset(pt_handle* h) {
 // ---------------------------------------------------------------------------------------------
 // The forward pass.  rows = B*S rows per track; row m is sequence m / S at position pos0 + m % S.
 // ---------------------------------------------------------------------------------------------
-static int run_gemm(pt_handle* h, const pt_gemm_args& g, int cls) {
+static int run_gemm(pt_handle* h, const pt_gemm_args& g_in, int cls) {
   prof_scope ps(h, cls);
+  pt_gemm_args g = g_in;
+  g.sk_part = (float*)(h->ws + h->lay.off_skp);
   if (h->path == PT_PATH_AUTO) {
-    int r = g.M <= 64 ? pt_launch_gemm_skinny(g, h->stream) : 0;
+    int r = g.M <= 64 ? pt_launch_gemm_skinny(g, false, h->stream) : 0;
     if (r < 0) return r;
     if (r == 1) return PT_OK;
     r = pt_launch_gemm_mfma(g, h->stream);
@@ -312,6 +315,35 @@ static int run_gemm(pt_handle* h, const pt_gemm_args& g, int cls) {
     if (r == 1) return PT_OK;
   }
   return pt_launch_gemm_generic(g, h->stream);
+}
+
+// Residual GEMM (out = res + A W^T) followed, when gain is given, by the RMSNorm of the new residual stream
+// into `normed`.  In decode the GEMM may split K over workgroups; the kernel that adds the slices also adds the
+// residual and normalises.
+static int run_residual_gemm_norm(pt_handle* h, const pt_gemm_args& g_in, int cls, const float* gain,
+                                  int64_t gain_bstride, void* normed) {
+  const pt_config& c = h->cfg;
+  pt_gemm_args g = g_in;
+  g.sk_part = (float*)(h->ws + h->lay.off_skp);
+  const int64_t rows = g.M;
+  int rc;
+  if (h->path == PT_PATH_AUTO && g.M <= 64 && g.N == g.ldo && g.N <= 8192 && pt_gemm_skinny_ksplit(g) > 1) {
+    const int slices = pt_gemm_skinny_ksplit(g);
+    {
+      prof_scope ps(h, cls);
+      rc = pt_launch_gemm_skinny(g, true, h->stream);
+      if (rc < 0) return rc;
+      if (rc != 1) return pt_set_error(PT_ERR_HIP, "decode GEMM refused a shape it had accepted");
+    }
+    prof_scope ps(h, PT_K_RMSNORM);
+    return pt_launch_resnorm(g.sk_part, slices, g.res, g.res_bstride, g.out, g.out_bstride, gain, gain_bstride,
+                             gain ? normed : nullptr, rows * g.N, g.batch, rows, g.N, c.rms_eps, h->stream);
+  }
+  rc = run_gemm(h, g_in, cls);
+  if (rc || !gain) return rc;
+  prof_scope ps(h, PT_K_RMSNORM);
+  return pt_launch_rmsnorm(g.out, g.out_bstride, gain, gain_bstride, normed, rows * g.N, c.dtype, g.batch, rows,
+                           g.N, c.rms_eps, h->stream);
 }
 
 static int run_attention(pt_handle* h, const pt_attn_args& a) {
@@ -366,6 +398,7 @@ static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
   const int64_t kv_head_k = (int64_t)c.max_seq * c.head_dim;
   const int64_t kv_head_v = (int64_t)c.head_dim * l.s_pad;
   int merge_idx = 0;
+  bool normed = false;   // abuf already holds the normalised input of this layer's attention half
   for (int64_t layer = 0; layer < L; ++layer) {
     const bool first = (layer % c.block_depth) == 0;
     const float* src = first ? x : hres;
@@ -374,12 +407,12 @@ static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
     const int64_t w_bstride = L * l.layer_w_elems;
 
     // attention half
-    {
+    if (!normed) {
       prof_scope ps(h, PT_K_RMSNORM);
       rc = pt_launch_rmsnorm(src, src_bstride, gains + (layer * 2 + 0) * d, L * 2 * d, abuf, rows * d,
                              c.dtype, (int32_t)T, rows, (int32_t)d, c.rms_eps, st);
+      if (rc) return rc;
     }
-    if (rc) return rc;
     pt_gemm_args g;
     memset(&g, 0, sizeof(g));
     g.A = abuf; g.a_bstride = rows * d; g.lda = (int32_t)d;
@@ -418,16 +451,11 @@ static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
     g.dtype = c.dtype; g.epi = EPI_RESIDUAL;
     g.out = hres; g.out_bstride = rows * d; g.ldo = (int32_t)d;
     g.res = src; g.res_bstride = src_bstride;
-    rc = run_gemm(h, g, PT_K_GEMM_OUT);
+    // ... and the RMSNorm that opens the feed-forward half
+    rc = run_residual_gemm_norm(h, g, PT_K_GEMM_OUT, gains + (layer * 2 + 1) * d, L * 2 * d, abuf);
     if (rc) return rc;
 
     // feed-forward half
-    {
-      prof_scope ps(h, PT_K_RMSNORM);
-      rc = pt_launch_rmsnorm(hres, rows * d, gains + (layer * 2 + 1) * d, L * 2 * d, abuf, rows * d,
-                             c.dtype, (int32_t)T, rows, (int32_t)d, c.rms_eps, st);
-    }
-    if (rc) return rc;
     memset(&g, 0, sizeof(g));
     g.A = abuf; g.a_bstride = rows * d; g.lda = (int32_t)d;
     g.W = wl + (size_t)((l.wqkv_elems + l.wo_elems) * es); g.w_bstride = w_bstride; g.ldb = (int32_t)d;
@@ -443,8 +471,12 @@ static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
     g.dtype = c.dtype; g.epi = EPI_RESIDUAL;
     g.out = hres; g.out_bstride = rows * d; g.ldo = (int32_t)d;
     g.res = hres; g.res_bstride = rows * d;
-    rc = run_gemm(h, g, PT_K_GEMM_DOWN);
+    // inside a block the next layer's first RMSNorm follows directly; at a block end the merge comes first
+    const bool block_end = (layer + 1) % c.block_depth == 0;
+    rc = run_residual_gemm_norm(h, g, PT_K_GEMM_DOWN, block_end ? nullptr : gains + ((layer + 1) * 2 + 0) * d,
+                                L * 2 * d, abuf);
     if (rc) return rc;
+    normed = !block_end;
 
     // Algorithm 1: after every D-th layer, all-reduce the track activations; every track
     // continues from the reduced activation.

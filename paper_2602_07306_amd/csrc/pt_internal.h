@@ -57,6 +57,7 @@ struct pt_layout {
   size_t off_rope;    // fp32 [max_seq, hd/2, 2] cos, sin
   size_t off_part;    // fp32 split-K decode partials
   size_t off_last;    // dtype [max_batch, d] normed last rows for the head
+  size_t off_skp;     // fp32 K slices of the decode residual GEMMs, [slice][T][rows][d]
   size_t ws_bytes;
   int32_t elem_size;  // 4 or 2
   int32_t max_splits;
@@ -129,13 +130,20 @@ struct pt_gemm_args {
   // kv_head_elems = max_seq * hd elements of K and hd * s_pad elements of V^T
   int64_t kv_bstride, kv_seq_stride, kv_head_elems;
   int32_t H, Hkv, hd, S, pos0, s_pad;
+  // K-slice scratch of the decode kernel, PT_SK_PART_FLOATS floats (may be null: K is not split over workgroups)
+  float* sk_part;
 };
+
+enum { PT_SK_PART_FLOATS = 16 << 20 };
 
 int pt_launch_gemm_generic(const pt_gemm_args& g, hipStream_t s);
 // Returns 1 if the MFMA kernel family supports this problem (then it has been launched), 0 if not.
 int pt_launch_gemm_mfma(const pt_gemm_args& g, hipStream_t s);
-// Weight-streaming kernel for M <= 64 (decode); same return convention.
-int pt_launch_gemm_skinny(const pt_gemm_args& g, hipStream_t s);
+// Weight-streaming kernel for M <= 64 (decode); same return convention.  With allow_split a residual GEMM may
+// leave pt_gemm_skinny_ksplit(g) > 1 K slices in g.sk_part ([slice][batch][M][N] fp32) instead of writing
+// out = res + product; pt_launch_resnorm adds them up.
+int pt_launch_gemm_skinny(const pt_gemm_args& g, bool allow_split, hipStream_t s);
+int pt_gemm_skinny_ksplit(const pt_gemm_args& g);
 
 // ---------------------------------------------------------------------------------------------
 // Attention over the KV cache.  q/o: [batch_t][rows][H*hd]; row m is sequence m / S at position
@@ -175,6 +183,11 @@ int pt_launch_merge(const void* const* tracks, int32_t n, int64_t elems, int32_t
 int pt_launch_copy_f32(const float* src, float* dst, int64_t elems, hipStream_t s);
 int pt_launch_argmax(const float* logits, int32_t rows, int32_t vocab, int32_t* out, hipStream_t s);
 int pt_launch_rope_table(float* table, int32_t max_seq, int32_t hd, float theta, hipStream_t s);
+// h[b][r][:] = res[b][r][:] + sum over slices of part[slice][b][r][:]  (slices added in order), then, when out
+// is given, out[b][r][:] = RMSNorm(h[b][r][:]) * gains[b][:].  res may alias h.  d <= 8192, bf16 out.
+int pt_launch_resnorm(const float* part, int32_t slices, const float* res, int64_t res_bstride, float* h,
+                      int64_t h_bstride, const float* gains, int64_t g_bstride, void* out, int64_t out_bstride,
+                      int32_t batch, int64_t rows, int32_t d, float eps, hipStream_t s);
 int pt_launch_fill_f32(float* dst, int64_t n, float v, hipStream_t s);
 // weight access: tensor ids are PT_W_*; phys points at the tensor's physical base
 int pt_launch_weight_init(pt_handle* h, uint64_t seed);

@@ -66,6 +66,9 @@ CASES = {
     "three_tracks": (dict(n_tracks=3, n_layers=3, block_depth=1, merge_scale=1.0 / 3), 1, 64, 1),
     "split_decode": (dict(max_batch=1, max_seq=1024), 1, 704, 3),   # decode context split in two, ragged tail
     "one_token_prompt": (dict(), 2, 1, 3),
+    # grouped-query decode with a split, ragged context; 16 query heads on one KV head
+    "gqa_split_decode": (dict(n_kv_heads=1, max_batch=2, max_seq=1024), 2, 701, 3),
+    "gqa_16_per_group": (dict(n_heads=16, n_kv_heads=1, head_dim=64, max_seq=512), 1, 333, 2),
 }
 
 
