@@ -117,7 +117,7 @@ def run_prefill(args, torch, PB, I):
 
 
 def run_decode(args, torch, PB, I):
-    B, prompt, steps = 32, 2048, 128
+    B, prompt, steps = 32, 2048, args.decode_steps
     cfg = I.config_mid(max_batch=B, max_seq=prompt + steps + 64)
     model = PB.PTModel(cfg)
     model.pt_init_weights(1)
@@ -142,13 +142,17 @@ def run_decode(args, torch, PB, I):
     wbytes, kv_step, kv_launch = decode_bytes(cfg, B, prompt + steps // 2)
     gbs = kv_launch / (ms_attn / n_attn * 1e-3) / 1e9
     med = per[len(per) // 2]
-    out = {"workload": "Mid PT decode: batch 32, 2048-token prompts, 128 KV-cached steps",
+    traffic = None   # HBM-side bytes per launch from the rocprofv3 --pmc passes kept under profiles/
+    tpath = os.path.join(ROOT, "profiles", "mid_decode_attn_traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get("traffic_bytes_per_launch")
+    out = {"workload": "Mid PT decode: batch 32, 2048-token prompts, %d KV-cached steps" % steps,
            "ms_per_step_median": med, "ms_per_step_min": per[0], "ms_per_token": med / B,
            "prompt_prefill_s": prefill_s,
            "step_bytes_GB": (wbytes + kv_step) / 1e9, "step_GBs": (wbytes + kv_step) / (med * 1e-3) / 1e9,
            "step_frac_of_hbm_peak": (wbytes + kv_step) / (med * 1e-3) / 1e9 / HBM_PEAK_GBS,
            "roofline": {"bound": "hbm", "kernel": "attn_decode_kernel<64>", "achieved": gbs,
-                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": traffic,
                         "launches": n_attn, "avg_launch_ms": ms_attn / n_attn,
                         "bytes_per_launch": kv_launch}}
     model.close()
@@ -186,6 +190,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--skip-decode", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--decode-steps", type=int, default=128,
+                    help="KV-cached decode steps of the decode leg (a counter pass uses a handful)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference for the HBM byte counters)")
     args = ap.parse_args()
