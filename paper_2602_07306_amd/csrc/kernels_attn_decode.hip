@@ -188,8 +188,9 @@ __global__ void __launch_bounds__(64) attn_decode_combine_kernel(const pt_attn_a
 // which is the prefill formulation with the query heads of a group in place of query positions (MFMA
 // column = query head, padded to 32).  A workgroup owns one key range of one (track, sequence, KV head);
 // its 4 wavefronts take the 32-key blocks of the range round-robin, each with its own online-softmax
-// state, and merge the four states through LDS.  Operands go from global memory directly into the MFMA
-// register layout (16 bytes per lane); nothing is staged because nothing is reused.
+// state, and merge the four states through LDS.  The cache is read by the whole workgroup in tiles of 128
+// keys as 16-byte pieces of whole cache lines and handed to the MFMAs through LDS: lane-per-row loads in
+// operand layout touch 32 cache lines per instruction and hold the CU's memory path below what HBM delivers.
 // ------------------------------------------------------------------------------------------------
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
@@ -201,10 +202,21 @@ union dpk8 {
 
 #define DEC_GMAX 16
 
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+// Tiles of 128 keys: K [128 x hd] (one contiguous piece of the cache) and V^T [hd x 128] are read by the whole
+// workgroup as 16-byte pieces of whole cache lines, held in registers while the previous tile is multiplied,
+// and parked in one of two LDS buffers (16-byte chunk c of row r at position c ^ swizzle(r)); wavefront w then
+// works on keys 32w .. 32w+31 of the tile with fragments read from LDS.
 template <int HD>
 __global__ void __launch_bounds__(256) attn_decode_gqa_kernel(const pt_attn_args a, int nsplit, int keys_per_split) {
   constexpr int KS = HD / 16, HB = HD / 32;
-  __shared__ float red_o[4][HD][DEC_GMAX];
+  constexpr int KROW = HD * 2;                  // bytes of a key row
+  constexpr int KCH = KROW / 16;                // 16-byte chunks per key row
+  constexpr int TILE = 128 * KROW;              // bytes of the K tile = bytes of the V^T tile (hd rows x 256 B)
+  constexpr int NLD = TILE / 16 / 256;          // 16-byte pieces per thread and operand
+  extern __shared__ __attribute__((aligned(1024))) char smem[];   // 2 buffers x (K tile + V^T tile)
+  float (*red_o)[HD][DEC_GMAX] = (float (*)[HD][DEC_GMAX])smem;   // reuses the tiles after the key loop
   __shared__ float red_m[4][32], red_l[4][32];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
@@ -215,9 +227,11 @@ __global__ void __launch_bounds__(256) attn_decode_gqa_kernel(const pt_attn_args
   const int k0 = split * keys_per_split;
   const int k1 = min(nkeys, k0 + keys_per_split);
   const int64_t hidx = t * a.kv_bstride + seq * a.kv_seq_stride + kvh;
-  const bf16_t* K = (const bf16_t*)a.kc + hidx * a.kv_head_elems;
-  const bf16_t* Vt = (const bf16_t*)a.vc + hidx * ((int64_t)HD * a.s_pad);
+  const char* K = (const char*)((const bf16_t*)a.kc + hidx * a.kv_head_elems);
+  const char* Vt = (const char*)((const bf16_t*)a.vc + hidx * ((int64_t)HD * a.s_pad));
   const int64_t qbase = t * a.q_bstride + (int64_t)seq * (a.H * HD) + (int64_t)kvh * G * HD;
+  auto kswz = [](int row) { return HD == 128 ? (row & 15) : ((row >> 1) & 7); };   // K rows of 256 or 128 bytes
+  auto vswz = [](int row) { return row & 15; };                                   // V^T rows of 256 bytes
 
   // B operand of S^T: query head l32 of the group (zero beyond G)
   bf16x8_t qf[KS];
@@ -231,6 +245,45 @@ __global__ void __launch_bounds__(256) attn_decode_gqa_kernel(const pt_attn_args
   const int krow = (l32 & ~12) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);   // MFMA row r of S^T holds key pi(r)
   const float c_log2 = 1.4426950408889634f / sqrtf((float)HD);
 
+  // staging: piece i of this thread is chunk id c = tid + 256 i of the tile
+  u32x4_t kreg[NLD], vreg[NLD];
+  auto load_tile = [&](int kb) {
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const int c = tid + 256 * i;
+      const int kr = c / KCH, kc = c - kr * KCH;                 // key row, chunk of K
+      kreg[i] = *(const u32x4_t*)(K + (int64_t)min(kb + kr, k1 - 1) * KROW + kc * 16);
+      const int vr = c >> 4, vc = c & 15;                        // hd row, chunk (8 keys) of V^T
+      const int key = min(kb + vc * 8, (k1 - 1) & ~7);           // never past the chunk that holds the last key
+      vreg[i] = *(const u32x4_t*)(Vt + ((int64_t)vr * a.s_pad + key) * 2);
+    }
+  };
+  auto park_tile = [&](int buf, int kb) {
+    char* kt = smem + buf * (2 * TILE);
+    char* vt = kt + TILE;
+    const bool tail = kb + 128 > k1;   // workgroup-uniform
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const int c = tid + 256 * i;
+      const int kr = c / KCH, kc = c - kr * KCH;
+      *(u32x4_t*)(kt + kr * KROW + ((kc ^ kswz(kr)) * 16)) = kreg[i];
+      const int vr = c >> 4, vc = c & 15;
+      u32x4_t v = vreg[i];
+      if (tail) {
+        // cache bytes beyond the range are not data: zero them so that 0 * x stays 0
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int key = kb + vc * 8 + 2 * j;
+          uint32_t w = v[j];
+          if (key >= k1) w &= 0xffff0000u;
+          if (key + 1 >= k1) w &= 0x0000ffffu;
+          v[j] = w;
+        }
+      }
+      *(u32x4_t*)(vt + vr * 256 + ((vc ^ vswz(vr)) * 16)) = v;
+    }
+  };
+
   f32x16_t oacc[HB];
 #pragma unroll
   for (int hb = 0; hb < HB; ++hb)
@@ -238,74 +291,69 @@ __global__ void __launch_bounds__(256) attn_decode_gqa_kernel(const pt_attn_args
     for (int v = 0; v < 16; ++v) oacc[hb][v] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
-  for (int kb = k0 + wave * 32; kb < k1; kb += 128) {
-    const bool tail = kb + 32 > k1;   // wave-uniform: some keys of the block lie beyond the range
-    f32x16_t s;
+  const int kfr_row = wave * 32 + krow;         // row of the K tile this lane multiplies
+  load_tile(k0);
+  park_tile(0, k0);
+  __syncthreads();
+  int buf = 0;
+  for (int kb = k0; kb < k1; kb += 128, buf ^= 1) {
+    const bool more = kb + 128 < k1;
+    if (more) load_tile(kb + 128);
+    const char* kt = smem + buf * (2 * TILE);
+    const char* vt = kt + TILE;
+    const int kw = kb + wave * 32;              // first key of this wavefront's block
+    if (kw < k1) {                              // wave-uniform
+      f32x16_t s;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) s[v] = 0.f;
-    // rows beyond the range are clamped to a valid row; their scores are masked below
-    const bf16_t* kp = K + (int64_t)min(kb + krow, k1 - 1) * HD + half * 8;
-    bf16x8_t kf[KS];
+      for (int v = 0; v < 16; ++v) s[v] = 0.f;
 #pragma unroll
-    for (int kk = 0; kk < KS; ++kk) kf[kk] = *(const bf16x8_t*)(kp + kk * 16);
-    dpk8 vf[HB][2];
+      for (int kk = 0; kk < KS; ++kk) {
+        const bf16x8_t kf = *(const bf16x8_t*)(kt + kfr_row * KROW + (((2 * kk + half) ^ kswz(kfr_row)) * 16));
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s, 0, 0, 0);
+      }
+      // register v: key kw + 16*(v/8) + 8*half + v%8, query head l32
+      if (kw + 32 > k1) {
 #pragma unroll
-    for (int hb = 0; hb < HB; ++hb)
+        for (int v = 0; v < 16; ++v)
+          if (kw + 16 * (v >> 3) + 8 * half + (v & 7) >= k1) s[v] = -INFINITY;
+      }
+      float mx = -INFINITY;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[v]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m_run, mx);
+      const float corr = __builtin_amdgcn_exp2f((m_run - m_new) * c_log2);
+      const float mc = m_new * c_log2;
+      float psum = 0.f;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        s[v] = __builtin_amdgcn_exp2f(fmaf(s[v], c_log2, -mc));
+        psum += s[v];
+      }
+      l_run = l_run * corr + psum;
+      m_run = m_new;
+      if (__any(corr != 1.0f)) {
+#pragma unroll
+        for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) oacc[hb][v] *= corr;
+      }
+      dpk8 pf[2];
 #pragma unroll
       for (int u = 0; u < 2; ++u)
-        vf[hb][u].v = *(const bf16x8_t*)(Vt + (int64_t)(hb * 32 + l32) * a.s_pad + kb + 16 * u + 8 * half);
 #pragma unroll
-    for (int kk = 0; kk < KS; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], s, 0, 0, 0);
-    // register v: key kb + 16*(v/8) + 8*half + v%8, query head l32
-    if (tail) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v)
-        if (kb + 16 * (v >> 3) + 8 * half + (v & 7) >= k1) s[v] = -INFINITY;
-      // cache bytes beyond the range are not data: zero them so that 0 * x stays 0
+        for (int i = 0; i < 4; ++i) pf[u].u[i] = pack_bf16x2(s[8 * u + 2 * i], s[8 * u + 2 * i + 1]);
 #pragma unroll
       for (int hb = 0; hb < HB; ++hb)
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const int key = kb + 16 * u + 8 * half + 2 * i;
-            uint32_t w = vf[hb][u].u[i];
-            if (key >= k1) w &= 0xffff0000u;
-            if (key + 1 >= k1) w &= 0x0000ffffu;
-            vf[hb][u].u[i] = w;
-          }
+        for (int u = 0; u < 2; ++u) {
+          const int vr = hb * 32 + l32;
+          const bf16x8_t vf = *(const bf16x8_t*)(vt + vr * 256 + (((wave * 4 + 2 * u + half) ^ vswz(vr)) * 16));
+          oacc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u].v, oacc[hb], 0, 0, 0);
+        }
     }
-    float mx = -INFINITY;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[v]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);
-    const float corr = __builtin_amdgcn_exp2f((m_run - m_new) * c_log2);
-    const float mc = m_new * c_log2;
-    float psum = 0.f;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      s[v] = __builtin_amdgcn_exp2f(fmaf(s[v], c_log2, -mc));
-      psum += s[v];
-    }
-    l_run = l_run * corr + psum;
-    m_run = m_new;
-    if (__any(corr != 1.0f)) {
-#pragma unroll
-      for (int hb = 0; hb < HB; ++hb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) oacc[hb][v] *= corr;
-    }
-    dpk8 pf[2];
-#pragma unroll
-    for (int u = 0; u < 2; ++u)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) pf[u].u[i] = pack_bf16x2(s[8 * u + 2 * i], s[8 * u + 2 * i + 1]);
-#pragma unroll
-    for (int hb = 0; hb < HB; ++hb)
-#pragma unroll
-      for (int u = 0; u < 2; ++u)
-        oacc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[hb][u].v, pf[u].v, oacc[hb], 0, 0, 0);
+    if (more) park_tile(buf ^ 1, kb + 128);     // last read while tile kb - 128 was multiplied
+    __syncthreads();
   }
   // the two half-waves of a query head hold disjoint key subsets with a common running max
   l_run += __shfl_xor(l_run, 32, 64);
@@ -339,6 +387,20 @@ __global__ void __launch_bounds__(256) attn_decode_gqa_kernel(const pt_attn_args
   }
 }
 
+template <int HD>
+static int launch_gqa(const pt_attn_args& a, dim3 grid, int nsplit, int kps, hipStream_t s) {
+  constexpr int LDS = 2 * 2 * 128 * HD * 2;
+  static_assert(LDS >= 4 * HD * DEC_GMAX * 4, "merge buffer must fit the tiles");
+  auto kern = attn_decode_gqa_kernel<HD>;
+  static bool configured = false;
+  if (!configured) {
+    PT_HIP_CHECK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS));
+    configured = true;
+  }
+  hipLaunchKernelGGL(kern, grid, dim3(256), LDS, s, a, nsplit, kps);
+  return PT_OK;
+}
+
 int pt_launch_attn_decode(const pt_attn_args& a, hipStream_t s) {
   if (a.dtype != PT_BF16 || a.S != 1) return 0;
   if (a.hd != 64 && a.hd != 128) return 0;
@@ -358,10 +420,8 @@ int pt_launch_attn_decode(const pt_attn_args& a, hipStream_t s) {
     kps = (kps + 127) / 128 * 128;
     nsplit = (nkeys + kps - 1) / kps;      // no empty split
     dim3 grid((unsigned)nsplit, (unsigned)a.Hkv, (unsigned)z);
-    if (a.hd == 64)
-      hipLaunchKernelGGL(attn_decode_gqa_kernel<64>, grid, dim3(256), 0, s, a, nsplit, kps);
-    else
-      hipLaunchKernelGGL(attn_decode_gqa_kernel<128>, grid, dim3(256), 0, s, a, nsplit, kps);
+    const int rc = a.hd == 64 ? launch_gqa<64>(a, grid, nsplit, kps, s) : launch_gqa<128>(a, grid, nsplit, kps, s);
+    if (rc) return rc;
     if (nsplit > 1)
       hipLaunchKernelGGL(attn_decode_combine_kernel, dim3((unsigned)a.H, (unsigned)z), dim3(64), 0, s, a, nsplit);
     PT_HIP_CHECK(hipGetLastError());
