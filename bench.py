@@ -183,6 +183,53 @@ def run_cpu_baseline(I):
             "sample": "sequence 0 of the 4 x 1024-token batch (1024 tokens, full model), %.1f s" % dt}
 
 
+def run_paper_sweep(args, torch, PB, I):
+    """Latency-mode shape of the paper's serving tables (Section 3.3: batch 1, input lengths 1024 ... 63488,
+    30B-shaped PT model, track block depth 2, 4, 8) on one GPU with all 8 tracks resident: time to first token
+    = one prefill, time per output token = mean of the KV-cached decode steps that follow.  Widths are this
+    build's choice (inputs.config_paper30b); the paper's numbers are for 8 GPUs and are context only."""
+    lengths = [int(x) for x in args.sweep_lengths.split(",")]
+    out = []
+    for D in [int(x) for x in args.sweep_depths.split(",")]:
+        cfg = I.config_paper30b(block_depth=D, max_batch=1, max_seq=max(lengths) + args.sweep_decode_steps + 8)
+        model = PB.PTModel(cfg)
+        model.pt_init_weights(5)
+        logits = torch.empty((1, cfg.vocab), dtype=torch.float32, device="cuda")
+        nxt = torch.zeros((1,), dtype=torch.int32, device="cuda")
+        warm = torch.from_numpy(I.make_tokens(5, 1, 256, cfg.vocab)).cuda()
+        model.pt_prefill(warm, logits_mode=PB.PT_LOGITS_LAST, logits_out=logits)
+        torch.cuda.synchronize()
+        for S in lengths:
+            tokens = torch.from_numpy(I.make_tokens(5, 1, S, cfg.vocab)).cuda()
+            model.pt_reset()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            model.pt_prefill(tokens, logits_mode=PB.PT_LOGITS_LAST, logits_out=logits)
+            torch.cuda.synchronize()
+            ttft = time.perf_counter() - t0
+            nxt.copy_(logits.argmax(dim=-1).to(torch.int32))
+            model.pt_decode_step(nxt, logits_out=logits, argmax_out=nxt, want_argmax=True)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.sweep_decode_steps):
+                model.pt_decode_step(nxt, logits_out=logits, argmax_out=nxt, want_argmax=True)
+            torch.cuda.synchronize()
+            tpot = (time.perf_counter() - t0) / args.sweep_decode_steps
+            flops, _ = prefill_flops(cfg, 1, S, 1)
+            wbytes, kv_step, _ = decode_bytes(cfg, 1, S + 1 + args.sweep_decode_steps // 2)
+            rec = {"block_depth": D, "input_len": S, "ttft_ms": ttft * 1e3, "tpot_ms": tpot * 1e3,
+                   "prefill_TFLOPs": flops / ttft / 1e12, "decode_GBs": (wbytes + kv_step) / tpot / 1e9,
+                   "merges_per_forward": cfg.n_layers // D}
+            log("paper sweep D=%d input %6d: TTFT %9.2f ms (%.0f TFLOP/s), TPOT %6.2f ms (%.0f GB/s)" % (
+                D, S, rec["ttft_ms"], rec["prefill_TFLOPs"], rec["tpot_ms"], rec["decode_GBs"]))
+            out.append(rec)
+            del tokens
+        model.close()
+        del model
+        torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -194,6 +241,12 @@ def main():
                     help="KV-cached decode steps of the decode leg (a counter pass uses a handful)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference for the HBM byte counters)")
+    ap.add_argument("--paper-sweep", action="store_true",
+                    help="instead of the benchmark: TTFT / TPOT at batch 1 over input lengths for the "
+                         "30B-shaped PT model at track block depth 2, 4, 8 (one JSON line)")
+    ap.add_argument("--sweep-lengths", default="1024,4096,16384,63488")
+    ap.add_argument("--sweep-depths", default="2,4,8")
+    ap.add_argument("--sweep-decode-steps", type=int, default=32)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs the PT forward on ONE GPU (all tracks resident); "
@@ -213,6 +266,12 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    if args.paper_sweep:
+        print(json.dumps({"paper_sweep": run_paper_sweep(args, torch, PB, I), "n_gpus": 1, "dtype": "bf16",
+                          "data": "synthetic",
+                          "workload": "30B-shaped PT model (8 tracks x 48 layers, 8 query heads / 1 KV head per "
+                                      "track, head_dim 128, per-track d_model 3072, FFN 8192), batch 1"}), flush=True)
+        return
     pre = run_prefill(args, torch, PB, I)
     log("prefill: %.3f ms/step, %.0f tokens/s, %.1f%% of bf16 MFMA peak end to end" % (
         pre["ms_step"], pre["tokens_per_s"],

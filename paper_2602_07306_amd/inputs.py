@@ -275,6 +275,15 @@ def config_large(max_batch: int = 8, max_seq: int = 4096, n_kv_heads: int = 16) 
                     max_batch=max_batch, max_seq=max_seq, dtype=PT_BF16)
 
 
+def config_paper30b(block_depth: int = 8, max_batch: int = 1, max_seq: int = 4096) -> PTConfig:
+    """Shape of the paper's 30B PT model (Section 3.1, Table 1): 8 tracks, 48 layers, 8 query heads and 1 KV
+    head per track, track block depth 2, 4 or 8.  The paper prints no widths: per-track d_model 3072,
+    head_dim 128 and FFN 8192 are chosen here so that the 8 tracks hold about 31.7 B parameters."""
+    return PTConfig(n_tracks=8, n_layers=48, block_depth=block_depth, d_model=3072, n_heads=8,
+                    n_kv_heads=1, head_dim=128, d_ffn=8192, vocab=32000, max_batch=max_batch,
+                    max_seq=max_seq, dtype=PT_BF16)
+
+
 def config_share(max_batch: int = 2, max_seq: int = 4096) -> PTConfig:
     return PTConfig(n_tracks=1, n_layers=8, block_depth=8, d_model=8192, n_heads=64, n_kv_heads=64,
                     head_dim=128, d_ffn=28672, vocab=0, max_batch=max_batch, max_seq=max_seq,
