@@ -197,6 +197,7 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
   } else {  // EPI_QKV
     const int hd = g.hd, half = hd >> 1, hq = g.H * hd, hk = g.Hkv * hd;
     const bool wide = hd == 128;     // partner tile distance (hd/2)/32: 1 for hd 64, 2 for hd 128
+    const int hd_sh = wide ? 7 : 6;  // hd is 64 or 128 here: shifts and masks instead of runtime divisions
     const bool s4 = (g.S & 3) == 0;  // 4 consecutive rows of a register group lie in one sequence
     constexpr int QPITCH = TN + 8;   // bf16 elements per staged row of q / k
     constexpr int VPITCH = 32 + 8;   // bf16 elements per staged V^T row (32 positions)
@@ -210,22 +211,53 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
       if ((g.S & 31) == 0 && (g.pos0 & 7) == 0 && wave_n < g.N) {
         staged_done = true;
         const bool is_qk = wave_n < hq + hk, is_q = wave_n < hq;
+        // cos/sin of (position, column): the table is read once per 32-row block, for the lane's first row;
+        // the lane's other rows follow by rotating with the table's entries for 1 and 5 positions (its rows
+        // are r, r+1, r+2, r+3, r+8, ...).  All loads are issued before the first staging store: a load after
+        // a store through the staging pointer would wait for it, and the registers to keep one table entry
+        // per accumulator element in flight are not there.  With hd = 64 every low-half tile uses column
+        // col_l, with hd = 128 the two low-half tiles use col_l and col_l + 32.
+        float2 cs_base[MI][2], rot1[2], rot5[2];
+        if (is_qk) {
+          const float2* tab = (const float2*)g.rope + col_l;
+          rot1[0] = tab[half];
+          rot5[0] = tab[5 * half];
+          if (wide) { rot1[1] = tab[half + 32]; rot5[1] = tab[5 * half + 32]; }
+          static_for<MI>([&](auto MI_) {
+            constexpr int mi = decltype(MI_)::value;
+            const int mrow0 = min(wave_m + mi * 32, g.M - 32);
+            const int seq = mrow0 / g.S, pos0b = g.pos0 + (mrow0 - seq * g.S);
+            const float2* rp = tab + (int64_t)(pos0b + row_l) * half;
+            cs_base[mi][0] = rp[0];
+            if (wide) cs_base[mi][1] = rp[32];
+          });
+        }
         static_for<MI>([&](auto MI_) {
           constexpr int mi = decltype(MI_)::value;
           const int mrow0 = wave_m + mi * 32;           // first row of the block
           if (mrow0 < g.M) {
             const int seq = mrow0 / g.S, pos0b = g.pos0 + (mrow0 - seq * g.S);
             if (is_qk) {
+              float2 cs_cur[2] = {cs_base[mi][0], wide ? cs_base[mi][1] : cs_base[mi][0]};
               static_for<16>([&](auto V_) {
                 constexpr int v = decltype(V_)::value;
                 const int row_in = 8 * (v >> 2) + row_l + (v & 3);
-                const float2* rp = (const float2*)g.rope + (int64_t)(pos0b + row_in) * half + col_l;
+                if constexpr (v > 0) {
+#pragma unroll
+                  for (int w = 0; w < 2; ++w) {
+                    if (w == 1 && !wide) break;
+                    const float2 r = (v & 3) == 0 ? rot5[w] : rot1[w];
+                    const float2 c = cs_cur[w];
+                    cs_cur[w].x = c.x * r.x - c.y * r.y;
+                    cs_cur[w].y = c.y * r.x + c.x * r.y;
+                  }
+                }
                 static_for<NI>([&](auto NI_) {
                   constexpr int ni = decltype(NI_)::value;
                   constexpr int p1 = ni + 1 < NI ? ni + 1 : ni, p2 = ni + 2 < NI ? ni + 2 : ni;
-                  const int jb = (wave_n + ni * 32) % hd;   // wave-uniform
+                  const int jb = (wave_n + ni * 32) & (hd - 1);   // wave-uniform
                   if (jb < half) {
-                    const float2 cs = rp[jb];
+                    const float2 cs = jb == 0 ? cs_cur[0] : cs_cur[1];
                     const float lo = acc[mi][ni][v];
                     const float hi = wide ? acc[mi][p2][v] : acc[mi][p1][v];
                     stage[row_in * QPITCH + ni * 32 + col_l] = f32_to_bf16(lo * cs.x - hi * cs.y);
@@ -236,7 +268,7 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
               constexpr int LPR = TN / 8, RPI = 64 / LPR;
               const int c8 = (lane % LPR) * 8;
               const int c = (is_q ? wave_n : wave_n - hq) + c8;       // column inside the q or k section
-              const int head = c / hd, j = c - head * hd;
+              const int head = c >> hd_sh, j = c & (hd - 1);
               static_for<32 / RPI>([&](auto IT_) {
                 constexpr int it = decltype(IT_)::value;
                 const int row_in = it * RPI + lane / LPR;
@@ -265,7 +297,7 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
                 const int col = it * 16 + (lane >> 2);
                 const u32x4_t val = *(const u32x4_t*)(stage + col * VPITCH + p8);
                 const int c = wave_n - hq - hk + col;
-                const int head = c / hd, j = c - head * hd;
+                const int head = c >> hd_sh, j = c & (hd - 1);
                 const int64_t hidx = b * g.kv_bstride + seq * g.kv_seq_stride + head;
                 *(u32x4_t*)((bf16_t*)g.vc + hidx * ((int64_t)hd * g.s_pad) + (int64_t)j * g.s_pad + pos0b + p8) = val;
               });
@@ -292,7 +324,7 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
             // q or k: rotate (u_j, u_{j+hd/2}); the low half owns the pair
             const bool is_q = nb < hq;
             const int c = is_q ? nb : nb - hq;
-            const int head = c / hd, jb = c - head * hd;
+            const int head = c >> hd_sh, jb = c & (hd - 1);
             if (jb < half && nb < g.N) {
               const int j = jb + col_l;
               constexpr int p1 = ni + 1 < NI ? ni + 1 : ni, p2 = ni + 2 < NI ? ni + 2 : ni;
@@ -324,7 +356,7 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
           } else if (nb < g.N) {
             // v: transposed store, 4 consecutive positions of one head-dim row
             const int c = nb - hq - hk;
-            const int head = c / hd, j = c - head * hd + col_l;
+            const int head = c >> hd_sh, j = (c & (hd - 1)) + col_l;
             if (s4 && mb + 3 < g.M && (pos4 & 3) == 0) {
               const int64_t hidx = b * g.kv_bstride + seq4 * g.kv_seq_stride + head;
               bf16_t* v = (bf16_t*)g.vc + hidx * ((int64_t)hd * g.s_pad) + (int64_t)j * g.s_pad + pos4;
