@@ -88,7 +88,7 @@ def run_prefill(args, torch, PB, I):
     tpath = os.path.join(ROOT, "profiles", "mid_prefill_gateup_traffic.json")
     if os.path.exists(tpath):
         traffic = json.load(open(tpath)).get("traffic_bytes_per_launch")
-    roofline = {"bound": "mfma", "kernel": "gemm_mfma_kernel<256, 256, 2, 2, 64, EPI_SWIGLU> (gate/up GEMM)",
+    roofline = {"bound": "mfma", "kernel": "gemm_dl_kernel<256, 256, 4, 2, EPI_SWIGLU> (gate/up GEMM)",
                 "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic,
                 "launches": n_dom, "avg_launch_ms": ms_dom / n_dom,
@@ -151,7 +151,7 @@ def run_decode(args, torch, PB, I):
            "prompt_prefill_s": prefill_s,
            "step_bytes_GB": (wbytes + kv_step) / 1e9, "step_GBs": (wbytes + kv_step) / (med * 1e-3) / 1e9,
            "step_frac_of_hbm_peak": (wbytes + kv_step) / (med * 1e-3) / 1e9 / HBM_PEAK_GBS,
-           "roofline": {"bound": "hbm", "kernel": "attn_decode_kernel<64>", "achieved": gbs,
+           "roofline": {"bound": "hbm", "kernel": "attn_decode_tiled_kernel<64>", "achieved": gbs,
                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": traffic,
                         "launches": n_attn, "avg_launch_ms": ms_attn / n_attn,
                         "bytes_per_launch": kv_launch}}

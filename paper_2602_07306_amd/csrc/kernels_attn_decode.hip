@@ -1,7 +1,9 @@
 // Split-K decode attention over the contiguous KV cache (bf16 cache, fp32 arithmetic).
 //
-// One query row per (track, sequence, head).  The work is HBM-bound: every key and value element is
-// read exactly once with 16-byte loads.  A workgroup owns one key range ("split") of one head:
+// One query row per (track, sequence, head).  The work is HBM-bound.  Two kernels: a matrix-core kernel
+// (further down; groups of up to 32 query heads per KV head) and this vector kernel for larger groups,
+// which reads the cache once per query head with 16-byte loads.  A workgroup owns one key range ("split")
+// of one head:
 //   phase 1  scores: a key row (hd contiguous) is covered by hd/8 lanes, 8 elements each; the partial
 //            dot products are folded with cross-lane exchanges and the score goes to LDS;
 //   phase 2  exact softmax numerators over the range (max, then exp2, then sum) in LDS;
@@ -179,8 +181,9 @@ __global__ void __launch_bounds__(64) attn_decode_combine_kernel(const pt_attn_a
 }
 
 // ------------------------------------------------------------------------------------------------
-// Grouped-query variant on the matrix cores: the G = H / Hkv query heads that share a KV head are
-// processed together, so every key and value element is still read exactly once.
+// Matrix-core kernel, used whenever G = H / Hkv <= 32 (the kernel above serves larger groups): the G
+// query heads that share a KV head (G = 1: plain multi-head attention) are processed together, so every
+// key and value element is read exactly once.
 //
 //   S^T [32 keys x G] = K_blk [32 x hd] . Q^T       (A = key rows straight from the cache, B = the G queries)
 //   O^T [hd x G]     += V^T_blk [hd x 32] . P^T     (A = rows of the V^T cache, B = P^T from the S^T registers)
@@ -200,7 +203,7 @@ union dpk8 {
   uint32_t u[4];
 };
 
-#define DEC_GMAX 16
+#define DEC_GMAX 32
 
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
@@ -209,7 +212,7 @@ typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 // and parked in one of two LDS buffers (16-byte chunk c of row r at position c ^ swizzle(r)); wavefront w then
 // works on keys 32w .. 32w+31 of the tile with fragments read from LDS.
 template <int HD>
-__global__ void __launch_bounds__(256) attn_decode_gqa_kernel(const pt_attn_args a, int nsplit, int keys_per_split) {
+__global__ void __launch_bounds__(256) attn_decode_tiled_kernel(const pt_attn_args a, int nsplit, int keys_per_split) {
   constexpr int KS = HD / 16, HB = HD / 32;
   constexpr int KROW = HD * 2;                  // bytes of a key row
   constexpr int KCH = KROW / 16;                // 16-byte chunks per key row
@@ -391,7 +394,7 @@ template <int HD>
 static int launch_gqa(const pt_attn_args& a, dim3 grid, int nsplit, int kps, hipStream_t s) {
   constexpr int LDS = 2 * 2 * 128 * HD * 2;
   static_assert(LDS >= 4 * HD * DEC_GMAX * 4, "merge buffer must fit the tiles");
-  auto kern = attn_decode_gqa_kernel<HD>;
+  auto kern = attn_decode_tiled_kernel<HD>;
   static bool configured = false;
   if (!configured) {
     PT_HIP_CHECK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS));
@@ -409,7 +412,7 @@ int pt_launch_attn_decode(const pt_attn_args& a, hipStream_t s) {
   if (z > 65535 || a.H > 65535) return 0;
   const int nkeys = a.pos0 + 1;
   const int G = a.H / a.Hkv;
-  if (G > 1 && G <= DEC_GMAX && (a.s_pad & 7) == 0) {
+  if (G <= DEC_GMAX && (a.s_pad & 7) == 0) {   // measured at least as fast as the VALU kernel for G = 1 too
     const int64_t gbase = z * a.Hkv;
     int nsplit = (int)((1024 + gbase - 1) / gbase);
     const int by_len = (nkeys + 511) / 512;

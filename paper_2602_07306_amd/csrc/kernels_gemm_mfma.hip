@@ -764,12 +764,13 @@ int pt_launch_gemm_mfma(const pt_gemm_args& g, hipStream_t s) {
   if ((g.epi == EPI_STORE_F32 || g.epi == EPI_RESIDUAL) &&
       ((g.ldo & 3) || (g.N & 3) || (g.out_bstride & 3) || (g.res_bstride & 3) || (((uintptr_t)g.out | (uintptr_t)g.res) & 15))) return 0;
   if (g.epi == EPI_SWIGLU && ((g.olp_bstride & 7) || ((uintptr_t)g.olp & 15))) return 0;
-  static const int big[] = {0, 4, 2, -1}, big_qkv[] = {10, 8, 0, 4, 2, -1}, mid[] = {4, 2, -1}, m64[] = {3, 6, -1}, m32[] = {5, 7, -1};
+  // measured: the direct-to-LDS variant (10) wins for the QKV epilogue and, at short K, for SwiGLU
+  static const int big[] = {0, 4, 2, -1}, big_qkv[] = {10, 8, 0, 4, 2, -1}, big_dl[] = {10, 0, 4, 2, -1}, mid[] = {4, 2, -1}, m64[] = {3, 6, -1}, m32[] = {5, 7, -1};
   const int* cand;
   if (g.M <= 32) cand = m32;
   else if (g.M <= 64) cand = m64;
   else if (g.M <= 128 || (int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256) * g.batch < 200) cand = mid;
-  else cand = g.epi == EPI_QKV ? big_qkv : big;
+  else cand = g.epi == EPI_QKV ? big_qkv : (g.epi == EPI_SWIGLU && g.K <= 1024) ? big_dl : big;
   int cfg = -1;
   if (pt_gemm_mfma_force_cfg >= 0 && pt_gemm_mfma_force_cfg < GM_NCFG) {
     if (cfg_fits(g, pt_gemm_mfma_force_cfg)) cfg = pt_gemm_mfma_force_cfg;

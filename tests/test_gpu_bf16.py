@@ -69,6 +69,9 @@ CASES = {
     # grouped-query decode with a split, ragged context; 16 query heads on one KV head
     "gqa_split_decode": (dict(n_kv_heads=1, max_batch=2, max_seq=1024), 2, 701, 3),
     "gqa_16_per_group": (dict(n_heads=16, n_kv_heads=1, head_dim=64, max_seq=512), 1, 333, 2),
+    # 24 query heads per KV head (matrix-core decode kernel, more than 16 columns) and 40 (vector decode kernel)
+    "gqa_24_per_group": (dict(n_heads=24, n_kv_heads=1, head_dim=64, max_seq=512), 1, 200, 2),
+    "gqa_40_per_group": (dict(n_heads=40, n_kv_heads=1, head_dim=64, max_seq=512), 1, 200, 2),
     # per-track shape of the paper's 30B model (Table 1: 8 tracks, 8 query heads and 1 KV head per track), batch 1
     "paper30b_track_shape": (dict(n_tracks=8, n_layers=2, block_depth=2, d_model=512, n_heads=8, n_kv_heads=1,
                                   head_dim=128, d_ffn=1024, max_batch=1, max_seq=512), 1, 192, 3),
