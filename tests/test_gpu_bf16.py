@@ -72,6 +72,11 @@ CASES = {
     # 24 query heads per KV head (matrix-core decode kernel, more than 16 columns) and 40 (vector decode kernel)
     "gqa_24_per_group": (dict(n_heads=24, n_kv_heads=1, head_dim=64, max_seq=512), 1, 200, 2),
     "gqa_40_per_group": (dict(n_heads=40, n_kv_heads=1, head_dim=64, max_seq=512), 1, 200, 2),
+    # decode GEMM planner: odd row counts, three tracks, K = 3 x 512 (three K slices), uneven tile dealing
+    "decode_5_rows_3_tracks": (dict(n_tracks=3, n_layers=2, block_depth=1, d_model=512, n_heads=8, n_kv_heads=2,
+                                    head_dim=64, d_ffn=1536, max_batch=5, max_seq=128, merge_scale=1.0 / 3), 5, 70, 3),
+    "decode_33_rows": (dict(n_layers=2, block_depth=2, d_model=512, n_heads=8, n_kv_heads=8, head_dim=64,
+                            d_ffn=1024, max_batch=33, max_seq=64), 33, 8, 2),
     # per-track shape of the paper's 30B model (Table 1: 8 tracks, 8 query heads and 1 KV head per track), batch 1
     "paper30b_track_shape": (dict(n_tracks=8, n_layers=2, block_depth=2, d_model=512, n_heads=8, n_kv_heads=1,
                                   head_dim=128, d_ffn=1024, max_batch=1, max_seq=512), 1, 192, 3),
