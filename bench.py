@@ -185,13 +185,16 @@ def run_cpu_baseline(I):
 
 def run_paper_sweep(args, torch, PB, I):
     """Latency-mode shape of the paper's serving tables (Section 3.3: batch 1, input lengths 1024 ... 63488,
-    30B-shaped PT model, track block depth 2, 4, 8) on one GPU with all 8 tracks resident: time to first token
+    30B-shaped PT model, track block depth 1, 2, 4, 8, and the dense model of matched size) on one GPU with all 8
+    tracks resident: time to first token
     = one prefill, time per output token = mean of the KV-cached decode steps that follow.  Widths are this
     build's choice (inputs.config_paper30b); the paper's numbers are for 8 GPUs and are context only."""
     lengths = [int(x) for x in args.sweep_lengths.split(",")]
     out = []
-    for D in [int(x) for x in args.sweep_depths.split(",")]:
-        cfg = I.config_paper30b(block_depth=D, max_batch=1, max_seq=max(lengths) + args.sweep_decode_steps + 8)
+    for D in [int(x) for x in args.sweep_depths.split(",")]:   # 0 = the dense model of matched size
+        max_seq = max(lengths) + args.sweep_decode_steps + 8
+        cfg = (I.config_paper30b(block_depth=D, max_batch=1, max_seq=max_seq) if D > 0
+               else I.config_dense30b(max_batch=1, max_seq=max_seq))
         model = PB.PTModel(cfg)
         model.pt_init_weights(5)
         logits = torch.empty((1, cfg.vocab), dtype=torch.float32, device="cuda")
@@ -217,9 +220,9 @@ def run_paper_sweep(args, torch, PB, I):
             tpot = (time.perf_counter() - t0) / args.sweep_decode_steps
             flops, _ = prefill_flops(cfg, 1, S, 1)
             wbytes, kv_step, _ = decode_bytes(cfg, 1, S + 1 + args.sweep_decode_steps // 2)
-            rec = {"block_depth": D, "input_len": S, "ttft_ms": ttft * 1e3, "tpot_ms": tpot * 1e3,
+            rec = {"model": "PT 8 tracks" if D > 0 else "dense", "block_depth": D if D > 0 else None, "input_len": S, "ttft_ms": ttft * 1e3, "tpot_ms": tpot * 1e3,
                    "prefill_TFLOPs": flops / ttft / 1e12, "decode_GBs": (wbytes + kv_step) / tpot / 1e9,
-                   "merges_per_forward": cfg.n_layers // D}
+                   "merges_per_forward": cfg.n_layers // cfg.block_depth if D > 0 else 0}
             log("paper sweep D=%d input %6d: TTFT %9.2f ms (%.0f TFLOP/s), TPOT %6.2f ms (%.0f GB/s)" % (
                 D, S, rec["ttft_ms"], rec["prefill_TFLOPs"], rec["tpot_ms"], rec["decode_GBs"]))
             out.append(rec)
@@ -245,7 +248,8 @@ def main():
                     help="instead of the benchmark: TTFT / TPOT at batch 1 over input lengths for the "
                          "30B-shaped PT model at track block depth 2, 4, 8 (one JSON line)")
     ap.add_argument("--sweep-lengths", default="1024,4096,16384,63488")
-    ap.add_argument("--sweep-depths", default="2,4,8")
+    ap.add_argument("--sweep-depths", default="0,1,2,4,8",
+                    help="track block depths of the sweep; 0 = the dense model of matched parameter count")
     ap.add_argument("--sweep-decode-steps", type=int, default=32)
     args = ap.parse_args()
     if args.gpus != 1:

@@ -284,6 +284,15 @@ def config_paper30b(block_depth: int = 8, max_batch: int = 1, max_seq: int = 409
                     max_seq=max_seq, dtype=PT_BF16)
 
 
+def config_dense30b(max_batch: int = 1, max_seq: int = 4096) -> PTConfig:
+    """Dense counterpart of config_paper30b with the same layer, head and KV-head totals (Table 1: 48 layers,
+    64 query heads, 8 KV heads) and a matched parameter count (31.4 B): one track that merges after every
+    layer is a standard decoder.  Width 8192 and FFN 20480 are this build's choice."""
+    return PTConfig(n_tracks=1, n_layers=48, block_depth=1, d_model=8192, n_heads=64, n_kv_heads=8,
+                    head_dim=128, d_ffn=20480, vocab=32000, max_batch=max_batch, max_seq=max_seq,
+                    dtype=PT_BF16)
+
+
 def config_share(max_batch: int = 2, max_seq: int = 4096) -> PTConfig:
     return PTConfig(n_tracks=1, n_layers=8, block_depth=8, d_model=8192, n_heads=64, n_kv_heads=64,
                     head_dim=128, d_ffn=28672, vocab=0, max_batch=max_batch, max_seq=max_seq,
