@@ -55,6 +55,75 @@ __device__ __forceinline__ sk_tile sk_decode_tile(const pt_gemm_args& g, int til
   return t;
 }
 
+// Fused epilogue on the finished (or K-slice) values of row m: lo[i] / hi[i] belong to columns off + i of the
+// first / second 16-row segment of `tile` (off a multiple of 4).  ksn > 1 (EPI_RESIDUAL only): slice ks leaves
+// its partial product in sk_part[ks][b][m][n]; the kernel that consumes the residual stream adds the slices.
+template <int EPI>
+__device__ __forceinline__ void sk_finish(const pt_gemm_args& g, int b, int tile, int m, int off, int ks, int ksn,
+                                          const float (&lo)[4], const float (&hi)[4]) {
+  const sk_tile tl = sk_decode_tile<EPI>(g, tile);
+  const int n_a = tl.n_a, n_b = tl.n_b, j0 = tl.j0, qk_head = tl.qk_head;
+  (void)n_a; (void)n_b; (void)j0; (void)qk_head;
+  if constexpr (EPI == EPI_STORE_F32 || EPI == EPI_RESIDUAL) {
+    // K split over workgroups: slice ks leaves its partial product in sk_part[ks][b][m][n]; the kernel that
+    // consumes the residual stream adds the slices and the residual
+    const bool split = EPI == EPI_RESIDUAL && ksn > 1;
+    float* out = split ? g.sk_part + (((int64_t)ks * g.batch + b) * g.M + m) * g.N
+                       : g.out + b * g.out_bstride + (int64_t)m * g.ldo;
+    const float* res = EPI == EPI_RESIDUAL ? g.res + b * g.res_bstride + (int64_t)m * g.ldo : nullptr;
+#pragma unroll
+    for (int sgm = 0; sgm < 2; ++sgm) {
+      const int n = (sgm ? n_b : n_a) + off;
+      const float* x = sgm ? hi : lo;
+      if (n < g.N) {
+        f32x4_t v4 = {x[0], x[1], x[2], x[3]};
+        if constexpr (EPI == EPI_RESIDUAL) if (!split) v4 += *(const f32x4_t*)(res + n);
+        *(f32x4_t*)(out + n) = v4;
+      }
+    }
+  } else if constexpr (EPI == EPI_SWIGLU) {
+    bf16_t* o = (bf16_t*)g.olp + b * g.olp_bstride + (int64_t)m * (g.N >> 1) + j0 + off;
+    uint2 pk;
+    pk.x = pack_bf16x2(silu_f(lo[0]) * hi[0], silu_f(lo[1]) * hi[1]);
+    pk.y = pack_bf16x2(silu_f(lo[2]) * hi[2], silu_f(lo[3]) * hi[3]);
+    *(uint2*)o = pk;
+  } else {  // EPI_QKV
+    const int seq = m / g.S, pos = g.pos0 + (m - seq * g.S);
+    const int hd = g.hd, half_hd = hd >> 1, hq = g.H * hd;
+    if (tl.rot) {
+      const int j = j0 + off;
+      const float4* rp = (const float4*)((const float2*)g.rope + (int64_t)pos * half_hd + j);
+      const float4 cs01 = rp[0], cs23 = rp[1];
+      const float c[4] = {cs01.x, cs01.z, cs23.x, cs23.z}, sn[4] = {cs01.y, cs01.w, cs23.y, cs23.w};
+      uint2 plo, phi;
+      plo.x = pack_bf16x2(lo[0] * c[0] - hi[0] * sn[0], lo[1] * c[1] - hi[1] * sn[1]);
+      plo.y = pack_bf16x2(lo[2] * c[2] - hi[2] * sn[2], lo[3] * c[3] - hi[3] * sn[3]);
+      phi.x = pack_bf16x2(hi[0] * c[0] + lo[0] * sn[0], hi[1] * c[1] + lo[1] * sn[1]);
+      phi.y = pack_bf16x2(hi[2] * c[2] + lo[2] * sn[2], hi[3] * c[3] + lo[3] * sn[3]);
+      bf16_t* dst;
+      if (qk_head < g.H) {
+        dst = (bf16_t*)g.olp + b * g.olp_bstride + (int64_t)m * hq + qk_head * hd + j;
+      } else {
+        const int64_t hidx = b * g.kv_bstride + seq * g.kv_seq_stride + (qk_head - g.H);
+        dst = (bf16_t*)g.kc + hidx * g.kv_head_elems + (int64_t)pos * hd + j;
+      }
+      *(uint2*)dst = plo;
+      *(uint2*)(dst + half_hd) = phi;
+    } else {
+#pragma unroll
+      for (int sgm = 0; sgm < 2; ++sgm) {
+        const int cbase = (sgm ? n_b : n_a) - (g.H + g.Hkv) * hd + off;   // column inside the v section
+        const float* x = sgm ? hi : lo;
+        const int head = cbase / hd, j = cbase - head * hd;
+        const int64_t hidx = b * g.kv_bstride + seq * g.kv_seq_stride + head;
+        bf16_t* vt = (bf16_t*)g.vc + hidx * ((int64_t)hd * g.s_pad) + (int64_t)j * g.s_pad + pos;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) vt[(int64_t)i * g.s_pad] = f32_to_bf16(x[i]);
+      }
+    }
+  }
+}
+
 // MI: 32-row blocks of A (M <= 32*MI); RB: 32-row blocks of W per workgroup (each A fragment is multiplied
 // with RB blocks of weight rows).
 //
@@ -192,69 +261,8 @@ __device__ __forceinline__ void skinny_body(const pt_gemm_args& g, int b, int fi
   const int off = 8 * vg + 4 * half;   // column offset inside a segment
   const bool owner = mi_e < MI && m < g.M;
 
-  // fused epilogue on the reduced values of one block of weight rows
   auto finish = [&](int rb, const float (&lo)[4], const float (&hi)[4]) {
-    const sk_tile tl = sk_decode_tile<EPI>(g, first_tile + rb);
-    const int n_a = tl.n_a, n_b = tl.n_b, j0 = tl.j0, qk_head = tl.qk_head;
-    (void)n_a; (void)n_b; (void)j0; (void)qk_head;
-    if constexpr (EPI == EPI_STORE_F32 || EPI == EPI_RESIDUAL) {
-      // K split over workgroups: slice ks leaves its partial product in sk_part[ks][b][m][n]; the kernel that
-      // consumes the residual stream adds the slices and the residual
-      const bool split = EPI == EPI_RESIDUAL && ksn > 1;
-      float* out = split ? g.sk_part + (((int64_t)ks * g.batch + b) * g.M + m) * g.N
-                         : g.out + b * g.out_bstride + (int64_t)m * g.ldo;
-      const float* res = EPI == EPI_RESIDUAL ? g.res + b * g.res_bstride + (int64_t)m * g.ldo : nullptr;
-#pragma unroll
-      for (int sgm = 0; sgm < 2; ++sgm) {
-        const int n = (sgm ? n_b : n_a) + off;
-        const float* x = sgm ? hi : lo;
-        if (n < g.N) {
-          f32x4_t v4 = {x[0], x[1], x[2], x[3]};
-          if constexpr (EPI == EPI_RESIDUAL) if (!split) v4 += *(const f32x4_t*)(res + n);
-          *(f32x4_t*)(out + n) = v4;
-        }
-      }
-    } else if constexpr (EPI == EPI_SWIGLU) {
-      bf16_t* o = (bf16_t*)g.olp + b * g.olp_bstride + (int64_t)m * (g.N >> 1) + j0 + off;
-      uint2 pk;
-      pk.x = pack_bf16x2(silu_f(lo[0]) * hi[0], silu_f(lo[1]) * hi[1]);
-      pk.y = pack_bf16x2(silu_f(lo[2]) * hi[2], silu_f(lo[3]) * hi[3]);
-      *(uint2*)o = pk;
-    } else {  // EPI_QKV
-      const int seq = m / g.S, pos = g.pos0 + (m - seq * g.S);
-      const int hd = g.hd, half_hd = hd >> 1, hq = g.H * hd;
-      if (tl.rot) {
-        const int j = j0 + off;
-        const float4* rp = (const float4*)((const float2*)g.rope + (int64_t)pos * half_hd + j);
-        const float4 cs01 = rp[0], cs23 = rp[1];
-        const float c[4] = {cs01.x, cs01.z, cs23.x, cs23.z}, sn[4] = {cs01.y, cs01.w, cs23.y, cs23.w};
-        uint2 plo, phi;
-        plo.x = pack_bf16x2(lo[0] * c[0] - hi[0] * sn[0], lo[1] * c[1] - hi[1] * sn[1]);
-        plo.y = pack_bf16x2(lo[2] * c[2] - hi[2] * sn[2], lo[3] * c[3] - hi[3] * sn[3]);
-        phi.x = pack_bf16x2(hi[0] * c[0] + lo[0] * sn[0], hi[1] * c[1] + lo[1] * sn[1]);
-        phi.y = pack_bf16x2(hi[2] * c[2] + lo[2] * sn[2], hi[3] * c[3] + lo[3] * sn[3]);
-        bf16_t* dst;
-        if (qk_head < g.H) {
-          dst = (bf16_t*)g.olp + b * g.olp_bstride + (int64_t)m * hq + qk_head * hd + j;
-        } else {
-          const int64_t hidx = b * g.kv_bstride + seq * g.kv_seq_stride + (qk_head - g.H);
-          dst = (bf16_t*)g.kc + hidx * g.kv_head_elems + (int64_t)pos * hd + j;
-        }
-        *(uint2*)dst = plo;
-        *(uint2*)(dst + half_hd) = phi;
-      } else {
-#pragma unroll
-        for (int sgm = 0; sgm < 2; ++sgm) {
-          const int cbase = (sgm ? n_b : n_a) - (g.H + g.Hkv) * hd + off;   // column inside the v section
-          const float* x = sgm ? hi : lo;
-          const int head = cbase / hd, j = cbase - head * hd;
-          const int64_t hidx = b * g.kv_bstride + seq * g.kv_seq_stride + head;
-          bf16_t* vt = (bf16_t*)g.vc + hidx * ((int64_t)hd * g.s_pad) + (int64_t)j * g.s_pad + pos;
-#pragma unroll
-          for (int i = 0; i < 4; ++i) vt[(int64_t)i * g.s_pad] = f32_to_bf16(x[i]);
-        }
-      }
-    }
+    sk_finish<EPI>(g, b, first_tile + rb, m, off, ks, ksn, lo, hi);
   };
 
   // per block of weight rows: the four wavefronts' partial tiles meet in LDS
@@ -276,6 +284,168 @@ __device__ __forceinline__ void skinny_body(const pt_gemm_args& g, int b, int fi
       finish(rb, lo, hi);
     }
   }
+}
+
+// ------------------------------------------------------------------------------------------------
+// M <= 4 rows (latency-mode decode, one to four sequences): matrix-vector form on the vector ALUs.
+// Nothing is staged: a wavefront reads 8 weight rows (4 epilogue pairs of a 32-row tile) as 1 KB
+// contiguous pieces, 16 bytes per lane, multiplies them with the A values of the lane's K positions
+// (A sits in LDS, bf16) and folds the 64 lanes with cross-lane adds at the end.  Two register sets keep
+// 16 KB of weights in flight per wavefront.  A workgroup (4 wavefronts) owns one 32-row tile.
+// ------------------------------------------------------------------------------------------------
+template <int MR, int EPI>
+__global__ void __launch_bounds__(256) gemm_gemv_kernel(const pt_gemm_args g, int tiles, int wgs_per_track) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];   // A: [MR][K] bf16
+  bf16_t* As = (bf16_t*)smem;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = blockIdx.x / wgs_per_track, wg = blockIdx.x - b * wgs_per_track;
+  const int K = g.K;
+  // A rows into LDS (rows past M repeat the last one; their results are not stored)
+  if (g.norm_src) {
+    // A = RMSNorm of the fp32 residual stream, formed here (every workgroup repeats these few thousand
+    // operations; the launch of a separate kernel would cost more)
+    __shared__ float s_ss[4];
+    const float* gain = g.norm_gain + b * g.norm_gbstride;
+    for (int m = 0; m < MR; ++m) {
+      const float* x = g.norm_src + b * g.norm_bstride + (int64_t)min(m, g.M - 1) * K;
+      float ss = 0.f;
+      for (int k4 = tid; k4 < (K >> 2); k4 += 256) {
+        const f32x4_t v = *(const f32x4_t*)(x + 4 * k4);
+        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+      }
+      ss = wave_sum(ss);
+      if (m > 0) __syncthreads();
+      if (lane == 0) s_ss[wave] = ss;
+      __syncthreads();
+      ss = (s_ss[0] + s_ss[1]) + (s_ss[2] + s_ss[3]);
+      const float inv = 1.0f / sqrtf(ss / (float)K + g.norm_eps);
+      for (int k4 = tid; k4 < (K >> 2); k4 += 256) {
+        const f32x4_t v = *(const f32x4_t*)(x + 4 * k4);
+        const f32x4_t w = *(const f32x4_t*)(gain + 4 * k4);
+        uint2 pk;
+        pk.x = pack_bf16x2(v.x * inv * w.x, v.y * inv * w.y);
+        pk.y = pack_bf16x2(v.z * inv * w.z, v.w * inv * w.w);
+        *(uint2*)(As + m * K + 4 * k4) = pk;
+      }
+    }
+  } else {
+    for (int c = tid; c < MR * (K >> 3); c += 256) {
+      const int m = c / (K >> 3), kc = c - m * (K >> 3);
+      *(u32x4_t*)(As + m * K + kc * 8) =
+          *(const u32x4_t*)((const bf16_t*)g.A + b * g.a_bstride + (int64_t)min(m, g.M - 1) * g.lda + kc * 8);
+    }
+  }
+  // This workgroup's tiles: wg, wg + wgs_per_track, ...  The wavefront walks (tile, 512-wide K chunk) items
+  // in one stream, so the loads of a tile's first chunks are in flight while the previous tile is finished.
+  const int my_tiles = (tiles - wg + wgs_per_track - 1) / wgs_per_track;
+  const int nchunks = K >> 9;   // K is a multiple of 512
+  const int nitems = my_tiles * nchunks;
+  const bf16_t* wrow[8];   // rows 2i: first segment, 2i + 1: partner in the second segment
+  auto set_rows = [&](int tile) {
+    const sk_tile tl = sk_decode_tile<EPI>(g, tile);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int p = wave * 4 + i;
+      wrow[2 * i] = (const bf16_t*)g.W + b * g.w_bstride + (int64_t)(tl.n_a + p) * g.ldb + lane * 8;
+      wrow[2 * i + 1] = (const bf16_t*)g.W + b * g.w_bstride + (int64_t)(tl.n_b + p) * g.ldb + lane * 8;
+    }
+  };
+  float acc[8][MR];
+#pragma unroll
+  for (int r = 0; r < 8; ++r)
+#pragma unroll
+    for (int m = 0; m < MR; ++m) acc[r][m] = 0.f;
+  u32x4_t wreg[2][8];
+  int ld_tile = wg, ld_chunk = 0;    // the load stream's position
+  set_rows(ld_tile);
+  auto load_next = [&](int buf) {     // past the last item: re-reads the last chunk (unused)
+#pragma unroll
+    for (int r = 0; r < 8; ++r) wreg[buf][r] = *(const u32x4_t*)(wrow[r] + ld_chunk * 512);
+    if (ld_chunk + 1 < nchunks) {
+      ++ld_chunk;
+    } else if (ld_tile + wgs_per_track < tiles) {
+      ld_tile += wgs_per_track;
+      ld_chunk = 0;
+      set_rows(ld_tile);
+    }
+  };
+  int cur_tile = wg, cur_chunk = 0;  // the multiply stream's position
+  auto mul = [&](int buf) {
+    float av[MR][8];
+#pragma unroll
+    for (int m = 0; m < MR; ++m) {
+      const u32x4_t a4 = *(const u32x4_t*)(As + m * K + cur_chunk * 512 + lane * 8);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        av[m][2 * i] = __uint_as_float(a4[i] << 16);
+        av[m][2 * i + 1] = __uint_as_float(a4[i] & 0xffff0000u);
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < 8; ++r)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float w0 = __uint_as_float(wreg[buf][r][i] << 16), w1 = __uint_as_float(wreg[buf][r][i] & 0xffff0000u);
+#pragma unroll
+        for (int m = 0; m < MR; ++m) acc[r][m] = fmaf(w1, av[m][2 * i + 1], fmaf(w0, av[m][2 * i], acc[r][m]));
+      }
+    if (++cur_chunk == nchunks) {     // the tile is complete: fold the lanes, lane m finishes A row m
+#pragma unroll
+      for (int r = 0; r < 8; ++r)
+#pragma unroll
+        for (int m = 0; m < MR; ++m) acc[r][m] = wave_sum(acc[r][m]);
+#pragma unroll
+      for (int m = 0; m < MR; ++m) {
+        if (lane == m && m < g.M) {
+          const float lo[4] = {acc[0][m], acc[2][m], acc[4][m], acc[6][m]};
+          const float hi[4] = {acc[1][m], acc[3][m], acc[5][m], acc[7][m]};
+          sk_finish<EPI>(g, b, cur_tile, m, wave * 4, 0, 1, lo, hi);
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < 8; ++r)
+#pragma unroll
+        for (int m = 0; m < MR; ++m) acc[r][m] = 0.f;
+      cur_tile += wgs_per_track;
+      cur_chunk = 0;
+    }
+  };
+  load_next(0);
+  __syncthreads();              // A is in LDS
+  for (int i = 0; i < nitems; i += 2) {
+    __builtin_amdgcn_sched_barrier(0);
+    load_next(1);
+    __builtin_amdgcn_sched_barrier(0);
+    mul(0);
+    __builtin_amdgcn_sched_barrier(0);
+    load_next(0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (i + 1 < nitems) mul(1);
+  }
+}
+
+template <int MR, int EPI>
+static int launch_gemv(const pt_gemm_args& g, int tiles, hipStream_t s) {
+  const int lds = MR * g.K * 2;
+  auto kern = gemm_gemv_kernel<MR, EPI>;
+  static bool configured = false;
+  if (!configured) {
+    PT_HIP_CHECK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 48 * 1024));
+    configured = true;
+  }
+  // about a thousand workgroups (three to four resident per compute unit), every one with the same number of tiles
+  const int tpw = (int)(((int64_t)tiles * g.batch + 1023) / 1024);
+  const int wpt = (tiles + tpw - 1) / tpw;
+  hipLaunchKernelGGL(kern, dim3((unsigned)((int64_t)wpt * g.batch)), dim3(256), lds, s, g, tiles, wpt);
+  PT_HIP_CHECK(hipGetLastError());
+  return 1;
+}
+
+template <int EPI>
+static int launch_gemv_m(const pt_gemm_args& g, int tiles, hipStream_t s) {
+  if (g.M == 1) return launch_gemv<1, EPI>(g, tiles, s);
+  if (g.M == 2) return launch_gemv<2, EPI>(g, tiles, s);
+  return launch_gemv<4, EPI>(g, tiles, s);
 }
 
 // The tiles (blocks of 32 weight rows) of a track are dealt out to wgs_per_track workgroups as evenly as
@@ -407,9 +577,19 @@ static bool skinny_covers(const pt_gemm_args& g) {
 
 // Number of K slices the decode kernel would use for this residual GEMM when the caller is ready to add the
 // slices itself (0: the kernel does not cover the shape; 1: no split).
+// one to four rows: matrix-vector kernel, if A fits its LDS budget and the grid is at least half a round
+static bool use_gemv(const pt_gemm_args& g) {
+  return g.M <= 4 && pt_gemm_skinny_force == 0 && g.K % 512 == 0 &&
+         (int64_t)(g.M == 3 ? 4 : g.M) * g.K * 2 <= 48 * 1024 && (int64_t)(g.N / 32) * g.batch >= 128;
+}
+
+bool pt_gemm_fuses_norm(const pt_gemm_args& g) {
+  return skinny_covers(g) && use_gemv(g) && (g.epi == EPI_QKV || g.epi == EPI_SWIGLU) && g.lda == g.K;
+}
+
 int pt_gemm_skinny_ksplit(const pt_gemm_args& g) {
   if (!skinny_covers(g)) return 0;
-  if (g.epi != EPI_RESIDUAL || !g.sk_part || (g.N & 3)) return 1;
+  if (g.epi != EPI_RESIDUAL || !g.sk_part || (g.N & 3) || use_gemv(g)) return 1;
   return plan_skinny(g, g.N / 32, 16).ks;
 }
 
@@ -419,6 +599,15 @@ int pt_launch_gemm_skinny(const pt_gemm_args& g, bool allow_split, hipStream_t s
   if (!skinny_covers(g)) return 0;
   const int tiles = g.N / 32;
   const int ks_max = allow_split && g.epi == EPI_RESIDUAL && g.sk_part && !(g.N & 3) ? 16 : 1;
+  if (g.norm_src && !pt_gemm_fuses_norm(g)) return 0;
+  if (use_gemv(g)) {
+    switch (g.epi) {
+      case EPI_STORE_F32: return launch_gemv_m<EPI_STORE_F32>(g, tiles, s);
+      case EPI_RESIDUAL: return launch_gemv_m<EPI_RESIDUAL>(g, tiles, s);
+      case EPI_SWIGLU: return launch_gemv_m<EPI_SWIGLU>(g, tiles, s);
+      case EPI_QKV: return launch_gemv_m<EPI_QKV>(g, tiles, s);
+    }
+  }
   const bool two = g.M > 32;
   switch (g.epi) {
     case EPI_STORE_F32: return two ? launch_skinny<2, EPI_STORE_F32>(g, tiles, ks_max, s) : launch_skinny<1, EPI_STORE_F32>(g, tiles, ks_max, s);

@@ -310,6 +310,7 @@ static int run_gemm(pt_handle* h, const pt_gemm_args& g_in, int cls) {
     int r = g.M <= 64 ? pt_launch_gemm_skinny(g, false, h->stream) : 0;
     if (r < 0) return r;
     if (r == 1) return PT_OK;
+    if (g.norm_src) return pt_set_error(PT_ERR_HIP, "a GEMM that was to form its own normalised operand was not taken by that kernel");
     r = pt_launch_gemm_mfma(g, h->stream);
     if (r < 0) return r;
     if (r == 1) return PT_OK;
@@ -375,6 +376,7 @@ static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
 
   float* hres = (float*)(h->ws + l.off_h);   // [T, rows, d]
   float* hm = (float*)(h->ws + l.off_hm);    // [rows, d]
+  const float* merged = hm;                  // the output activation of Algorithm 1 after the last merge
   char* abuf = h->ws + l.off_a;
   char* qbuf = h->ws + l.off_q;
   char* obuf = h->ws + l.off_o;
@@ -399,6 +401,21 @@ static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
   const int64_t kv_head_v = (int64_t)c.head_dim * l.s_pad;
   int merge_idx = 0;
   bool normed = false;   // abuf already holds the normalised input of this layer's attention half
+  // Latency-mode decode (a handful of rows): the QKV and gate/up kernels form their RMSNorm-ed operand
+  // themselves, which saves two launches per layer.  The decision depends on shapes only.
+  bool fuse_qkv_norm = false, fuse_ffn_norm = false;
+  if (h->path == PT_PATH_AUTO) {
+    pt_gemm_args p;
+    memset(&p, 0, sizeof(p));
+    p.A = abuf; p.W = h->w + l.off_layers; p.lda = p.ldb = p.K = (int32_t)d;
+    p.a_bstride = rows * d; p.w_bstride = L * l.layer_w_elems;
+    p.M = (int32_t)rows; p.batch = (int32_t)T; p.dtype = c.dtype;
+    p.N = (int32_t)l.n_qkv; p.epi = EPI_QKV; p.olp = qbuf; p.olp_bstride = rows * l.hq;
+    p.H = c.n_heads; p.Hkv = c.n_kv_heads; p.hd = c.head_dim; p.S = S; p.s_pad = (int32_t)l.s_pad;
+    fuse_qkv_norm = pt_gemm_fuses_norm(p);
+    p.N = (int32_t)(2 * f); p.epi = EPI_SWIGLU; p.olp = mbuf; p.olp_bstride = rows * f;
+    fuse_ffn_norm = pt_gemm_fuses_norm(p);
+  }
   for (int64_t layer = 0; layer < L; ++layer) {
     const bool first = (layer % c.block_depth) == 0;
     const float* src = first ? x : hres;
@@ -407,7 +424,7 @@ static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
     const int64_t w_bstride = L * l.layer_w_elems;
 
     // attention half
-    if (!normed) {
+    if (!normed && !fuse_qkv_norm) {
       prof_scope ps(h, PT_K_RMSNORM);
       rc = pt_launch_rmsnorm(src, src_bstride, gains + (layer * 2 + 0) * d, L * 2 * d, abuf, rows * d,
                              c.dtype, (int32_t)T, rows, (int32_t)d, c.rms_eps, st);
@@ -429,6 +446,10 @@ static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
     g.kv_bstride = L * c.max_batch * c.n_kv_heads;   // in heads; kernels scale by the head size
     g.kv_seq_stride = c.n_kv_heads;                  // in heads
     g.kv_head_elems = kv_head_k;
+    if (fuse_qkv_norm) {
+      g.norm_src = src; g.norm_bstride = src_bstride;
+      g.norm_gain = gains + (layer * 2 + 0) * d; g.norm_gbstride = L * 2 * d; g.norm_eps = c.rms_eps;
+    }
     rc = run_gemm(h, g, PT_K_GEMM_QKV);
     if (rc) return rc;
 
@@ -452,7 +473,7 @@ static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
     g.out = hres; g.out_bstride = rows * d; g.ldo = (int32_t)d;
     g.res = src; g.res_bstride = src_bstride;
     // ... and the RMSNorm that opens the feed-forward half
-    rc = run_residual_gemm_norm(h, g, PT_K_GEMM_OUT, gains + (layer * 2 + 1) * d, L * 2 * d, abuf);
+    rc = run_residual_gemm_norm(h, g, PT_K_GEMM_OUT, fuse_ffn_norm ? nullptr : gains + (layer * 2 + 1) * d, L * 2 * d, abuf);
     if (rc) return rc;
 
     // feed-forward half
@@ -462,6 +483,10 @@ static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
     g.M = (int32_t)rows; g.N = (int32_t)(2 * f); g.K = (int32_t)d; g.batch = (int32_t)T;
     g.dtype = c.dtype; g.epi = EPI_SWIGLU;
     g.olp = mbuf; g.olp_bstride = rows * f;
+    if (fuse_ffn_norm) {
+      g.norm_src = hres; g.norm_bstride = rows * d;
+      g.norm_gain = gains + (layer * 2 + 1) * d; g.norm_gbstride = L * 2 * d; g.norm_eps = c.rms_eps;
+    }
     rc = run_gemm(h, g, PT_K_GEMM_GATEUP);
     if (rc) return rc;
     memset(&g, 0, sizeof(g));
@@ -473,10 +498,11 @@ static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
     g.res = hres; g.res_bstride = rows * d;
     // inside a block the next layer's first RMSNorm follows directly; at a block end the merge comes first
     const bool block_end = (layer + 1) % c.block_depth == 0;
-    rc = run_residual_gemm_norm(h, g, PT_K_GEMM_DOWN, block_end ? nullptr : gains + ((layer + 1) * 2 + 0) * d,
+    const bool norm_next = !block_end && !fuse_qkv_norm;
+    rc = run_residual_gemm_norm(h, g, PT_K_GEMM_DOWN, norm_next ? gains + ((layer + 1) * 2 + 0) * d : nullptr,
                                 L * 2 * d, abuf);
     if (rc) return rc;
-    normed = !block_end;
+    normed = norm_next;
 
     // Algorithm 1: after every D-th layer, all-reduce the track activations; every track
     // continues from the reduced activation.
@@ -488,29 +514,37 @@ static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
         if (rc) return rc;
       }
       float* tap = h->taps ? h->taps + (int64_t)merge_idx * rows * d : nullptr;
-      {
-        prof_scope ps(h, PT_K_MERGE);
-        rc = pt_launch_merge(tr, (int32_t)T, rows * d, PT_F32, c.merge_scale, hm, tap, st);
+      if (T == 1 && c.merge_scale == 1.0f && !tap) {
+        // one track, plain sum: the all-reduce is the identity and the track simply continues
+        merged = hres;
+        x = hres;
+        x_bstride = rows * d;
+      } else {
+        {
+          prof_scope ps(h, PT_K_MERGE);
+          rc = pt_launch_merge(tr, (int32_t)T, rows * d, PT_F32, c.merge_scale, hm, tap, st);
+        }
+        if (rc) return rc;
+        merged = hm;
+        x = hm;
+        x_bstride = 0;
       }
-      if (rc) return rc;
-      x = hm;
-      x_bstride = 0;
       ++merge_idx;
       ++h->merges;
     }
   }
 
   if (dev_hidden_out) {
-    rc = pt_launch_copy_f32(hm, dev_hidden_out, rows * d, st);
+    rc = pt_launch_copy_f32(merged, dev_hidden_out, rows * d, st);
     if (rc) return rc;
   }
   if (logits_mode != PT_LOGITS_NONE && (dev_logits || dev_argmax)) {
     const int64_t lrows = logits_mode == PT_LOGITS_ALL ? rows : B;
     const float* gf = (const float*)(h->w + l.off_gf);
     if (logits_mode == PT_LOGITS_ALL)
-      rc = pt_launch_rmsnorm_rows(hm, gf, abuf, c.dtype, lrows, 1, 0, (int32_t)d, c.rms_eps, st);
+      rc = pt_launch_rmsnorm_rows(merged, gf, abuf, c.dtype, lrows, 1, 0, (int32_t)d, c.rms_eps, st);
     else
-      rc = pt_launch_rmsnorm_rows(hm, gf, abuf, c.dtype, lrows, S, S - 1, (int32_t)d, c.rms_eps, st);
+      rc = pt_launch_rmsnorm_rows(merged, gf, abuf, c.dtype, lrows, S, S - 1, (int32_t)d, c.rms_eps, st);
     if (rc) return rc;
     float* lg = dev_logits;
     if (!lg) return pt_set_error(PT_ERR_NULL_POINTER, "argmax needs a logits buffer");

@@ -132,6 +132,12 @@ struct pt_gemm_args {
   int32_t H, Hkv, hd, S, pos0, s_pad;
   // K-slice scratch of the decode kernel, PT_SK_PART_FLOATS floats (may be null: K is not split over workgroups)
   float* sk_part;
+  // Optional, honoured only where pt_gemm_fuses_norm(g) holds: A is not read; row m of track b is
+  // RMSNorm(norm_src[b][m][0..K)) * norm_gain[b][0..K), formed by the kernel itself.
+  const float* norm_src;
+  const float* norm_gain;
+  int64_t norm_bstride, norm_gbstride;
+  float norm_eps;
 };
 
 enum { PT_SK_PART_FLOATS = 16 << 20 };
@@ -144,6 +150,9 @@ int pt_launch_gemm_mfma(const pt_gemm_args& g, hipStream_t s);
 // out = res + product; pt_launch_resnorm adds them up.
 int pt_launch_gemm_skinny(const pt_gemm_args& g, bool allow_split, hipStream_t s);
 int pt_gemm_skinny_ksplit(const pt_gemm_args& g);
+// True if pt_launch_gemm_skinny would run this problem (shape fields only) on the kernel that can form its A
+// operand from the fp32 residual stream (norm_* fields), which saves the RMSNorm launch in front of it.
+bool pt_gemm_fuses_norm(const pt_gemm_args& g);
 
 // ---------------------------------------------------------------------------------------------
 // Attention over the KV cache.  q/o: [batch_t][rows][H*hd]; row m is sequence m / S at position

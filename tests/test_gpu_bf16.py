@@ -77,6 +77,11 @@ CASES = {
                                     head_dim=64, d_ffn=1536, max_batch=5, max_seq=128, merge_scale=1.0 / 3), 5, 70, 3),
     "decode_33_rows": (dict(n_layers=2, block_depth=2, d_model=512, n_heads=8, n_kv_heads=8, head_dim=64,
                             d_ffn=1024, max_batch=33, max_seq=64), 33, 8, 2),
+    # matrix-vector decode kernel: two and three rows
+    "gemv_2_rows": (dict(n_tracks=4, n_layers=2, block_depth=2, d_model=512, n_heads=8, n_kv_heads=2, head_dim=64,
+                         d_ffn=1024, max_batch=2, max_seq=128), 2, 40, 3),
+    "gemv_3_rows": (dict(n_tracks=4, n_layers=2, block_depth=1, d_model=512, n_heads=4, n_kv_heads=4, head_dim=128,
+                         d_ffn=1536, max_batch=3, max_seq=128), 3, 33, 3),
     # per-track shape of the paper's 30B model (Table 1: 8 tracks, 8 query heads and 1 KV head per track), batch 1
     "paper30b_track_shape": (dict(n_tracks=8, n_layers=2, block_depth=2, d_model=512, n_heads=8, n_kv_heads=1,
                                   head_dim=128, d_ffn=1024, max_batch=1, max_seq=512), 1, 192, 3),
