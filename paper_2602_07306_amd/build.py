@@ -24,6 +24,13 @@ SOURCES = [
     "kernels_weights.hip",
     "kernels_gemm_generic.hip",
     "kernels_gemm_mfma.hip",
+    "kernels_gemm_mfma_store.hip",
+    "kernels_gemm_mfma_residual.hip",
+    "kernels_gemm_mfma_swiglu.hip",
+    "kernels_gemm_mfma_qkv_a.hip",
+    "kernels_gemm_mfma_qkv_b.hip",
+    "kernels_gemm_mfma_qkv_c.hip",
+    "kernels_gemm_mfma_qkv_d.hip",
     "kernels_gemm_skinny.hip",
     "kernels_attn_generic.hip",
     "kernels_attn_prefill_mfma.hip",

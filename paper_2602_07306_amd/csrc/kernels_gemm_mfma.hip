@@ -1,742 +1,29 @@
-// Track-batched bf16 GEMM on the gfx950 matrix cores with fused epilogues.
-//
-//   C[t] (M x N) = A[t] (M x K) * W[t]^T,   W[t] stored [N, K], for every track t (grid z-like dim)
-//
-// Both operands are contiguous along K, so a lane's 8-element MFMA operand is one 16-byte LDS read.
-// Tiling: a workgroup owns a BM x BN tile; WM x WN wavefronts each own a (BM/WM) x (BN/WN) sub-tile
-// made of 32x32x16 MFMAs.  K advances in steps of 64 through a double-buffered LDS tile whose
-// 16-byte chunks are XOR-swizzled by the row number, so that neither the 16-byte stores (8 lanes per
-// row) nor the operand reads (32 consecutive rows per half-wave) pile onto the same banks.  Global
-// loads for step k+1 are issued before the MFMAs of step k and parked in registers.
-//
-// Accumulator layout of a 32x32 MFMA tile: lane l holds column l%32 and, in register v, row
-// 8*(v/4) + 4*(l/32) + v%4.  The epilogues work directly on that layout:
-//   - fp32 stores / residual adds are 128-byte row segments per register;
-//   - the SwiGLU pair (gate_j, up_j) is (tile ni, tile ni+1) in the same lane and register, because
-//     the weight rows are interleaved in blocks of 32;
-//   - the rotary pair (j, j + hd/2) is (tile ni, tile ni + hd/64) in the same lane and register;
-//   - V is written transposed: 4 consecutive rows of a register group are 4 consecutive positions.
-#include <type_traits>
+// Chooses the tile configuration of the MFMA GEMM family by shape and dispatches to the kernels, which are
+// instantiated per epilogue in kernels_gemm_mfma_{store,residual,swiglu,qkv_a..d}.hip from gemm_mfma_impl.h.
+#include "pt_device.h"
 
-#include "pt_epilogue.h"
-
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
-typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));   // 16-byte staging register
-
-__device__ __forceinline__ float silu_fast(float z) {
-  return z * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * z));
-}
-
-#define GM_BK 64   // largest K step; K must be a multiple of 2 * GM_BK
-
-template <int N, typename F>
-__device__ __forceinline__ void static_for(F&& f) {
-  if constexpr (N > 0) {
-    static_for<N - 1>(f);
-    f(std::integral_constant<int, N - 1>{});
-  }
-}
-
-#ifdef GM_TIMING   // tuning builds only: per-phase clock stamps of workgroup 0
-__device__ long long gm_stamps[64];
-#define GM_STAMP(i) do { if (blockIdx.x == 0 && threadIdx.x == 0 && (i) < 64) gm_stamps[i] = wall_clock64(); } while (0)
-#else
-#define GM_STAMP(i) do { } while (0)
-#endif
-
-struct tile_coord {
-  int b, tm, tn;
-};
-
-// Workgroup ids are dealt round-robin to the 8 XCDs (XCD = id % 8).  Regrouping them so that each XCD
-// (own L2) walks a contiguous range of logical tile ids keeps the A and W slabs that concurrently
-// resident workgroups of one XCD share few.
-__device__ __forceinline__ int logical_tile(int id, int total) {
-  return (total & 7) == 0 ? (id & 7) * (total >> 3) + (id >> 3) : id;
-}
-
-// Logical id -> (track, m-tile, n-tile): groups of 4 m-tiles x all n-tiles, column-major inside a
-// group, so that concurrently resident workgroups share few A and W slabs.
-__device__ __forceinline__ tile_coord decode_tile(int id, int tiles_m, int tiles_n) {
-  const int per_b = tiles_m * tiles_n;
-  tile_coord c;
-  c.b = id / per_b;
-  int r = id - c.b * per_b;
-  const int GMg = 4;
-  const int group_sz = GMg * tiles_n;
-  const int grp = r / group_sz;
-  const int first_m = grp * GMg;
-  const int rows_in = min(GMg, tiles_m - first_m);
-  r -= grp * group_sz;
-  c.tm = first_m + r % rows_in;
-  c.tn = r / rows_in;
-  return c;
-}
-
-// ------------------------------------------------------------------------------------------------
-// Fused epilogues on the accumulator layout of 32x32 MFMA tiles (lane l: column l%32; register v: row
-// 8*(v/4) + 4*(l/32) + v%4).  `stage` is the wavefront's private LDS patch (STAGE_ELEMS bf16 elements),
-// usable once the K loop is over; wave_m / wave_n are the first row / column of the wavefront's tile.
-// ------------------------------------------------------------------------------------------------
-template <int MI, int NI, int EPI, bool STAGED, int STAGE_ELEMS>
-__device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&acc)[MI][NI], bf16_t* stage, int b,
-                                              int wave_m, int wave_n, int lane) {
-  constexpr int TN = NI * 32;
-  const int col_l = lane & 31;
-  const int row_l = 4 * (lane >> 5);
-  (void)stage;
-  if constexpr (EPI == EPI_STORE_F32 || EPI == EPI_RESIDUAL) {
-    float* out = g.out + b * g.out_bstride;
-    const float* res = EPI == EPI_RESIDUAL ? g.res + b * g.res_bstride : nullptr;
-    constexpr int FPITCH = TN + 8;   // floats; +8 keeps the two half-waves on disjoint banks
-    constexpr int RCH = 32 * FPITCH * 2 <= STAGE_ELEMS ? 32 : 16;   // rows staged at a time
-    if constexpr (STAGED && RCH * FPITCH * 2 <= STAGE_ELEMS) {
-      // RCH rows at a time through the wavefront's LDS patch: the accumulator layout (a lane owns a
-      // column) becomes row pieces of 4 floats, so the residual read-modify-write moves 16 bytes per
-      // lane and whole 128-byte lines per row
-      float* fst = (float*)stage;
-      constexpr int LPR = TN / 4, RPI = 64 / LPR, ITS = RCH / RPI;
-      typedef float f32x4_t __attribute__((ext_vector_type(4)));
-      static_for<MI * (32 / RCH)>([&](auto C_) {
-        constexpr int mi = decltype(C_)::value / (32 / RCH), rc = decltype(C_)::value % (32 / RCH);
-        constexpr int row0 = rc * RCH;                 // first row of the chunk inside the 32-row block
-        static_for<RCH / 2>([&](auto V_) {
-          constexpr int v = (row0 / 8) * 4 + decltype(V_)::value;     // registers whose rows lie in the chunk
-          const int row_in = 8 * (v >> 2) + row_l + (v & 3) - row0;
-          static_for<NI>([&](auto NI_) {
-            constexpr int ni = decltype(NI_)::value;
-            fst[row_in * FPITCH + ni * 32 + col_l] = acc[mi][ni][v];
-          });
-        });
-        const int c4 = (lane % LPR) * 4, n = wave_n + c4;
-        constexpr int BATCH = ITS < 8 ? ITS : 8;
-        static_for<ITS / BATCH>([&](auto B_) {
-          constexpr int it0 = decltype(B_)::value * BATCH;
-          f32x4_t r4[BATCH];
-          if constexpr (EPI == EPI_RESIDUAL) {
-            static_for<BATCH>([&](auto I_) {
-              constexpr int i = decltype(I_)::value;
-              const int m = wave_m + mi * 32 + row0 + (it0 + i) * RPI + lane / LPR;
-              r4[i] = (m < g.M && n < g.N) ? *(const f32x4_t*)(res + (int64_t)m * g.ldo + n) : f32x4_t{0.f, 0.f, 0.f, 0.f};
-            });
-          }
-          static_for<BATCH>([&](auto I_) {
-            constexpr int i = decltype(I_)::value;
-            const int row_in = (it0 + i) * RPI + lane / LPR;
-            const int m = wave_m + mi * 32 + row0 + row_in;
-            f32x4_t x = *(const f32x4_t*)(fst + row_in * FPITCH + c4);
-            if constexpr (EPI == EPI_RESIDUAL) x += r4[i];
-            if (m < g.M && n < g.N) *(f32x4_t*)(out + (int64_t)m * g.ldo + n) = x;
-          });
-        });
-      });
-    } else {
-#pragma unroll
-      for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int m = wave_m + mi * 32 + 8 * (v >> 2) + row_l + (v & 3);
-          if (m < g.M) {
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni) {
-              const int n = wave_n + ni * 32 + col_l;
-              if (n < g.N) {
-                const int64_t idx = (int64_t)m * g.ldo + n;
-                float x = acc[mi][ni][v];
-                if constexpr (EPI == EPI_RESIDUAL) x += res[idx];
-                out[idx] = x;
-              }
-            }
-          }
-        }
-    }
-  } else if constexpr (EPI == EPI_SWIGLU) {
-    bf16_t* o = (bf16_t*)g.olp + b * g.olp_bstride;
-    const int ldo = g.N >> 1;
-    if constexpr (STAGED) {
-      // 32 rows at a time: products go to the wavefront's LDS patch as bf16, come back as 16-byte
-      // row pieces and leave as full 128-byte lines
-      constexpr int OC = TN / 2, PITCH = OC + 8, LPR = OC / 8, RPI = 64 / LPR;
-      static_assert(32 * PITCH <= STAGE_ELEMS, "staging patch too small");
-      static_for<MI>([&](auto MI_) {
-        constexpr int mi = decltype(MI_)::value;
-        static_for<16>([&](auto V_) {
-          constexpr int v = decltype(V_)::value;
-          const int row_in = 8 * (v >> 2) + row_l + (v & 3);
-          static_for<NI / 2>([&](auto P_) {
-            constexpr int pp = decltype(P_)::value;
-            stage[row_in * PITCH + 32 * pp + col_l] = f32_to_bf16(silu_fast(acc[mi][2 * pp][v]) * acc[mi][2 * pp + 1][v]);
-          });
-          if constexpr ((v & 3) == 3) __builtin_amdgcn_sched_barrier(0);   // bounds the scheduler's window (register pressure)
-        });
-        static_for<32 / RPI>([&](auto IT_) {
-          constexpr int it = decltype(IT_)::value;
-          const int row_in = it * RPI + lane / LPR, chunk = lane % LPR;
-          const u32x4_t val = *(const u32x4_t*)(stage + row_in * PITCH + chunk * 8);
-          const int m = wave_m + mi * 32 + row_in;
-          const int j = (wave_n >> 1) + chunk * 8;
-          if (m < g.M && 2 * j < g.N) *(u32x4_t*)(o + (int64_t)m * ldo + j) = val;
-        });
-      });
-    } else {
-#pragma unroll
-      for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int m = wave_m + mi * 32 + 8 * (v >> 2) + row_l + (v & 3);
-          if (m < g.M) {
-#pragma unroll
-            for (int ni = 0; ni < NI; ni += 2) {
-              const int j = ((wave_n + ni * 32) >> 1) + col_l;   // (phys/64)*32 + lane column
-              if (2 * j < g.N) o[(int64_t)m * ldo + j] = f32_to_bf16(silu_fast(acc[mi][ni][v]) * acc[mi][ni + 1][v]);
-            }
-          }
-        }
-    }
-  } else {  // EPI_QKV
-    const int hd = g.hd, half = hd >> 1, hq = g.H * hd, hk = g.Hkv * hd;
-    const bool wide = hd == 128;     // partner tile distance (hd/2)/32: 1 for hd 64, 2 for hd 128
-    const int hd_sh = wide ? 7 : 6;  // hd is 64 or 128 here: shifts and masks instead of runtime divisions
-    const bool s4 = (g.S & 3) == 0;  // 4 consecutive rows of a register group lie in one sequence
-    constexpr int QPITCH = TN + 8;   // bf16 elements per staged row of q / k
-    constexpr int VPITCH = 32 + 8;   // bf16 elements per staged V^T row (32 positions)
-    constexpr bool CAN_STAGE = STAGED && 32 * QPITCH <= STAGE_ELEMS && TN * VPITCH <= STAGE_ELEMS;
-    bool staged_done = false;
-    if constexpr (CAN_STAGE) {
-      // Aligned prefill (32-row blocks inside one sequence, positions a multiple of 8): 32 rows at a
-      // time go through the wavefront's LDS patch.  q and k are rotated in registers, staged row-major
-      // and leave as 16-byte row pieces; v is staged transposed and leaves as 16-byte pieces of V^T
-      // rows (8 consecutive positions of one head-dim index).
-      if ((g.S & 31) == 0 && (g.pos0 & 7) == 0 && wave_n < g.N) {
-        staged_done = true;
-        const bool is_qk = wave_n < hq + hk, is_q = wave_n < hq;
-        // cos/sin of (position, column): the table is read once per 32-row block, for the lane's first row;
-        // the lane's other rows follow by rotating with the table's entries for 1 and 5 positions (its rows
-        // are r, r+1, r+2, r+3, r+8, ...).  All loads are issued before the first staging store: a load after
-        // a store through the staging pointer would wait for it, and the registers to keep one table entry
-        // per accumulator element in flight are not there.  With hd = 64 every low-half tile uses column
-        // col_l, with hd = 128 the two low-half tiles use col_l and col_l + 32.
-        float2 cs_base[MI][2], rot1[2], rot5[2];
-        if (is_qk) {
-          const float2* tab = (const float2*)g.rope + col_l;
-          rot1[0] = tab[half];
-          rot5[0] = tab[5 * half];
-          if (wide) { rot1[1] = tab[half + 32]; rot5[1] = tab[5 * half + 32]; }
-          static_for<MI>([&](auto MI_) {
-            constexpr int mi = decltype(MI_)::value;
-            const int mrow0 = min(wave_m + mi * 32, g.M - 32);
-            const int seq = mrow0 / g.S, pos0b = g.pos0 + (mrow0 - seq * g.S);
-            const float2* rp = tab + (int64_t)(pos0b + row_l) * half;
-            cs_base[mi][0] = rp[0];
-            if (wide) cs_base[mi][1] = rp[32];
-          });
-        }
-        static_for<MI>([&](auto MI_) {
-          constexpr int mi = decltype(MI_)::value;
-          const int mrow0 = wave_m + mi * 32;           // first row of the block
-          if (mrow0 < g.M) {
-            const int seq = mrow0 / g.S, pos0b = g.pos0 + (mrow0 - seq * g.S);
-            if (is_qk) {
-              float2 cs_cur[2] = {cs_base[mi][0], wide ? cs_base[mi][1] : cs_base[mi][0]};
-              static_for<16>([&](auto V_) {
-                constexpr int v = decltype(V_)::value;
-                const int row_in = 8 * (v >> 2) + row_l + (v & 3);
-                if constexpr (v > 0) {
-#pragma unroll
-                  for (int w = 0; w < 2; ++w) {
-                    if (w == 1 && !wide) break;
-                    const float2 r = (v & 3) == 0 ? rot5[w] : rot1[w];
-                    const float2 c = cs_cur[w];
-                    cs_cur[w].x = c.x * r.x - c.y * r.y;
-                    cs_cur[w].y = c.y * r.x + c.x * r.y;
-                  }
-                }
-                static_for<NI>([&](auto NI_) {
-                  constexpr int ni = decltype(NI_)::value;
-                  constexpr int p1 = ni + 1 < NI ? ni + 1 : ni, p2 = ni + 2 < NI ? ni + 2 : ni;
-                  const int jb = (wave_n + ni * 32) & (hd - 1);   // wave-uniform
-                  if (jb < half) {
-                    const float2 cs = jb == 0 ? cs_cur[0] : cs_cur[1];
-                    const float lo = acc[mi][ni][v];
-                    const float hi = wide ? acc[mi][p2][v] : acc[mi][p1][v];
-                    stage[row_in * QPITCH + ni * 32 + col_l] = f32_to_bf16(lo * cs.x - hi * cs.y);
-                    stage[row_in * QPITCH + ni * 32 + col_l + half] = f32_to_bf16(hi * cs.x + lo * cs.y);
-                  }
-                });
-              });
-              constexpr int LPR = TN / 8, RPI = 64 / LPR;
-              const int c8 = (lane % LPR) * 8;
-              const int c = (is_q ? wave_n : wave_n - hq) + c8;       // column inside the q or k section
-              const int head = c >> hd_sh, j = c & (hd - 1);
-              static_for<32 / RPI>([&](auto IT_) {
-                constexpr int it = decltype(IT_)::value;
-                const int row_in = it * RPI + lane / LPR;
-                const u32x4_t val = *(const u32x4_t*)(stage + row_in * QPITCH + c8);
-                if (is_q) {
-                  *(u32x4_t*)((bf16_t*)g.olp + b * g.olp_bstride + (int64_t)(mrow0 + row_in) * hq + c) = val;
-                } else {
-                  const int64_t hidx = b * g.kv_bstride + seq * g.kv_seq_stride + head;
-                  *(u32x4_t*)((bf16_t*)g.kc + hidx * g.kv_head_elems + (int64_t)(pos0b + row_in) * hd + j) = val;
-                }
-              });
-            } else {
-              static_for<4>([&](auto VG_) {
-                constexpr int vg = decltype(VG_)::value;
-                static_for<NI>([&](auto NI_) {
-                  constexpr int ni = decltype(NI_)::value;
-                  uint2 pk;
-                  pk.x = pack_bf16x2(acc[mi][ni][vg * 4 + 0], acc[mi][ni][vg * 4 + 1]);
-                  pk.y = pack_bf16x2(acc[mi][ni][vg * 4 + 2], acc[mi][ni][vg * 4 + 3]);
-                  *(uint2*)(stage + (ni * 32 + col_l) * VPITCH + 8 * vg + row_l) = pk;
-                });
-              });
-              const int p8 = (lane & 3) * 8;
-              static_for<TN / 16>([&](auto IT_) {
-                constexpr int it = decltype(IT_)::value;
-                const int col = it * 16 + (lane >> 2);
-                const u32x4_t val = *(const u32x4_t*)(stage + col * VPITCH + p8);
-                const int c = wave_n - hq - hk + col;
-                const int head = c >> hd_sh, j = c & (hd - 1);
-                const int64_t hidx = b * g.kv_bstride + seq * g.kv_seq_stride + head;
-                *(u32x4_t*)((bf16_t*)g.vc + hidx * ((int64_t)hd * g.s_pad) + (int64_t)j * g.s_pad + pos0b + p8) = val;
-              });
-            }
-          }
-        });
-      }
-    }
-    if (!staged_done)
-    static_for<MI>([&](auto MI_) {
-      constexpr int mi = decltype(MI_)::value;
-      static_for<4>([&](auto VG_) {
-        constexpr int vg = decltype(VG_)::value;
-        const int mb = wave_m + mi * 32 + 8 * vg + row_l;   // rows mb .. mb+3
-        int seq4 = 0, pos4 = 0;
-        if (s4) {
-          seq4 = mb / g.S;
-          pos4 = g.pos0 + (mb - seq4 * g.S);
-        }
-        static_for<NI>([&](auto NI_) {
-          constexpr int ni = decltype(NI_)::value;
-          const int nb = wave_n + ni * 32;   // first column of this 32-wide tile (wave-uniform)
-          if (nb < hq + hk) {
-            // q or k: rotate (u_j, u_{j+hd/2}); the low half owns the pair
-            const bool is_q = nb < hq;
-            const int c = is_q ? nb : nb - hq;
-            const int head = c >> hd_sh, jb = c & (hd - 1);
-            if (jb < half && nb < g.N) {
-              const int j = jb + col_l;
-              constexpr int p1 = ni + 1 < NI ? ni + 1 : ni, p2 = ni + 2 < NI ? ni + 2 : ni;
-              static_for<4>([&](auto R_) {
-                constexpr int r = decltype(R_)::value;
-                const int m = mb + r;
-                if (m < g.M) {
-                  int seq, pos;
-                  if (s4) { seq = seq4; pos = pos4 + r; }
-                  else { seq = m / g.S; pos = g.pos0 + (m - seq * g.S); }
-                  const float2 cs = ((const float2*)g.rope)[(int64_t)pos * half + j];
-                  const float lo = acc[mi][ni][vg * 4 + r];
-                  const float hi = wide ? acc[mi][p2][vg * 4 + r] : acc[mi][p1][vg * 4 + r];
-                  const bf16_t rlo = f32_to_bf16(lo * cs.x - hi * cs.y);
-                  const bf16_t rhi = f32_to_bf16(hi * cs.x + lo * cs.y);
-                  if (is_q) {
-                    bf16_t* q = (bf16_t*)g.olp + b * g.olp_bstride + (int64_t)m * hq + nb + col_l;
-                    q[0] = rlo;
-                    q[half] = rhi;
-                  } else {
-                    const int64_t hidx = b * g.kv_bstride + seq * g.kv_seq_stride + head;
-                    bf16_t* k = (bf16_t*)g.kc + hidx * g.kv_head_elems + (int64_t)pos * hd + j;
-                    k[0] = rlo;
-                    k[half] = rhi;
-                  }
-                }
-              });
-            }
-          } else if (nb < g.N) {
-            // v: transposed store, 4 consecutive positions of one head-dim row
-            const int c = nb - hq - hk;
-            const int head = c >> hd_sh, j = (c & (hd - 1)) + col_l;
-            if (s4 && mb + 3 < g.M && (pos4 & 3) == 0) {
-              const int64_t hidx = b * g.kv_bstride + seq4 * g.kv_seq_stride + head;
-              bf16_t* v = (bf16_t*)g.vc + hidx * ((int64_t)hd * g.s_pad) + (int64_t)j * g.s_pad + pos4;
-              uint2 pk;
-              pk.x = pack_bf16x2(acc[mi][ni][vg * 4 + 0], acc[mi][ni][vg * 4 + 1]);
-              pk.y = pack_bf16x2(acc[mi][ni][vg * 4 + 2], acc[mi][ni][vg * 4 + 3]);
-              *(uint2*)v = pk;
-            } else {
-              static_for<4>([&](auto R_) {
-                constexpr int r = decltype(R_)::value;
-                const int m = mb + r;
-                if (m < g.M) {
-                  const int seq = m / g.S, pos = g.pos0 + (m - seq * g.S);
-                  const int64_t hidx = b * g.kv_bstride + seq * g.kv_seq_stride + head;
-                  ((bf16_t*)g.vc)[hidx * ((int64_t)hd * g.s_pad) + (int64_t)j * g.s_pad + pos] = f32_to_bf16(acc[mi][ni][vg * 4 + r]);
-                }
-              });
-            }
-          }
-        });
-      });
-    });
-  }
-}
-
-template <int BM, int BN, int WM, int WN, int BK, int EPI>
-__global__ void __launch_bounds__(WM * WN * 64, (2 * (BM + BN) * BK * 2 <= 80 * 1024 && BM * BN <= 256 * 128 && WM * WN == 4) ? 2 : 1)
-gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
-  constexpr int NT = WM * WN * 64;
-  constexpr int TM = BM / WM, TN = BN / WN, MI = TM / 32, NI = TN / 32;
-  constexpr int CPR = BK / 8;        // 16-byte chunks per LDS row
-  constexpr int SS = BK / 16;        // MFMA sub-steps per K step
-  constexpr int A_CH = BM * CPR / NT, B_CH = BN * CPR / NT;  // 16-byte chunks per thread and K step
-  static_assert(BK == 64 || BK == 32, "K step");
-  static_assert(BM * CPR % NT == 0 && BN * CPR % NT == 0, "tile/threads mismatch");
-  // XOR swizzle of the 16-byte chunks: any 16 consecutive rows reading the same logical chunk hit 16
-  // different 16-byte columns of a 256-byte LDS line (gfx950 serves 16 lanes x 16 B per clock)
-  auto SWZ = [](int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); };
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  bf16_t* As = (bf16_t*)smem;            // [2][BM][BK]
-  bf16_t* Bs = As + 2 * BM * BK;      // [2][BN][BK]
-
-  GM_STAMP(0);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / WN, wn = wave % WN;
-  const tile_coord tc = decode_tile(logical_tile(blockIdx.x, gridDim.x), tiles_m, tiles_n);
-  const int m0 = tc.tm * BM, n0 = tc.tn * BN, b = tc.b;
-
-  // global -> register staging: chunk id = tid + i*NT; row = id/CPR, 16-byte chunk = id%CPR.
-  // Rows of one thread are NT/CPR apart, a multiple of 16, so they share the swizzle and the LDS
-  // destinations differ by a constant.
-  const int ld_row = tid / CPR, ld_ch = tid % CPR;
-  static_assert((NT / CPR) % 16 == 0, "staging rows must keep the swizzle");
-  constexpr int ST_STRIDE = (NT / CPR) * BK;                    // elements between a thread's staging rows
-  const int st_dst = ld_row * BK + ((ld_ch ^ SWZ(ld_row)) * 8);
-  u32x4_t a_reg[2][A_CH], w_reg[2][B_CH];                        // two staging sets: K steps of equal parity
-
-  const int KT = g.K / BK;   // even, >= 2
-  uint32_t a_voff[A_CH], w_voff[B_CH];   // byte offsets from the tile's first row
-#pragma unroll
-  for (int i = 0; i < A_CH; ++i) {
-    const int gr = min(m0 + ld_row + i * (NT / CPR), g.M - 1) - m0;
-    a_voff[i] = (uint32_t)((gr * g.lda + ld_ch * 8) * 2);
-  }
-#pragma unroll
-  for (int i = 0; i < B_CH; ++i) {
-    const int gr = min(n0 + ld_row + i * (NT / CPR), g.N - 1) - n0;
-    w_voff[i] = (uint32_t)((gr * g.ldb + ld_ch * 8) * 2);
-  }
-  const char* a_base = (const char*)((const bf16_t*)g.A + b * g.a_bstride + (int64_t)m0 * g.lda);   // wave-uniform
-  const char* w_base = (const char*)((const bf16_t*)g.W + b * g.w_bstride + (int64_t)n0 * g.ldb);
-  auto load_a = [&](int set, int i, int kstep) { a_reg[set][i] = *(const u32x4_t*)(a_base + (size_t)kstep * (BK * 2) + a_voff[i]); };
-  auto load_w = [&](int set, int i, int kstep) { w_reg[set][i] = *(const u32x4_t*)(w_base + (size_t)kstep * (BK * 2) + w_voff[i]); };
-
-  // operand reads: row = tile row + lane%32, 16-byte chunk = 2*kk + lane/32, swizzled by the row
-  const int fr_row = lane & 31, fr_half = lane >> 5, fr_sw = SWZ(lane & 31);
-  int a_fr[SS], b_fr[SS];   // element offsets of sub-step kk inside a buffer, first MFMA tile of the wavefront
-#pragma unroll
-  for (int kk = 0; kk < SS; ++kk) {
-    const int ch = ((kk * 2 + fr_half) ^ fr_sw) * 8;
-    a_fr[kk] = (wm * TM + fr_row) * BK + ch;
-    b_fr[kk] = (wn * TN + fr_row) * BK + ch;
-  }
-
-  // Software pipeline (K step = 64).  In every iteration the MFMAs run out of LDS buffer `cur` while
-  //   sub-steps 0,1: the next K step (staging set cur^1, loaded two iterations ago) is stored into the
-  //                  other LDS buffer,
-  //   sub-steps 2,3: the K step three ahead is loaded from global memory into the set just freed,
-  //   every sub-step: the operand fragments of the next sub-step are read from LDS,
-  // and every memory instruction is issued between two MFMAs, so no queue sees a burst.  The one
-  // barrier of the iteration sits in front of sub-step 3: after it the first fragments of the next
-  // K step are fetched in the shadow of the last MFMAs.
-#pragma unroll
-  for (int i = 0; i < A_CH; ++i) load_a(0, i, 0);
-#pragma unroll
-  for (int i = 0; i < B_CH; ++i) load_w(0, i, 0);
-#pragma unroll
-  for (int i = 0; i < A_CH; ++i) load_a(1, i, 1);
-#pragma unroll
-  for (int i = 0; i < B_CH; ++i) load_w(1, i, 1);
-#pragma unroll
-  for (int i = 0; i < A_CH; ++i) *(u32x4_t*)(As + st_dst + i * ST_STRIDE) = a_reg[0][i];
-#pragma unroll
-  for (int i = 0; i < B_CH; ++i) *(u32x4_t*)(Bs + st_dst + i * ST_STRIDE) = w_reg[0][i];
-#pragma unroll
-  for (int i = 0; i < A_CH; ++i) load_a(0, i, min(2, KT - 1));
-#pragma unroll
-  for (int i = 0; i < B_CH; ++i) load_w(0, i, min(2, KT - 1));
-  __syncthreads();
-
-  GM_STAMP(1);
-  bf16x8_t af[2][MI], bfr[2][NI];
-#pragma unroll
-  for (int mi = 0; mi < MI; ++mi) af[0][mi] = *(const bf16x8_t*)(As + a_fr[0] + mi * 32 * BK);
-#pragma unroll
-  for (int ni = 0; ni < NI; ++ni) bfr[0][ni] = *(const bf16x8_t*)(Bs + b_fr[0] + ni * 32 * BK);
-
-  constexpr int NM = MI * NI;                  // MFMAs per sub-step
-  constexpr int FR = MI + NI;                  // fragment reads per sub-step
-  constexpr int EX = A_CH + B_CH;              // staging chunks per K step
-  constexpr int HS = SS / 2;                   // sub-steps that store, then as many that load
-  constexpr int EXH = (EX + HS - 1) / HS;      // staging chunks handled per sub-step
-
-  f32x16_t acc[MI][NI];
-
-  auto iteration = [&](auto PAR, int kt) {
-    constexpr int cur = decltype(PAR)::value;          // LDS buffer being multiplied
-    constexpr int wset = cur ^ 1;                       // staging set stored, then reloaded
-    const bf16_t* Ac = As + cur * BM * BK;
-    const bf16_t* Bc = Bs + cur * BN * BK;
-    bf16_t* An = As + (cur ^ 1) * BM * BK;
-    bf16_t* Bn = Bs + (cur ^ 1) * BN * BK;
-    const int kload = min(kt + 3, KT - 1);   // K steps past the end re-read the last one (never multiplied)
-    static_for<SS>([&](auto KK) {
-      constexpr int kk = decltype(KK)::value;
-      constexpr int fb = (kk + 1) & 1;                  // fragment buffer being filled
-      constexpr int R = FR + EXH;                       // memory instructions of this sub-step
-      if constexpr (kk == SS - 1) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-      static_for<NM>([&](auto J) {
-        constexpr int j = decltype(J)::value;
-        constexpr int mi = j / NI, ni = j % NI;
-        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][mi], bfr[kk & 1][ni], acc[mi][ni], 0, 0, 0);
-        constexpr int lo = j * R / NM, hi = (j + 1) * R / NM;
-        static_for<hi - lo>([&](auto RR) {
-          constexpr int r = lo + decltype(RR)::value;
-          if constexpr (r < MI) {
-            const bf16_t* src = kk == SS - 1 ? An + a_fr[0] : Ac + a_fr[(kk + 1) % SS];
-            af[fb][r] = *(const bf16x8_t*)(src + r * 32 * BK);
-          } else if constexpr (r < FR) {
-            const bf16_t* src = kk == SS - 1 ? Bn + b_fr[0] : Bc + b_fr[(kk + 1) % SS];
-            bfr[fb][r - MI] = *(const bf16x8_t*)(src + (r - MI) * 32 * BK);
-          } else {
-            constexpr int e = (kk % HS) * EXH + (r - FR);   // staging chunk
-            if constexpr (e < EX) {
-              if constexpr (kk < HS) {
-                if constexpr (e < A_CH) *(u32x4_t*)(An + st_dst + e * ST_STRIDE) = a_reg[wset][e];
-                else *(u32x4_t*)(Bn + st_dst + (e - A_CH) * ST_STRIDE) = w_reg[wset][e - A_CH];
-              } else {
-                if constexpr (e < A_CH) load_a(wset, e, kload);
-                else load_w(wset, e - A_CH, kload);
-              }
-            }
-          }
-        });
-        __builtin_amdgcn_sched_barrier(0);
-      });
-    });
-  };
-
-#pragma unroll
-  for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
-  for (int kt = 0; kt < KT; kt += 2) {
-    iteration(std::integral_constant<int, 0>{}, kt);
-    iteration(std::integral_constant<int, 1>{}, kt + 1);
-  }
-  __syncthreads();   // LDS is free for the staged epilogues
-  GM_STAMP(2);
-
-  // ------------------------------------------------------------------ epilogue
-  // LDS patch of this wavefront for the staged epilogues (the K loop is over: all of LDS is free)
-  constexpr bool STAGED = BM >= 128 && BN >= 128;
-  constexpr int STAGE_ELEMS = 2 * (BM + BN) * BK / (WM * WN);   // per wavefront
-  bf16_t* stage = (bf16_t*)smem + wave * STAGE_ELEMS;
-  (void)stage;
-  const int wave_n = n0 + wn * TN;
-  const int wave_m = m0 + wm * TM;
-
-  gemm_epilogue<MI, NI, EPI, STAGED, STAGE_ELEMS>(g, acc, stage, b, wave_m, wave_n, lane);
-  GM_STAMP(3);
-}
-
-// ------------------------------------------------------------------------------------------------
-// Variant with direct global -> LDS loads (gfx950 global_load_lds_dwordx4): operand tiles never touch
-// registers on their way in.  K step 32, four LDS stages; the loads of K step kt+3 are issued while
-// step kt is multiplied, so three steps are always in flight.  A wavefront instruction moves 64 x 16
-// bytes into 1024 consecutive LDS bytes = 16 rows of 64 bytes; lane L therefore fetches, for row L/4,
-// the logical chunk (L%4) ^ swizzle(row), which yields the same conflict-free swizzled layout as the
-// register-staged kernel.  With 8 wavefronts (2 per SIMD, 128 accumulator registers each) one
-// wavefront's LDS and barrier waits are covered by the other's MFMAs.
-// ------------------------------------------------------------------------------------------------
-template <int BM, int BN, int WM, int WN, int EPI>
-__global__ void __launch_bounds__(WM * WN * 64, WM * WN == 8 ? 2 : 1)
-gemm_dl_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
-  constexpr int BK = 32, NSTG = 4, NW = WM * WN;
-  constexpr int TM = BM / WM, TN = BN / WN, MI = TM / 32, NI = TN / 32;
-  constexpr int STG = (BM + BN) * BK;                 // elements per stage: A rows then W rows
-  constexpr int LA = BM / 16 / NW, LB = BN / 16 / NW; // 16-row groups (= load instructions) per wavefront and K step
-  static_assert(BM / 16 % NW == 0 && BN / 16 % NW == 0, "tile/wavefront mismatch");
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  bf16_t* lds = (bf16_t*)smem;
-  auto SWZ = [](int row) { return (row >> 2) & 3; };
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / WN, wn = wave % WN;
-  const tile_coord tc = decode_tile(logical_tile(blockIdx.x, gridDim.x), tiles_m, tiles_n);
-  const int m0 = tc.tm * BM, n0 = tc.tn * BN, b = tc.b;
-  const int KT = g.K / BK;   // multiple of 4
-
-  // direct loads: group grp covers tile rows grp*16 .. +15; this lane fetches row L/4, logical chunk (L%4)^swz
-  const int rr = lane >> 2, pc = lane & 3;
-  uint32_t a_voff[LA], w_voff[LB];
-#pragma unroll
-  for (int i = 0; i < LA; ++i) {
-    const int row = (wave * LA + i) * 16 + rr;
-    const int gr = min(m0 + row, g.M - 1) - m0;
-    a_voff[i] = (uint32_t)((gr * g.lda + (pc ^ SWZ(row)) * 8) * 2);
-  }
-#pragma unroll
-  for (int i = 0; i < LB; ++i) {
-    const int row = (wave * LB + i) * 16 + rr;
-    const int gr = min(n0 + row, g.N - 1) - n0;
-    w_voff[i] = (uint32_t)((gr * g.ldb + (pc ^ SWZ(row)) * 8) * 2);
-  }
-  const char* a_base = (const char*)((const bf16_t*)g.A + b * g.a_bstride + (int64_t)m0 * g.lda);
-  const char* w_base = (const char*)((const bf16_t*)g.W + b * g.w_bstride + (int64_t)n0 * g.ldb);
-  typedef const __attribute__((address_space(1))) void* gptr_t;
-  typedef __attribute__((address_space(3))) void* lptr_t;
-  auto issue_load = [&](int i, int kstep, int stage) {   // i < LA: A group, else W group
-    if (i < LA)
-      __builtin_amdgcn_global_load_lds((gptr_t)(a_base + (size_t)kstep * (BK * 2) + a_voff[i]),
-                                       (lptr_t)(lds + stage * STG + (wave * LA + i) * 16 * BK), 16, 0, 0);
-    else
-      __builtin_amdgcn_global_load_lds((gptr_t)(w_base + (size_t)kstep * (BK * 2) + w_voff[i - LA]),
-                                       (lptr_t)(lds + stage * STG + BM * BK + (wave * LB + (i - LA)) * 16 * BK), 16, 0, 0);
-  };
-
-  // operand fragments: row = tile row + lane%32, 16-byte chunk = 2*kk + lane/32, swizzled by the row
-  const int fr_row = lane & 31, fr_half = lane >> 5;
-  int a_fr[2], b_fr[2];
-#pragma unroll
-  for (int kk = 0; kk < 2; ++kk) {
-    const int ra = wm * TM + fr_row, rb = wn * TN + fr_row;
-    a_fr[kk] = ra * BK + (((kk * 2 + fr_half) ^ SWZ(ra)) * 8);
-    b_fr[kk] = BM * BK + rb * BK + (((kk * 2 + fr_half) ^ SWZ(rb)) * 8);
-  }
-
-  f32x16_t acc[MI][NI];
-#pragma unroll
-  for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
-
-  constexpr int LPW = LA + LB;   // loads per wavefront and K step
-#pragma unroll
-  for (int st = 0; st < 3; ++st)
-#pragma unroll
-    for (int i = 0; i < LPW; ++i) issue_load(i, min(st, KT - 1), st);
-  // K step 0 has landed once at most the two younger steps are outstanding
-  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(2 * LPW) : "memory");
-
-  bf16x8_t af[2][MI], bfr[2][NI];
-#pragma unroll
-  for (int mi = 0; mi < MI; ++mi) af[0][mi] = *(const bf16x8_t*)(lds + a_fr[0] + mi * 32 * BK);
-#pragma unroll
-  for (int ni = 0; ni < NI; ++ni) bfr[0][ni] = *(const bf16x8_t*)(lds + b_fr[0] + ni * 32 * BK);
-
-  constexpr int NM = MI * NI, FR = MI + NI;
-  auto iteration = [&](auto STAGE, int kt) {
-    constexpr int st = decltype(STAGE)::value;            // stage being multiplied = kt % 4
-    const bf16_t* cur = lds + st * STG;
-    const bf16_t* nxt = lds + ((st + 1) & 3) * STG;
-    const int kload = min(kt + 3, KT - 1);                 // steps past the end re-read the last one into a dead stage
-    static_for<2>([&](auto KK) {
-      constexpr int kk = decltype(KK)::value;
-      constexpr int R = kk == 0 ? FR + LPW : FR;           // memory instructions of this sub-step
-      if constexpr (kk == 1)
-        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * LPW) : "memory");
-      static_for<NM>([&](auto J) {
-        constexpr int j = decltype(J)::value;
-        constexpr int mi = j / NI, ni = j % NI;
-        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk][mi], bfr[kk][ni], acc[mi][ni], 0, 0, 0);
-        constexpr int lo = j * R / NM, hi = (j + 1) * R / NM;
-        static_for<hi - lo>([&](auto RR) {
-          constexpr int r = lo + decltype(RR)::value;
-          if constexpr (r < MI) {
-            const bf16_t* src = kk == 1 ? nxt + a_fr[0] : cur + a_fr[1];
-            af[kk ^ 1][r] = *(const bf16x8_t*)(src + r * 32 * BK);
-          } else if constexpr (r < FR) {
-            const bf16_t* src = kk == 1 ? nxt + b_fr[0] : cur + b_fr[1];
-            bfr[kk ^ 1][r - MI] = *(const bf16x8_t*)(src + (r - MI) * 32 * BK);
-          } else {
-            issue_load(r - FR, kload, (st + 3) & 3);
-          }
-        });
-        __builtin_amdgcn_sched_barrier(0);
-      });
-    });
-  };
-  for (int kt = 0; kt < KT; kt += 4) {
-    iteration(std::integral_constant<int, 0>{}, kt);
-    iteration(std::integral_constant<int, 1>{}, kt + 1);
-    iteration(std::integral_constant<int, 2>{}, kt + 2);
-    iteration(std::integral_constant<int, 3>{}, kt + 3);
-  }
-  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");   // no load may still be landing in LDS
-
-  constexpr bool STAGED = true;
-  constexpr int STAGE_ELEMS = NSTG * STG / NW;   // per wavefront
-  bf16_t* stage = lds + wave * STAGE_ELEMS;
-  gemm_epilogue<MI, NI, EPI, STAGED, STAGE_ELEMS>(g, acc, stage, b, m0 + wm * TM, n0 + wn * TN, lane);
-}
-
-template <int BM, int BN, int WM, int WN, int EPI>
-static int launch_dl(const pt_gemm_args& g, hipStream_t s) {
-  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
-  const size_t lds = (size_t)4 * (BM + BN) * 32 * sizeof(bf16_t);
-  auto kern = gemm_dl_kernel<BM, BN, WM, WN, EPI>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    PT_HIP_CHECK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    attr_set = true;
-  }
-  const int64_t total = (int64_t)tiles_m * tiles_n * g.batch;
-  if (total > 0x7fffffff) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "GEMM grid too large");
-  hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(WM * WN * 64), lds, s, g, tiles_m, tiles_n);
-  PT_HIP_CHECK(hipGetLastError());
-  return 1;
-}
-
-template <int BM, int BN, int WM, int WN, int BK, int EPI>
-static int launch_cfg(const pt_gemm_args& g, hipStream_t s) {
-  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
-  const size_t lds = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t);
-  auto kern = gemm_mfma_kernel<BM, BN, WM, WN, BK, EPI>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    PT_HIP_CHECK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    attr_set = true;
-  }
-  const int64_t total = (int64_t)tiles_m * tiles_n * g.batch;
-  if (total > 0x7fffffff) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "GEMM grid too large");
-  const unsigned grid = (unsigned)total;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), lds, s, g, tiles_m, tiles_n);
-  PT_HIP_CHECK(hipGetLastError());
-  return 1;
-}
+template <int EPI, int CFG>
+int pt_gemm_mfma_launch_one(const pt_gemm_args& g, hipStream_t s);
 
 template <int EPI>
 static int launch_epi(const pt_gemm_args& g, hipStream_t s, int cfg) {
   switch (cfg) {
-    case 0: return launch_cfg<256, 256, 2, 2, 64, EPI>(g, s);
-    case 1: return launch_cfg<256, 128, 2, 2, 32, EPI>(g, s);
-    case 2: return launch_cfg<128, 128, 2, 2, 64, EPI>(g, s);
-    case 3: return launch_cfg<64, 256, 1, 4, 64, EPI>(g, s);
-    case 4: return launch_cfg<128, 256, 2, 2, 64, EPI>(g, s);
-    case 5: return launch_cfg<32, 256, 1, 4, 64, EPI>(g, s);
-    case 6: return launch_cfg<64, 256, 1, 2, 64, EPI>(g, s);
-    case 7: return launch_cfg<32, 256, 1, 2, 64, EPI>(g, s);
-    case 8: return launch_cfg<128, 256, 2, 2, 32, EPI>(g, s);
-    case 9: return launch_cfg<128, 128, 2, 2, 32, EPI>(g, s);
-    case 10: return launch_dl<256, 256, 4, 2, EPI>(g, s);
-    default: return launch_dl<256, 256, 2, 2, EPI>(g, s);
+    case 0: return pt_gemm_mfma_launch_one<EPI, 0>(g, s);
+    case 1: return pt_gemm_mfma_launch_one<EPI, 1>(g, s);
+    case 2: return pt_gemm_mfma_launch_one<EPI, 2>(g, s);
+    case 3: return pt_gemm_mfma_launch_one<EPI, 3>(g, s);
+    case 4: return pt_gemm_mfma_launch_one<EPI, 4>(g, s);
+    case 5: return pt_gemm_mfma_launch_one<EPI, 5>(g, s);
+    case 6: return pt_gemm_mfma_launch_one<EPI, 6>(g, s);
+    case 7: return pt_gemm_mfma_launch_one<EPI, 7>(g, s);
+    case 8: return pt_gemm_mfma_launch_one<EPI, 8>(g, s);
+    case 9: return pt_gemm_mfma_launch_one<EPI, 9>(g, s);
+    case 10: return pt_gemm_mfma_launch_one<EPI, 10>(g, s);
+    default: return pt_gemm_mfma_launch_one<EPI, 11>(g, s);
   }
 }
+
+#define GM_BK 64
 
 // Tile configuration override for tuning runs: -1 = choose by shape.
 int pt_gemm_mfma_force_cfg = -1;
