@@ -323,9 +323,32 @@ __global__ void __launch_bounds__(256) argmax_kernel(const float* __restrict__ l
   const float* row = logits + (int64_t)blockIdx.x * vocab;
   float best = -INFINITY;
   int32_t bi = 0x7fffffff;
-  for (int i = threadIdx.x; i < vocab; i += 256) {
-    const float v = row[i];
-    if (v > best || (v == best && i < bi)) { best = v; bi = i; }
+  // 16-byte loads, four in flight per thread (vocab is a multiple of 4 and rows are 16-byte aligned when the
+  // logits buffer is; otherwise one element at a time)
+  if ((vocab & 3) == 0 && ((uintptr_t)row & 15) == 0) {
+    const int n4 = vocab >> 2;
+    for (int i0 = threadIdx.x; i0 < n4; i0 += 4 * 256) {
+      float4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int i4 = i0 + u * 256;
+        v[u] = i4 < n4 ? ((const float4*)row)[i4] : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (i0 + u * 256 >= n4) break;
+        const int i = 4 * (i0 + u * 256);
+        const float e[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (e[j] > best || (e[j] == best && i + j < bi)) { best = e[j]; bi = i + j; }
+      }
+    }
+  } else {
+    for (int i = threadIdx.x; i < vocab; i += 256) {
+      const float v = row[i];
+      if (v > best || (v == best && i < bi)) { best = v; bi = i; }
+    }
   }
   sv[threadIdx.x] = best;
   si[threadIdx.x] = bi;
