@@ -133,12 +133,12 @@ __device__ __forceinline__ void sk_finish(const pt_gemm_args& g, int b, int tile
 // parked in LDS private to the wavefront and picked up from there as MFMA fragments.  Row r of a parked
 // block holds its 16-byte chunk c at position c ^ swizzle(r): writes and fragment reads are conflict-free.
 // Weight rows use two rotating register sets, refilled with step s+2 as soon as step s is parked, so two
-// steps of weights are in flight per wavefront; A uses one register set and two LDS slots.
+// steps of weights are in flight per wavefront; A uses one register set and one LDS slot.
 template <int MI, int RB, int EPI>
 __device__ __forceinline__ void skinny_body(const pt_gemm_args& g, int b, int first_tile, int ks, int ksn) {
   constexpr int A_STEP = MI * 32 * 128;                 // bytes of A per K step
   constexpr int W_STEP = RB * 32 * 128;                 // bytes of W per K step
-  constexpr int RING = 2 * A_STEP + W_STEP;             // per wavefront
+  constexpr int RING = A_STEP + W_STEP;                 // per wavefront
   extern __shared__ __attribute__((aligned(1024))) char smem[];   // max(4 * RING, reduction buffer) bytes
   float (*red)[MI][16][64] = (float (*)[MI][16][64])smem;         // reuses the rings after the K loop
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -150,7 +150,7 @@ __device__ __forceinline__ void skinny_body(const pt_gemm_args& g, int b, int fi
   // staging: load i of a 32-row block brings rows 8i .. 8i+7, lane L the chunk L%8 of row 8i + L/8
   auto swz = [](int row) { return (row >> 1) & 7; };
   char* a_ring = smem + wave * RING;
-  char* w_slot = a_ring + 2 * A_STEP;
+  char* w_slot = a_ring + A_STEP;
   int dst[4];   // position inside a parked 32-row block
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -180,7 +180,8 @@ __device__ __forceinline__ void skinny_body(const pt_gemm_args& g, int b, int fi
     for (int j = 0; j < 4 * MI; ++j) areg[j] = *(const u32x4_t*)(a_src[j] + step * 64);
   };
   auto park_a = [&](int step) {
-    char* slot = a_ring + (step & 1) * A_STEP;
+    char* slot = a_ring;
+    (void)step;
 #pragma unroll
     for (int j = 0; j < 4 * MI; ++j) *(u32x4_t*)(slot + (j >> 2) * 4096 + dst[j & 3]) = areg[j];
   };
@@ -208,7 +209,8 @@ __device__ __forceinline__ void skinny_body(const pt_gemm_args& g, int b, int fi
       for (int v = 0; v < 16; ++v) acc[rb][mi][v] = 0.f;
 
   auto mul_step = [&](int step) {
-    const char* a_slot = a_ring + (step & 1) * A_STEP;
+    const char* a_slot = a_ring;
+    (void)step;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int fo = fr_row + (((2 * u + half) ^ fr_sw) * 16);
@@ -245,11 +247,11 @@ __device__ __forceinline__ void skinny_body(const pt_gemm_args& g, int b, int fi
       __builtin_amdgcn_sched_barrier(0);
       load_w(par, min(st + 2, nsteps - 1));
       __builtin_amdgcn_sched_barrier(0);
-      park_a(st + 1);                             // into the slot of step st-1
+      mul_step(st);
+      __builtin_amdgcn_sched_barrier(0);
+      park_a(st + 1);                             // the fragments of step st have been read
       __builtin_amdgcn_sched_barrier(0);
       load_a(min(st + 2, nsteps - 1));
-      __builtin_amdgcn_sched_barrier(0);
-      mul_step(st);
     }
   }
   __syncthreads();   // the rings become the reduction buffer
@@ -481,7 +483,7 @@ struct sk_plan { int wpt, ks; };
 template <int MI, int RBHI, int EPI>
 static int launch_skinny_rb(const pt_gemm_args& g, int tiles, sk_plan p, hipStream_t s) {
   const unsigned grid = (unsigned)((int64_t)p.wpt * g.batch * p.ks);
-  constexpr int RING = 4 * (2 * MI + RBHI) * 32 * 128, RED = 4 * MI * 16 * 64 * 4;
+  constexpr int RING = 4 * (MI + RBHI) * 32 * 128, RED = 4 * MI * 16 * 64 * 4;
   constexpr int LDS = RING > RED ? RING : RED;
   auto kern = gemm_skinny_kernel<MI, RBHI, EPI>;
   static bool configured = false;
