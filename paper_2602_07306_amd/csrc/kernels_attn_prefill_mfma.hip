@@ -254,14 +254,14 @@ __global__ void __launch_bounds__(256, HD == 64 ? 3 : 2) attn_prefill_lds_kernel
 
     if (active && kt * 64 <= q0 + 31) {       // wave-uniform: tiles entirely above the diagonal are skipped
       f32x16_t s[2];
+      const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int rb = 0; rb < 2; ++rb) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) s[rb][v] = 0.f;
-#pragma unroll
         for (int kk = 0; kk < KS; ++kk) {
           const bf16x8_t kf = *(const bf16x8_t*)(Kc + k_fr[rb][kk]);
-          s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s[rb], 0, 0, 0);
+          // the first product takes the constant 0 as its addend: no register zeroing
+          s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], kk == 0 ? zero16 : s[rb], 0, 0, 0);
         }
       }
       // register v of block rb: key kt*64 + rb*32 + 16*(v/8) + 8*half + v%8, query q0 + l32
@@ -279,9 +279,22 @@ __global__ void __launch_bounds__(256, HD == 64 ? 3 : 2) attn_prefill_lds_kernel
 #pragma unroll
         for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[rb][v]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run, mx);
-      const float corr = __builtin_amdgcn_exp2f((m_run - m_new) * c_log2);
-      const float mc = m_new * c_log2;
+      // The reference of the exponentials moves to the new maximum only when that exceeds the old reference by
+      // more than 8 binary orders (always on the first tile, where the reference is -inf); until then the
+      // probabilities stay below 2^8 relative to the reference, which fp32 sums and bf16 operands hold without
+      // loss, and the accumulators need no rescaling.  Both half-waves of a query see the same mx.
+      const bool grow = (mx - m_run) * c_log2 > 8.0f;
+      if (__any(grow)) {
+        const float m_new = grow ? mx : m_run;
+        const float corr = __builtin_amdgcn_exp2f((m_run - m_new) * c_log2);
+        l_run *= corr;
+        m_run = m_new;
+#pragma unroll
+        for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) oacc[hb][v] *= corr;
+      }
+      const float mc = m_run * c_log2;
       float psum = 0.f;
 #pragma unroll
       for (int rb = 0; rb < 2; ++rb)
@@ -290,14 +303,7 @@ __global__ void __launch_bounds__(256, HD == 64 ? 3 : 2) attn_prefill_lds_kernel
           s[rb][v] = __builtin_amdgcn_exp2f(fmaf(s[rb][v], c_log2, -mc));
           psum += s[rb][v];
         }
-      l_run = l_run * corr + psum;
-      m_run = m_new;
-      if (__any(corr != 1.0f)) {
-#pragma unroll
-        for (int hb = 0; hb < HB; ++hb)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) oacc[hb][v] *= corr;
-      }
+      l_run += psum;
       pk8 pf[4];   // 16-key steps: (rb, u) -> rb*2 + u
 #pragma unroll
       for (int st = 0; st < 4; ++st)
