@@ -233,6 +233,117 @@ def run_paper_sweep(args, torch, PB, I):
     return out
 
 
+def run_large_configs(args, torch, PB, I):
+    """The two large BASELINE configurations on the same kernels: Large PT (T=8, L=32, D=8, d=2048, 16 heads x
+    128, FFN 8192) and one GPU's share of the wide model (one track, 8 layers, d=8192, 64 heads x 128, FFN
+    28672).  Prefill at the stated batch; decode at the stated batch and context, except that Large's decode
+    as written (MHA, batch 64, context 4096) needs a 550 GB KV cache: it runs with 2 KV heads per track at
+    batch 64 and as written (MHA) at batch 16."""
+    classes = ["rmsnorm", "gemm_qkv", "attn_prefill", "attn_decode", "gemm_out", "gemm_gateup", "gemm_down", "merge"]
+    out = []
+
+    def breakdown(model, nsteps):
+        r = {}
+        for c in classes:
+            ms, n = model.pt_profile_read(c)
+            if n:
+                r[c] = ms / nsteps
+        return r
+
+    def prefill_case(name, cfg, B, S, seed):
+        model = PB.PTModel(cfg)
+        model.pt_init_weights(seed)
+        if cfg.vocab:
+            kw = dict(tokens=torch.from_numpy(I.make_tokens(seed, B, S, cfg.vocab)).cuda(),
+                      logits_mode=PB.PT_LOGITS_LAST,
+                      logits_out=torch.empty((B, cfg.vocab), dtype=torch.float32, device="cuda"))
+            head_rows = B
+        else:
+            kw = dict(tokens=None, hidden_in=torch.randn((B, S, cfg.d_model), device="cuda"),
+                      logits_mode=PB.PT_LOGITS_NONE)
+            head_rows = 0
+        total, _ = prefill_flops(cfg, B, S, head_rows)
+        tokens = kw.pop("tokens")
+        run = lambda: model.pt_prefill(tokens, **kw)
+        run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(2):
+            run()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / 2
+        model.pt_profile_reset()
+        model.pt_profile_enable(classes)
+        run()
+        rec = {"workload": name, "kind": "prefill", "batch": B, "seq_len": S, "ms": dt * 1e3,
+               "tokens_per_s": B * S / dt, "TFLOP/s": total / dt / 1e12,
+               "frac_of_mfma_peak": total / dt / 1e12 / MFMA_BF16_PEAK_TFLOPS, "kernel_ms": breakdown(model, 1)}
+        log("%s: %.1f ms, %.0f tokens/s, %.0f TFLOP/s (%.1f%% of peak)" % (
+            name, rec["ms"], rec["tokens_per_s"], rec["TFLOP/s"], 100 * rec["frac_of_mfma_peak"]))
+        out.append(rec)
+        model.close()
+        del model, kw, tokens
+        torch.cuda.empty_cache()
+
+    def decode_case(name, cfg, B, ctx, seed):
+        model = PB.PTModel(cfg)
+        model.pt_init_weights(seed)
+        if cfg.vocab:
+            tokens = torch.from_numpy(I.make_tokens(seed, B, ctx, cfg.vocab)).cuda()
+            model.pt_prefill(tokens, logits_mode=PB.PT_LOGITS_NONE)
+            nxt = torch.zeros((B,), dtype=torch.int32, device="cuda")
+            logits = torch.empty((B, cfg.vocab), dtype=torch.float32, device="cuda")
+            step = lambda: model.pt_decode_step(nxt, logits_out=logits, argmax_out=nxt, want_argmax=True)
+            del tokens
+        else:
+            hid = torch.randn((B, ctx, cfg.d_model), device="cuda")
+            model.pt_prefill(hidden_in=hid, logits_mode=PB.PT_LOGITS_NONE)
+            del hid
+            x = torch.randn((B, cfg.d_model), device="cuda")
+            step = lambda: model.pt_decode_step(hidden_in=x, want_logits=False, want_hidden=True)
+        for _ in range(2):
+            step()
+        torch.cuda.synchronize()
+        n = 8
+        t0 = time.perf_counter()
+        for _ in range(n):
+            step()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / n
+        wb, kvstep, kvl = decode_bytes(cfg, B, ctx + 6)
+        model.pt_profile_reset()
+        model.pt_profile_enable(classes)
+        step()
+        br = breakdown(model, 1)
+        ms_attn, n_attn = model.pt_profile_read("attn_decode")
+        rec = {"workload": name, "kind": "decode", "batch": B, "context": ctx, "ms_per_step": dt * 1e3,
+               "step_bytes_GB": (wb + kvstep) / 1e9, "step_GBs": (wb + kvstep) / dt / 1e9,
+               "frac_of_hbm_peak": (wb + kvstep) / dt / 1e9 / HBM_PEAK_GBS,
+               "attention_GBs": kvl / (ms_attn / n_attn * 1e-3) / 1e9, "kernel_ms": br}
+        log("%s: %.2f ms/step, %.0f GB/s (%.1f%% of peak), attention %.0f GB/s" % (
+            name, rec["ms_per_step"], rec["step_GBs"], 100 * rec["frac_of_hbm_peak"], rec["attention_GBs"]))
+        out.append(rec)
+        model.close()
+        del model
+        torch.cuda.empty_cache()
+
+    which = args.large_configs.split(",")
+    if "large-prefill" in which:
+        prefill_case("Large PT prefill 8 x 4096", I.config_large(max_batch=8, max_seq=4096), 8, 4096, 3)
+    if "share-prefill" in which:
+        prefill_case("one-GPU share prefill 2 x 4096", I.config_share(max_batch=2, max_seq=4096), 2, 4096, 4)
+    if "large-decode-gqa" in which:
+        decode_case("Large PT decode, 2 KV heads per track, batch 64, context 4096",
+                    I.config_large(max_batch=64, max_seq=4096 + 64, n_kv_heads=2), 64, 4096, 3)
+    if "large-decode-mha" in which:
+        decode_case("Large PT decode, MHA, batch 16, context 4096",
+                    I.config_large(max_batch=16, max_seq=4096 + 64), 16, 4096, 3)
+    if "share-decode" in which:
+        decode_case("one-GPU share decode, batch 64, context 8192",
+                    I.config_share(max_batch=64, max_seq=8192 + 64), 64, 8192, 4)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -247,6 +358,9 @@ def main():
     ap.add_argument("--paper-sweep", action="store_true",
                     help="instead of the benchmark: TTFT / TPOT at batch 1 over input lengths for the "
                          "30B-shaped PT model at track block depth 2, 4, 8 (one JSON line)")
+    ap.add_argument("--large-configs", default="",
+                    help="instead of the benchmark: comma list of large-prefill, share-prefill, large-decode-gqa, "
+                         "large-decode-mha, share-decode (one JSON line)")
     ap.add_argument("--sweep-lengths", default="1024,4096,16384,63488")
     ap.add_argument("--sweep-depths", default="0,1,2,4,8",
                     help="track block depths of the sweep; 0 = the dense model of matched parameter count")
@@ -270,6 +384,10 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    if args.large_configs:
+        print(json.dumps({"large_configs": run_large_configs(args, torch, PB, I), "n_gpus": 1, "dtype": "bf16",
+                          "data": "synthetic"}), flush=True)
+        return
     if args.paper_sweep:
         print(json.dumps({"paper_sweep": run_paper_sweep(args, torch, PB, I), "n_gpus": 1, "dtype": "bf16",
                           "data": "synthetic",
