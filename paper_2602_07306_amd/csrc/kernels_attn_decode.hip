@@ -209,7 +209,8 @@ typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 // Tiles of 128 keys: K [128 x hd] (one contiguous piece of the cache) and V^T [hd x 128] are read by the whole
 // workgroup as 16-byte pieces of whole cache lines, held in registers while the previous tile is multiplied,
-// and parked in one of two LDS buffers (16-byte chunk c of row r at position c ^ swizzle(r)); wavefront w then
+// and parked in LDS (two buffers for hd = 128; one for hd = 64, where a third resident workgroup covers the
+// extra barrier; 16-byte chunk c of row r sits at position c ^ swizzle(r)); wavefront w then
 // works on keys 32w .. 32w+31 of the tile with fragments read from LDS.
 template <int HD>
 __global__ void __launch_bounds__(256) attn_decode_tiled_kernel(const pt_attn_args a, int nsplit, int keys_per_split) {
@@ -218,6 +219,7 @@ __global__ void __launch_bounds__(256) attn_decode_tiled_kernel(const pt_attn_ar
   constexpr int KCH = KROW / 16;                // 16-byte chunks per key row
   constexpr int TILE = 128 * KROW;              // bytes of the K tile = bytes of the V^T tile (hd rows x 256 B)
   constexpr int NLD = TILE / 16 / 256;          // 16-byte pieces per thread and operand
+  constexpr int NBUF = HD == 64 ? 1 : 2;        // LDS buffers: one (and three workgroups per CU) or two
   extern __shared__ __attribute__((aligned(1024))) char smem[];   // 2 buffers x (K tile + V^T tile)
   float (*red_o)[HD][DEC_GMAX] = (float (*)[HD][DEC_GMAX])smem;   // reuses the tiles after the key loop
   __shared__ float red_m[4][32], red_l[4][32];
@@ -299,7 +301,7 @@ __global__ void __launch_bounds__(256) attn_decode_tiled_kernel(const pt_attn_ar
   park_tile(0, k0);
   __syncthreads();
   int buf = 0;
-  for (int kb = k0; kb < k1; kb += 128, buf ^= 1) {
+  for (int kb = k0; kb < k1; kb += 128, buf ^= (NBUF - 1)) {
     const bool more = kb + 128 < k1;
     if (more) load_tile(kb + 128);
     const char* kt = smem + buf * (2 * TILE);
@@ -355,7 +357,8 @@ __global__ void __launch_bounds__(256) attn_decode_tiled_kernel(const pt_attn_ar
           oacc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u].v, oacc[hb], 0, 0, 0);
         }
     }
-    if (more) park_tile(buf ^ 1, kb + 128);     // last read while tile kb - 128 was multiplied
+    if (NBUF == 1) __syncthreads();             // one buffer: everybody is done with the tile before it is replaced
+    if (more) park_tile(buf ^ (NBUF - 1), kb + 128);   // two buffers: last read while tile kb - 128 was multiplied
     __syncthreads();
   }
   // the two half-waves of a query head hold disjoint key subsets with a common running max
@@ -392,7 +395,7 @@ __global__ void __launch_bounds__(256) attn_decode_tiled_kernel(const pt_attn_ar
 
 template <int HD>
 static int launch_gqa(const pt_attn_args& a, dim3 grid, int nsplit, int kps, hipStream_t s) {
-  constexpr int LDS = 2 * 2 * 128 * HD * 2;
+  constexpr int LDS = (HD == 64 ? 1 : 2) * 2 * 128 * HD * 2;
   static_assert(LDS >= 4 * HD * DEC_GMAX * 4, "merge buffer must fit the tiles");
   auto kern = attn_decode_tiled_kernel<HD>;
   static bool configured = false;
