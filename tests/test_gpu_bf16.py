@@ -77,6 +77,10 @@ CASES = {
                                     head_dim=64, d_ffn=1536, max_batch=5, max_seq=128, merge_scale=1.0 / 3), 5, 70, 3),
     "decode_33_rows": (dict(n_layers=2, block_depth=2, d_model=512, n_heads=8, n_kv_heads=8, head_dim=64,
                             d_ffn=1024, max_batch=33, max_seq=64), 33, 8, 2),
+    # long prompts: many key tiles per query block in prefill, split decode over a long cache
+    "long_prompt_hd64": (dict(max_batch=1, max_seq=2112), 1, 2048, 2),
+    "long_prompt_hd128_gqa": (dict(head_dim=128, n_heads=4, n_kv_heads=2, d_model=512, n_layers=2, block_depth=2,
+                                   max_batch=1, max_seq=1600), 1, 1536, 2),
     # matrix-vector decode kernel: two and three rows
     "gemv_2_rows": (dict(n_tracks=4, n_layers=2, block_depth=2, d_model=512, n_heads=8, n_kv_heads=2, head_dim=64,
                          d_ffn=1024, max_batch=2, max_seq=128), 2, 40, 3),
