@@ -121,8 +121,10 @@ int pt_prefill(pt_handle* h, const int32_t* dev_tokens, const float* dev_hidden_
 /* One KV-cached decode step: one new row per sequence at position len, appended to the cache.
  *   dev_tokens int32 [B] or dev_hidden_in fp32 [hidden_tracks, B, d]; B must equal the B of the
  *   preceding prefill.  dev_logits fp32 [B, V], dev_hidden_out fp32 [B, d], dev_argmax int32 [B]
- *   (lowest id on ties); each may be NULL.
- * Errors as pt_prefill; CAPACITY when len + 1 > max_seq; BAD_STATE before a prefill. */
+ *   (lowest id on ties); dev_logits and dev_hidden_out may each be NULL; dev_argmax may be NULL
+ *   and, when given, needs dev_logits as well (the ids are taken from the stored logits).
+ * Errors as pt_prefill; CAPACITY when len + 1 > max_seq; BAD_STATE before a prefill;
+ * NULL_POINTER for dev_argmax without dev_logits. */
 int pt_decode_step(pt_handle* h, const int32_t* dev_tokens, const float* dev_hidden_in,
                    int32_t hidden_tracks, int32_t B, float* dev_logits, float* dev_hidden_out,
                    int32_t* dev_argmax);
@@ -134,6 +136,12 @@ int pt_decode_step(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
  *   tracks[0].  n <= 16.  d must be a multiple of 8.  Enqueued on hip_stream. */
 int pt_track_merge(const void* const* host_tracks, int32_t n, int64_t tokens, int32_t d,
                    int32_t dtype, float scale, void* dev_out, void* hip_stream);
+
+/* Greedy token choice, stateless: dev_out[r] = index of the largest of dev_logits[r, 0..vocab), the
+ * lowest index on exact ties (the rule both sides of the parity tests use); fp32 logits [rows, vocab]
+ * row-major, int32 out [rows].  The same kernel serves dev_argmax of pt_decode_step.  Enqueued on
+ * hip_stream.  Errors: NULL_POINTER, INVALID_ARGUMENT (rows < 0 or vocab < 1). */
+int pt_argmax(const float* dev_logits, int32_t rows, int32_t vocab, int32_t* dev_out, void* hip_stream);
 
 /* Optional observation point: when set (non-NULL), every merge inside pt_prefill /
  * pt_decode_step also stores the merged activation to dev_taps, fp32
@@ -147,6 +155,13 @@ int pt_set_taps(pt_handle* h, float* dev_taps, float* dev_track_taps);
  * kernels everywhere (slow; used to cross-check the tuned kernels). */
 enum { PT_PATH_AUTO = 0, PT_PATH_GENERIC = 1 };
 int pt_set_kernel_path(pt_handle* h, int32_t path);
+
+/* Token ids outside [0, vocab) are not an error the asynchronous forward calls can return: the
+ * embedding kernel reads row 0 (negative ids) or row vocab-1 instead and raises a flag in device
+ * memory.  pt_sync_status synchronises the handle's stream, reads and clears that flag and returns
+ * PT_ERR_INVALID_ARGUMENT if any forward call since the previous pt_sync_status (or pt_create) met
+ * such an id; the logits of those calls are then meaningless.  PT_OK otherwise. */
+int pt_sync_status(pt_handle* h);
 
 /* Forgets all sequences (lengths = 0); the KV cache contents become dead. */
 int pt_reset(pt_handle* h);
@@ -172,6 +187,29 @@ int pt_profile_enable(pt_handle* h, uint32_t class_mask);
  * pt_profile_reset.  Either out pointer may be NULL. */
 int pt_profile_read(pt_handle* h, int32_t kernel_class, double* total_ms, int64_t* launches);
 int pt_profile_reset(pt_handle* h);
+
+/* Which kernel family served the launches of a class (counted on the host at every launch of a
+ * GEMM or attention class, whether or not timing is on; zeroed by pt_profile_reset).  Family 0 is
+ * the shape-generic kernel that takes whatever the tuned ones refuse, so a test can tell a tuned
+ * launch from a silent fall-back:
+ *   GEMM classes       1 = MFMA tile kernel (more than 64 rows), 2 = weight-streaming kernel
+ *                      (5..64 rows), 3 = matrix-vector kernel (1..4 rows)
+ *   PT_K_ATTN_PREFILL  1 = flash-style kernel with LDS key/value tiles, 2 = its register-operand
+ *                      form (lengths that are a multiple of 32 but not of 64)
+ *   PT_K_ATTN_DECODE   1 = matrix-core split-K kernel (up to 32 query heads per KV head),
+ *                      2 = vector split-K kernel (larger groups)
+ * counts receives PT_FAMILY_COUNT values. */
+enum { PT_FAMILY_GENERIC = 0, PT_FAMILY_COUNT = 4 };
+int pt_profile_paths(pt_handle* h, int32_t kernel_class, int64_t* counts);
+
+/* Process-wide tuning overrides for benchmark sweeps; the defaults select by shape.
+ *   PT_TUNE_GEMM_TILE_CONFIG   value -1 (default): automatic; 0..11: force that tile configuration
+ *                              of the MFMA GEMM wherever it fits the shape
+ *   PT_TUNE_SKINNY_PLAN        value 0 (default): automatic; else 256 * workgroups per track +
+ *                              K slices for the weight-streaming GEMM (where the shape allows)
+ * Not thread-safe against concurrent forward calls.  Errors: INVALID_ARGUMENT (unknown knob). */
+enum { PT_TUNE_GEMM_TILE_CONFIG = 0, PT_TUNE_SKINNY_PLAN = 1 };
+int pt_set_tuning(int32_t knob, int32_t value);
 
 const char* pt_last_error(void);
 

@@ -47,6 +47,11 @@ import numpy as np
 F64 = np.float64
 
 
+def _f64(w: np.ndarray) -> np.ndarray:
+    """The array as float64 (the same values; no copy when the caller already holds float64)."""
+    return np.asarray(w, dtype=F64)
+
+
 def rmsnorm(h: np.ndarray, g: np.ndarray, eps: float) -> np.ndarray:
     """a = h * g / sqrt(mean_d(h^2) + eps) over the last axis."""
     h = np.asarray(h, dtype=F64)
@@ -130,20 +135,20 @@ def _layer(cfg, W: Dict[str, np.ndarray], i: int, l: int, h: np.ndarray, pos: np
     H, Hkv, hd = cfg.n_heads, cfg.n_kv_heads, cfg.head_dim
     S = h.shape[0]
     a = rmsnorm(h, W["g1"][i, l], cfg.rms_eps)
-    q = (a @ W["wq"][i, l].astype(F64)).reshape(S, H, hd)
-    k = (a @ W["wk"][i, l].astype(F64)).reshape(S, Hkv, hd)
-    v = (a @ W["wv"][i, l].astype(F64)).reshape(S, Hkv, hd)
+    q = (a @ _f64(W["wq"][i, l])).reshape(S, H, hd)
+    k = (a @ _f64(W["wk"][i, l])).reshape(S, Hkv, hd)
+    v = (a @ _f64(W["wv"][i, l])).reshape(S, Hkv, hd)
     q = rope(q, pos, cfg.rope_theta)
     k = rope(k, pos, cfg.rope_theta)
     state.k[i, l, b, pos] = k
     state.v[i, l, b, pos] = v
     ctx = int(pos[-1]) + 1
     o = causal_attention(q, state.k[i, l, b, :ctx], state.v[i, l, b, :ctx], pos)
-    h = h + o.reshape(S, H * hd) @ W["wo"][i, l].astype(F64)
+    h = h + o.reshape(S, H * hd) @ _f64(W["wo"][i, l])
     a2 = rmsnorm(h, W["g2"][i, l], cfg.rms_eps)
-    gate = a2 @ W["wg"][i, l].astype(F64)
-    up = a2 @ W["wu"][i, l].astype(F64)
-    h = h + (silu(gate) * up) @ W["wd"][i, l].astype(F64)
+    gate = a2 @ _f64(W["wg"][i, l])
+    up = a2 @ _f64(W["wu"][i, l])
+    h = h + (silu(gate) * up) @ _f64(W["wd"][i, l])
     return h
 
 
@@ -168,7 +173,7 @@ def _run_rows(cfg, W, state: PTState, x_tracks: List[np.ndarray], b: int, pos: n
 
 def logits_from_hidden(cfg, W, h: np.ndarray) -> np.ndarray:
     """Final RMSNorm and the (untied) output head on merged hidden rows [.., d]."""
-    return rmsnorm(h, W["gf"], cfg.rms_eps) @ W["head"].astype(F64)
+    return rmsnorm(h, W["gf"], cfg.rms_eps) @ _f64(W["head"])
 
 
 def pt_prefill(cfg, W, state: PTState, tokens: Optional[np.ndarray] = None,
@@ -193,7 +198,7 @@ def pt_prefill(cfg, W, state: PTState, tokens: Optional[np.ndarray] = None,
     pos = np.arange(S)
     for b in range(B):
         if tokens is not None:
-            x = W["embed"][tokens[b]].astype(F64)
+            x = _f64(W["embed"][tokens[b]])
             xs = [x] * T
         elif hidden_in.ndim == 3:
             xs = [hidden_in[b]] * T
@@ -227,7 +232,7 @@ def pt_decode_step(cfg, W, state: PTState, tokens: Optional[np.ndarray] = None,
     for b in range(B):
         pos = np.array([state.length[b]])
         if tokens is not None:
-            x = W["embed"][np.asarray(tokens)[b]].astype(F64)[None, :]
+            x = _f64(W["embed"][np.asarray(tokens)[b]])[None, :]
             xs = [x] * T
         else:
             hin = np.asarray(hidden_in, dtype=F64)

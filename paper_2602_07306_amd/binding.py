@@ -17,6 +17,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpt.so")
 
 PT_LOGITS_NONE, PT_LOGITS_LAST, PT_LOGITS_ALL = 0, 1, 2
+PT_FAMILY_GENERIC, PT_FAMILY_COUNT = 0, 4
+PT_TUNE_GEMM_TILE_CONFIG, PT_TUNE_SKINNY_PLAN = 0, 1
 PT_PATH_AUTO, PT_PATH_GENERIC = 0, 1
 PT_W_EMBED, PT_W_HEAD, PT_W_Q, PT_W_K, PT_W_V, PT_W_O, PT_W_G, PT_W_U, PT_W_D, PT_W_G1, PT_W_G2, PT_W_GF = range(1, 13)
 WEIGHT_IDS = {"embed": PT_W_EMBED, "head": PT_W_HEAD, "wq": PT_W_Q, "wk": PT_W_K, "wv": PT_W_V,
@@ -31,7 +33,7 @@ EXPORTS = [
     "pt_query_bytes", "pt_create", "pt_destroy", "pt_init_weights", "pt_set_weight", "pt_get_weight",
     "pt_prefill", "pt_decode_step", "pt_track_merge", "pt_set_taps", "pt_set_kernel_path", "pt_reset",
     "pt_merge_count", "pt_seq_len", "pt_last_error", "pt_profile_enable", "pt_profile_read",
-    "pt_profile_reset",
+    "pt_profile_reset", "pt_profile_paths", "pt_sync_status", "pt_set_tuning", "pt_argmax",
 ]
 
 KERNEL_CLASSES = ["embed", "rmsnorm", "gemm_qkv", "attn_prefill", "attn_decode", "gemm_out",
@@ -84,6 +86,10 @@ def lib() -> C.CDLL:
     L.pt_profile_enable.argtypes = [vp, C.c_uint32]
     L.pt_profile_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(i64)]
     L.pt_profile_reset.argtypes = [vp]
+    L.pt_profile_paths.argtypes = [vp, i32, C.POINTER(i64)]
+    L.pt_sync_status.argtypes = [vp]
+    L.pt_set_tuning.argtypes = [i32, i32]
+    L.pt_argmax.argtypes = [vp, i32, i32, vp, vp]
     L.pt_last_error.argtypes = []
     L.pt_last_error.restype = C.c_char_p
     for name in EXPORTS:
@@ -106,6 +112,10 @@ def to_c_config(cfg: PTConfig) -> pt_config:
 
 def pt_last_error() -> str:
     return lib().pt_last_error().decode()
+
+
+def pt_set_tuning(knob: int, value: int) -> None:
+    _check(lib().pt_set_tuning(knob, value))
 
 
 def pt_query_bytes(cfg: PTConfig):
@@ -133,6 +143,17 @@ def pt_track_merge(tracks, scale: float, out=None, stream=None):
     st = torch.cuda.current_stream().cuda_stream if stream is None else stream
     tokens, d = (t0.shape[0], t0.shape[1]) if t0.dim() == 2 else (t0.numel() // t0.shape[-1], t0.shape[-1])
     _check(lib().pt_track_merge(arr, len(tracks), tokens, d, dtype, float(scale), out.data_ptr(), st))
+    return out
+
+
+def pt_argmax(logits, out=None, stream=None):
+    """out[r] = argmax of logits[r, :] (float32 device tensor [rows, vocab]), lowest id on ties."""
+    import torch
+    assert logits.dtype == torch.float32 and logits.is_contiguous() and logits.dim() == 2
+    if out is None:
+        out = torch.empty((logits.shape[0],), dtype=torch.int32, device=logits.device)
+    st = torch.cuda.current_stream().cuda_stream if stream is None else getattr(stream, "cuda_stream", stream)
+    _check(lib().pt_argmax(logits.data_ptr(), logits.shape[0], logits.shape[1], out.data_ptr(), st))
     return out
 
 
@@ -234,7 +255,7 @@ class PTModel:
 
     def pt_decode_step(self, tokens=None, hidden_in=None, want_logits: bool = True,
                        want_hidden: bool = False, want_argmax: bool = False, logits_out=None,
-                       argmax_out=None):
+                       argmax_out=None, hidden_out=None):
         cfg, torch = self.cfg, self.torch
         if tokens is not None:
             B, ht = tokens.shape[0], 1
@@ -244,7 +265,9 @@ class PTModel:
         logits = logits_out
         if logits is None and (want_logits or want_argmax) and cfg.vocab > 0:
             logits = torch.empty((B, cfg.vocab), dtype=torch.float32, device=self.device)
-        hidden = torch.empty((B, cfg.d_model), dtype=torch.float32, device=self.device) if want_hidden else None
+        hidden = hidden_out
+        if hidden is None and want_hidden:
+            hidden = torch.empty((B, cfg.d_model), dtype=torch.float32, device=self.device)
         amax = argmax_out
         if amax is None and want_argmax:
             amax = torch.empty((B,), dtype=torch.int32, device=self.device)
@@ -267,6 +290,17 @@ class PTModel:
 
     def pt_profile_reset(self):
         _check(lib().pt_profile_reset(self.h))
+
+    def pt_profile_paths(self, cls: str):
+        """Launches of one kernel class per kernel family since the last pt_profile_reset
+        (index 0: the shape-generic kernel; see include/pt.h)."""
+        counts = (C.c_int64 * PT_FAMILY_COUNT)()
+        _check(lib().pt_profile_paths(self.h, KERNEL_CLASSES.index(cls), counts))
+        return list(counts)
+
+    def pt_sync_status(self):
+        """Synchronises the stream; raises PTError if a forward call met an out-of-range token id."""
+        _check(lib().pt_sync_status(self.h))
 
     def pt_reset(self):
         _check(lib().pt_reset(self.h))

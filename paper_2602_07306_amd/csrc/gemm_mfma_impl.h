@@ -40,13 +40,6 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
-#ifdef GM_TIMING   // tuning builds only: per-phase clock stamps of workgroup 0
-__device__ long long gm_stamps[64];
-#define GM_STAMP(i) do { if (blockIdx.x == 0 && threadIdx.x == 0 && (i) < 64) gm_stamps[i] = wall_clock64(); } while (0)
-#else
-#define GM_STAMP(i) do { } while (0)
-#endif
-
 struct tile_coord {
   int b, tm, tn;
 };
@@ -400,8 +393,6 @@ gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16_t* As = (bf16_t*)smem;            // [2][BM][BK]
   bf16_t* Bs = As + 2 * BM * BK;      // [2][BN][BK]
-
-  GM_STAMP(0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
   const tile_coord tc = decode_tile(logical_tile(blockIdx.x, gridDim.x), tiles_m, tiles_n);
@@ -468,8 +459,6 @@ gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
 #pragma unroll
   for (int i = 0; i < B_CH; ++i) load_w(0, i, min(2, KT - 1));
   __syncthreads();
-
-  GM_STAMP(1);
   bf16x8_t af[2][MI], bfr[2][NI];
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi) af[0][mi] = *(const bf16x8_t*)(As + a_fr[0] + mi * 32 * BK);
@@ -539,7 +528,6 @@ gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
     iteration(std::integral_constant<int, 1>{}, kt + 1);
   }
   __syncthreads();   // LDS is free for the staged epilogues
-  GM_STAMP(2);
 
   // ------------------------------------------------------------------ epilogue
   // LDS patch of this wavefront for the staged epilogues (the K loop is over: all of LDS is free)
@@ -551,7 +539,6 @@ gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
   const int wave_m = m0 + wm * TM;
 
   gemm_epilogue<MI, NI, EPI, STAGED, STAGE_ELEMS>(g, acc, stage, b, wave_m, wave_n, lane);
-  GM_STAMP(3);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -692,11 +679,7 @@ static int launch_dl(const pt_gemm_args& g, hipStream_t s) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   const size_t lds = (size_t)4 * (BM + BN) * 32 * sizeof(bf16_t);
   auto kern = gemm_dl_kernel<BM, BN, WM, WN, EPI>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    PT_HIP_CHECK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    attr_set = true;
-  }
+  PT_SET_MAX_LDS_ONCE(kern, lds);
   const int64_t total = (int64_t)tiles_m * tiles_n * g.batch;
   if (total > 0x7fffffff) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "GEMM grid too large");
   hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(WM * WN * 64), lds, s, g, tiles_m, tiles_n);
@@ -709,11 +692,7 @@ static int launch_cfg(const pt_gemm_args& g, hipStream_t s) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   const size_t lds = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t);
   auto kern = gemm_mfma_kernel<BM, BN, WM, WN, BK, EPI>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    PT_HIP_CHECK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    attr_set = true;
-  }
+  PT_SET_MAX_LDS_ONCE(kern, lds);
   const int64_t total = (int64_t)tiles_m * tiles_n * g.batch;
   if (total > 0x7fffffff) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "GEMM grid too large");
   const unsigned grid = (unsigned)total;

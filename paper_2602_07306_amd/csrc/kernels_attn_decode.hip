@@ -398,11 +398,7 @@ static int launch_gqa(const pt_attn_args& a, dim3 grid, int nsplit, int kps, hip
   constexpr int LDS = (HD == 64 ? 1 : 2) * 2 * 128 * HD * 2;
   static_assert(LDS >= 4 * HD * DEC_GMAX * 4, "merge buffer must fit the tiles");
   auto kern = attn_decode_tiled_kernel<HD>;
-  static bool configured = false;
-  if (!configured) {
-    PT_HIP_CHECK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS));
-    configured = true;
-  }
+  PT_SET_MAX_LDS_ONCE(kern, LDS);
   hipLaunchKernelGGL(kern, grid, dim3(256), LDS, s, a, nsplit, kps);
   return PT_OK;
 }
@@ -453,5 +449,5 @@ int pt_launch_attn_decode(const pt_attn_args& a, hipStream_t s) {
   if (nsplit > 1)
     hipLaunchKernelGGL(attn_decode_combine_kernel, dim3((unsigned)a.H, (unsigned)z), dim3(64), 0, s, a, nsplit);
   PT_HIP_CHECK(hipGetLastError());
-  return 1;
+  return 2;
 }

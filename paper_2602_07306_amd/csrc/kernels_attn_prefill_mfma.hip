@@ -350,11 +350,7 @@ static int launch_lds(const pt_attn_args& a, hipStream_t s) {
   const dim3 grid((unsigned)total);
   const size_t lds = (size_t)2 * (64 * HD + HD * 64) * sizeof(bf16_t);
   auto kern = attn_prefill_lds_kernel<HD>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    PT_HIP_CHECK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    attr_set = true;
-  }
+  PT_SET_MAX_LDS_ONCE(kern, lds);
   hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, a, nqb);
   PT_HIP_CHECK(hipGetLastError());
   return 1;
@@ -374,5 +370,5 @@ int pt_launch_attn_prefill_mfma(const pt_attn_args& a, hipStream_t s) {
   else
     hipLaunchKernelGGL(attn_prefill_mfma_kernel<128>, grid, dim3(256), 0, s, a);
   PT_HIP_CHECK(hipGetLastError());
-  return 1;
+  return 2;
 }

@@ -3,27 +3,32 @@
 #include "pt_device.h"
 
 // ------------------------------------------------------------------------------------------
-// Embedding: h[row, :] = E[token[row], :] as fp32.  Out-of-range ids are clamped into the table.
+// Embedding: h[row, :] = E[token[row], :] as fp32.  An id outside [0, vocab) reads the nearest table row (so
+// that no access leaves the table) and sets bit 0 of the device status word, which pt_sync_status reports.
 // ------------------------------------------------------------------------------------------
 template <typename T>
 __global__ void __launch_bounds__(256) embed_kernel(const T* __restrict__ E, const int32_t* __restrict__ tok,
-                                                    int64_t rows, int32_t d, int32_t vocab, float* __restrict__ h) {
+                                                    int64_t rows, int32_t d, int32_t vocab, float* __restrict__ h,
+                                                    int32_t* __restrict__ flag) {
   const int64_t row = blockIdx.x;
   if (row >= rows) return;
   int32_t id = tok[row];
-  id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
+  if (id < 0 || id >= vocab) {
+    if (threadIdx.x == 0 && flag) atomicOr(flag, 1);
+    id = id < 0 ? 0 : vocab - 1;
+  }
   const T* src = E + (int64_t)id * d;
   float* dst = h + row * d;
   for (int c = threadIdx.x; c < d; c += 256) dst[c] = elem<T>::ld(src + c);
 }
 
 int pt_launch_embed(const void* embed, int32_t dtype, const int32_t* tokens, int64_t rows, int32_t d,
-                    int32_t vocab, float* h, hipStream_t s) {
+                    int32_t vocab, float* h, int32_t* flag, hipStream_t s) {
   if (rows <= 0) return PT_OK;
   if (dtype == PT_F32)
-    hipLaunchKernelGGL(embed_kernel<float>, dim3((unsigned)rows), dim3(256), 0, s, (const float*)embed, tokens, rows, d, vocab, h);
+    hipLaunchKernelGGL(embed_kernel<float>, dim3((unsigned)rows), dim3(256), 0, s, (const float*)embed, tokens, rows, d, vocab, h, flag);
   else
-    hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3((unsigned)rows), dim3(256), 0, s, (const bf16_t*)embed, tokens, rows, d, vocab, h);
+    hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3((unsigned)rows), dim3(256), 0, s, (const bf16_t*)embed, tokens, rows, d, vocab, h, flag);
   PT_HIP_CHECK(hipGetLastError());
   return PT_OK;
 }

@@ -25,8 +25,8 @@ static int launch_epi(const pt_gemm_args& g, hipStream_t s, int cfg) {
 
 #define GM_BK 64
 
-// Tile configuration override for tuning runs: -1 = choose by shape.
-int pt_gemm_mfma_force_cfg = -1;
+// Tile configuration override for tuning runs (pt_set_tuning): -1 = choose by shape.
+int pt_tune_gemm_cfg = -1;
 
 #define GM_NCFG 12
 static const int kWaveN[GM_NCFG] = {128, 64, 64, 64, 128, 64, 128, 128, 128, 64, 128, 128};   // columns per wavefront
@@ -59,8 +59,8 @@ int pt_launch_gemm_mfma(const pt_gemm_args& g, hipStream_t s) {
   else if (g.M <= 128 || (int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256) * g.batch < 200) cand = mid;
   else cand = g.epi == EPI_QKV ? big_qkv : (g.epi == EPI_SWIGLU && g.K <= 1024) ? big_dl : big;
   int cfg = -1;
-  if (pt_gemm_mfma_force_cfg >= 0 && pt_gemm_mfma_force_cfg < GM_NCFG) {
-    if (cfg_fits(g, pt_gemm_mfma_force_cfg)) cfg = pt_gemm_mfma_force_cfg;
+  if (pt_tune_gemm_cfg >= 0 && pt_tune_gemm_cfg < GM_NCFG) {
+    if (cfg_fits(g, pt_tune_gemm_cfg)) cfg = pt_tune_gemm_cfg;
   } else {
     for (; *cand >= 0; ++cand)
       if (cfg_fits(g, *cand)) { cfg = *cand; break; }

@@ -430,17 +430,13 @@ template <int MR, int EPI>
 static int launch_gemv(const pt_gemm_args& g, int tiles, hipStream_t s) {
   const int lds = MR * g.K * 2;
   auto kern = gemm_gemv_kernel<MR, EPI>;
-  static bool configured = false;
-  if (!configured) {
-    PT_HIP_CHECK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 48 * 1024));
-    configured = true;
-  }
+  PT_SET_MAX_LDS_ONCE(kern, 48 * 1024);
   // about a thousand workgroups (three to four resident per compute unit), every one with the same number of tiles
   const int tpw = (int)(((int64_t)tiles * g.batch + 1023) / 1024);
   const int wpt = (tiles + tpw - 1) / tpw;
   hipLaunchKernelGGL(kern, dim3((unsigned)((int64_t)wpt * g.batch)), dim3(256), lds, s, g, tiles, wpt);
   PT_HIP_CHECK(hipGetLastError());
-  return 1;
+  return 3;
 }
 
 template <int EPI>
@@ -475,8 +471,9 @@ __global__ void __launch_bounds__(256) gemm_skinny_kernel(const pt_gemm_args g, 
   }
 }
 
-// Tuning knob for benchmarks: 0 = automatic, else 256 * workgroups per track + K slices (where the shape allows).
-int pt_gemm_skinny_force = 0;
+// Tuning knob for benchmarks (pt_set_tuning): 0 = automatic, else 256 * workgroups per track + K slices
+// (where the shape allows).
+int pt_tune_skinny_plan = 0;
 
 struct sk_plan { int wpt, ks; };
 
@@ -486,14 +483,10 @@ static int launch_skinny_rb(const pt_gemm_args& g, int tiles, sk_plan p, hipStre
   constexpr int RING = 4 * (MI + RBHI) * 32 * 128, RED = 4 * MI * 16 * 64 * 4;
   constexpr int LDS = RING > RED ? RING : RED;
   auto kern = gemm_skinny_kernel<MI, RBHI, EPI>;
-  static bool configured = false;
-  if (!configured) {
-    PT_HIP_CHECK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS));
-    configured = true;
-  }
+  PT_SET_MAX_LDS_ONCE(kern, LDS);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), LDS, s, g, p.wpt, tiles % p.wpt, p.ks);
   PT_HIP_CHECK(hipGetLastError());
-  return 1;
+  return 2;
 }
 
 static int device_cus() {
@@ -541,8 +534,8 @@ static sk_plan plan_skinny(const pt_gemm_args& g, int tiles, int ks_max) {
       if (cost < best_cost * 0.999) { best_cost = cost; best.wpt = wpt; best.ks = ks; }
     }
   }
-  if (pt_gemm_skinny_force > 0) {
-    const int fw = pt_gemm_skinny_force >> 8, fks = pt_gemm_skinny_force & 255;
+  if (pt_tune_skinny_plan > 0) {
+    const int fw = pt_tune_skinny_plan >> 8, fks = pt_tune_skinny_plan & 255;
     if (fw >= (tiles + 3) / 4 && fw <= tiles) best.wpt = fw;
     best.ks = 1;
     if (fks > 1 && fks <= ks_max && g.K % (fks * 4 * 128) == 0 && (int64_t)fks * g.batch * g.M * g.N <= (int64_t)PT_SK_PART_FLOATS)
@@ -581,7 +574,7 @@ static bool skinny_covers(const pt_gemm_args& g) {
 // slices itself (0: the kernel does not cover the shape; 1: no split).
 // one to four rows: matrix-vector kernel, if A fits its LDS budget and the grid is at least half a round
 static bool use_gemv(const pt_gemm_args& g) {
-  return g.M <= 4 && pt_gemm_skinny_force == 0 && g.K % 512 == 0 &&
+  return g.M <= 4 && pt_tune_skinny_plan == 0 && g.K % 512 == 0 &&
          (int64_t)(g.M == 3 ? 4 : g.M) * g.K * 2 <= 48 * 1024 && (int64_t)(g.N / 32) * g.batch >= 128;
 }
 
@@ -595,7 +588,7 @@ int pt_gemm_skinny_ksplit(const pt_gemm_args& g) {
   return plan_skinny(g, g.N / 32, 16).ks;
 }
 
-// Returns 1 if launched, 0 if the shape is not covered.  With allow_split the K slices chosen by
+// Returns the kernel family launched (2, or 3 for the matrix-vector form), 0 if the shape is not covered.  With allow_split the K slices chosen by
 // pt_gemm_skinny_ksplit are left in g.sk_part instead of the finished residual stream.
 int pt_launch_gemm_skinny(const pt_gemm_args& g, bool allow_split, hipStream_t s) {
   if (!skinny_covers(g)) return 0;

@@ -90,6 +90,7 @@ int pt_compute_layout(const pt_config* c, pt_layout* l) {
   l->off_part = off; off = align_up(off + (size_t)(T * B * c->n_heads * l->max_splits * (hd + 2) * 4), 256);
   l->off_last = off; off = align_up(off + (size_t)(B * d * es), 256);
   l->off_skp = off;  off = align_up(off + (size_t)PT_SK_PART_FLOATS * 4, 256);
+  l->off_flag = off; off = align_up(off + 4, 256);
   l->ws_bytes = off;
   return PT_OK;
 }
@@ -226,6 +227,12 @@ extern "C" int pt_track_merge(const void* const* host_tracks, int32_t n, int64_t
   return pt_launch_merge(host_tracks, n, tokens * d, dtype, scale, dev_out, nullptr, (hipStream_t)hip_stream);
 }
 
+extern "C" int pt_argmax(const float* dev_logits, int32_t rows, int32_t vocab, int32_t* dev_out, void* hip_stream) {
+  if (!dev_logits || !dev_out) return pt_set_error(PT_ERR_NULL_POINTER, "logits or out is NULL");
+  if (rows < 0 || vocab < 1) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "rows must be >= 0 and vocab >= 1");
+  return pt_launch_argmax(dev_logits, rows, vocab, dev_out, (hipStream_t)hip_stream);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Per-kernel timing: a pair of events around each launch of a selected class.
 // ---------------------------------------------------------------------------------------------
@@ -295,13 +302,54 @@ extern "C" int pt_profile_reset(pt_handle* h) {
   if (!h) return pt_set_error(PT_ERR_NULL_POINTER, "handle is NULL");
   int rc = prof_fold(h);
   if (rc) return rc;
-  for (int k = 0; k < PT_K_COUNT; ++k) { h->prof.ms[k] = 0; h->prof.launches[k] = 0; }
+  for (int k = 0; k < PT_K_COUNT; ++k) {
+    h->prof.ms[k] = 0;
+    h->prof.launches[k] = 0;
+    for (int f = 0; f < PT_FAMILY_COUNT; ++f) h->prof.family[k][f] = 0;
+  }
+  return PT_OK;
+}
+
+extern "C" int pt_profile_paths(pt_handle* h, int32_t kernel_class, int64_t* counts) {
+  if (!h || !counts) return pt_set_error(PT_ERR_NULL_POINTER, "handle or counts is NULL");
+  if (kernel_class < 0 || kernel_class >= PT_K_COUNT) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "unknown kernel class %d", kernel_class);
+  for (int f = 0; f < PT_FAMILY_COUNT; ++f) counts[f] = h->prof.family[kernel_class][f];
+  return PT_OK;
+}
+
+extern "C" int pt_set_tuning(int32_t knob, int32_t value) {
+  if (knob == PT_TUNE_GEMM_TILE_CONFIG) pt_tune_gemm_cfg = value;
+  else if (knob == PT_TUNE_SKINNY_PLAN) pt_tune_skinny_plan = value;
+  else return pt_set_error(PT_ERR_INVALID_ARGUMENT, "unknown tuning knob %d", knob);
+  return PT_OK;
+}
+
+extern "C" int pt_sync_status(pt_handle* h) {
+  if (!h) return pt_set_error(PT_ERR_NULL_POINTER, "handle is NULL");
+  if (!h->rope_ready) {   // no forward call yet: nothing can have raised the flag
+    PT_HIP_CHECK(hipStreamSynchronize(h->stream));
+    return PT_OK;
+  }
+  int32_t flag = 0;
+  int32_t* dev_flag = (int32_t*)(h->ws + h->lay.off_flag);
+  PT_HIP_CHECK(hipMemcpyAsync(&flag, dev_flag, sizeof(flag), hipMemcpyDeviceToHost, h->stream));
+  PT_HIP_CHECK(hipStreamSynchronize(h->stream));
+  if (flag) {
+    int rc = pt_launch_fill_f32((float*)dev_flag, 1, 0.0f, h->stream);   // all-zero bits
+    if (rc) return rc;
+    if (flag & 1) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "a token id outside [0, vocab) was given to a forward call");
+  }
   return PT_OK;
 }
 
 // ---------------------------------------------------------------------------------------------
 // The forward pass.  rows = B*S rows per track; row m is sequence m / S at position pos0 + m % S.
 // ---------------------------------------------------------------------------------------------
+// Records which kernel family served a launch of class cls (pt_profile_paths).
+static inline void count_family(pt_handle* h, int cls, int family) {
+  if (family >= 0 && family < PT_FAMILY_COUNT) h->prof.family[cls][family] += 1;
+}
+
 static int run_gemm(pt_handle* h, const pt_gemm_args& g_in, int cls) {
   prof_scope ps(h, cls);
   pt_gemm_args g = g_in;
@@ -309,12 +357,13 @@ static int run_gemm(pt_handle* h, const pt_gemm_args& g_in, int cls) {
   if (h->path == PT_PATH_AUTO) {
     int r = g.M <= 64 ? pt_launch_gemm_skinny(g, false, h->stream) : 0;
     if (r < 0) return r;
-    if (r == 1) return PT_OK;
+    if (r > 0) { count_family(h, cls, r); return PT_OK; }
     if (g.norm_src) return pt_set_error(PT_ERR_HIP, "a GEMM that was to form its own normalised operand was not taken by that kernel");
     r = pt_launch_gemm_mfma(g, h->stream);
     if (r < 0) return r;
-    if (r == 1) return PT_OK;
+    if (r > 0) { count_family(h, cls, r); return PT_OK; }
   }
+  count_family(h, cls, PT_FAMILY_GENERIC);
   return pt_launch_gemm_generic(g, h->stream);
 }
 
@@ -334,7 +383,8 @@ static int run_residual_gemm_norm(pt_handle* h, const pt_gemm_args& g_in, int cl
       prof_scope ps(h, cls);
       rc = pt_launch_gemm_skinny(g, true, h->stream);
       if (rc < 0) return rc;
-      if (rc != 1) return pt_set_error(PT_ERR_HIP, "decode GEMM refused a shape it had accepted");
+      if (rc == 0) return pt_set_error(PT_ERR_HIP, "decode GEMM refused a shape it had accepted");
+      count_family(h, cls, rc);
     }
     prof_scope ps(h, PT_K_RMSNORM);
     return pt_launch_resnorm(g.sk_part, slices, g.res, g.res_bstride, g.out, g.out_bstride, gain, gain_bstride,
@@ -348,12 +398,14 @@ static int run_residual_gemm_norm(pt_handle* h, const pt_gemm_args& g_in, int cl
 }
 
 static int run_attention(pt_handle* h, const pt_attn_args& a) {
-  prof_scope ps(h, a.S == 1 ? PT_K_ATTN_DECODE : PT_K_ATTN_PREFILL);
+  const int cls = a.S == 1 ? PT_K_ATTN_DECODE : PT_K_ATTN_PREFILL;
+  prof_scope ps(h, cls);
   if (h->path == PT_PATH_AUTO) {
     int r = a.S == 1 ? pt_launch_attn_decode(a, h->stream) : pt_launch_attn_prefill_mfma(a, h->stream);
     if (r < 0) return r;
-    if (r == 1) return PT_OK;
+    if (r > 0) { count_family(h, cls, r); return PT_OK; }
   }
+  count_family(h, cls, PT_FAMILY_GENERIC);
   return pt_launch_attn_generic(a, h->stream);
 }
 
@@ -370,6 +422,8 @@ static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
 
   if (!h->rope_ready) {
     rc = pt_launch_rope_table((float*)(h->ws + l.off_rope), c.max_seq, c.head_dim, c.rope_theta, st);
+    if (rc) return rc;
+    rc = pt_launch_fill_f32((float*)(h->ws + l.off_flag), 1, 0.0f, st);   // device status word: all-zero bits
     if (rc) return rc;
     h->rope_ready = true;
   }
@@ -391,7 +445,7 @@ static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
     x = dev_hidden_in;
     x_bstride = hidden_tracks == 1 ? 0 : rows * d;
   } else {
-    { prof_scope ps(h, PT_K_EMBED); rc = pt_launch_embed(h->w + l.off_embed, c.dtype, dev_tokens, rows, (int32_t)d, c.vocab, hm, st); }
+    { prof_scope ps(h, PT_K_EMBED); rc = pt_launch_embed(h->w + l.off_embed, c.dtype, dev_tokens, rows, (int32_t)d, c.vocab, hm, (int32_t*)(h->ws + l.off_flag), st); }
     if (rc) return rc;
     x = hm;
     x_bstride = 0;

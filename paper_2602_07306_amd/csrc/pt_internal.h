@@ -8,7 +8,10 @@
 
 #include <vector>
 
+// The library is built with hidden symbol visibility; only what pt.h declares is exported.
+#pragma GCC visibility push(default)
 #include "pt.h"
+#pragma GCC visibility pop
 
 typedef uint16_t bf16_t;  // raw bfloat16 bits
 
@@ -58,6 +61,7 @@ struct pt_layout {
   size_t off_part;    // fp32 split-K decode partials
   size_t off_last;    // dtype [max_batch, d] normed last rows for the head
   size_t off_skp;     // fp32 K slices of the decode residual GEMMs, [slice][T][rows][d]
+  size_t off_flag;    // int32 device status word (bit 0: a token id was out of range)
   size_t ws_bytes;
   int32_t elem_size;  // 4 or 2
   int32_t max_splits;
@@ -74,6 +78,7 @@ struct pt_prof {
   std::vector<pt_prof_pair> pending;
   double ms[PT_K_COUNT] = {0};
   int64_t launches[PT_K_COUNT] = {0};
+  int64_t family[PT_K_COUNT][PT_FAMILY_COUNT] = {{0}};   // launches per kernel family (see pt_profile_paths)
 };
 
 struct pt_handle {
@@ -87,7 +92,7 @@ struct pt_handle {
   int32_t seq_len;    // their common length
   int64_t merges;
   bool weights_ready;
-  bool rope_ready;
+  bool rope_ready;    // the rotary table and the device status word have been written
   float* taps;
   float* track_taps;
   int32_t path;
@@ -143,11 +148,13 @@ struct pt_gemm_args {
 enum { PT_SK_PART_FLOATS = 16 << 20 };
 
 int pt_launch_gemm_generic(const pt_gemm_args& g, hipStream_t s);
-// Returns 1 if the MFMA kernel family supports this problem (then it has been launched), 0 if not.
+// Tuned launchers return 0 if they do not cover the problem (nothing launched), a negative PT_ERR_* code,
+// or the kernel family that was launched (the numbering of pt_profile_paths).
+// MFMA tile kernels: returns 1 when launched.
 int pt_launch_gemm_mfma(const pt_gemm_args& g, hipStream_t s);
-// Weight-streaming kernel for M <= 64 (decode); same return convention.  With allow_split a residual GEMM may
-// leave pt_gemm_skinny_ksplit(g) > 1 K slices in g.sk_part ([slice][batch][M][N] fp32) instead of writing
-// out = res + product; pt_launch_resnorm adds them up.
+// Weight-streaming kernel for M <= 64 (decode): returns 2, or 3 for its matrix-vector form (M <= 4).  With
+// allow_split a residual GEMM may leave pt_gemm_skinny_ksplit(g) > 1 K slices in g.sk_part
+// ([slice][batch][M][N] fp32) instead of writing out = res + product; pt_launch_resnorm adds them up.
 int pt_launch_gemm_skinny(const pt_gemm_args& g, bool allow_split, hipStream_t s);
 int pt_gemm_skinny_ksplit(const pt_gemm_args& g);
 // True if pt_launch_gemm_skinny would run this problem (shape fields only) on the kernel that can form its A
@@ -173,14 +180,20 @@ struct pt_attn_args {
 };
 
 int pt_launch_attn_generic(const pt_attn_args& a, hipStream_t s);
-int pt_launch_attn_prefill_mfma(const pt_attn_args& a, hipStream_t s);  // 1 if handled
-int pt_launch_attn_decode(const pt_attn_args& a, hipStream_t s);        // 1 if handled
+int pt_launch_attn_prefill_mfma(const pt_attn_args& a, hipStream_t s);  // 1: LDS-tiled, 2: register operands
+int pt_launch_attn_decode(const pt_attn_args& a, hipStream_t s);        // 1: matrix-core kernel, 2: vector kernel
+
+// Tuning overrides (pt_set_tuning): tile configuration of the MFMA GEMM (-1 = by shape) and plan of the
+// weight-streaming GEMM (0 = by shape).
+extern int pt_tune_gemm_cfg;
+extern int pt_tune_skinny_plan;
 
 // ---------------------------------------------------------------------------------------------
 // Elementwise / bandwidth-bound kernels.
 // ---------------------------------------------------------------------------------------------
+// flag: device status word; bit 0 is set when a token id lies outside [0, vocab)
 int pt_launch_embed(const void* embed, int32_t dtype, const int32_t* tokens, int64_t rows, int32_t d,
-                    int32_t vocab, float* h, hipStream_t s);
+                    int32_t vocab, float* h, int32_t* flag, hipStream_t s);
 int pt_launch_rmsnorm(const float* h, int64_t h_bstride, const float* gains, int64_t g_bstride,
                       void* out, int64_t out_bstride, int32_t dtype, int32_t batch, int64_t rows,
                       int32_t d, float eps, hipStream_t s);
@@ -198,6 +211,15 @@ int pt_launch_resnorm(const float* part, int32_t slices, const float* res, int64
                       int64_t h_bstride, const float* gains, int64_t g_bstride, void* out, int64_t out_bstride,
                       int32_t batch, int64_t rows, int32_t d, float eps, hipStream_t s);
 int pt_launch_fill_f32(float* dst, int64_t n, float v, hipStream_t s);
+// Sets attribute hipFuncAttributeMaxDynamicSharedMemorySize once per kernel (thread-safe: the result is the
+// initialiser of a function-local static at the call site).
+#define PT_SET_MAX_LDS_ONCE(kern, bytes)                                                                   \
+  do {                                                                                                     \
+    static const hipError_t attr_rc_ =                                                                     \
+        hipFuncSetAttribute((const void*)(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)(bytes)); \
+    if (attr_rc_ != hipSuccess)                                                                            \
+      return pt_set_error(PT_ERR_HIP, "hipFuncSetAttribute: %s", hipGetErrorString(attr_rc_));             \
+  } while (0)
 // weight access: tensor ids are PT_W_*; phys points at the tensor's physical base
 int pt_launch_weight_init(pt_handle* h, uint64_t seed);
 int pt_launch_weight_copy(pt_handle* h, int32_t tensor, int32_t track, int32_t layer, float* logical,

@@ -18,6 +18,33 @@ def rel_err(got, ref) -> float:
     return float(np.max(np.abs(got - ref)) / max(np.max(np.abs(ref)), 1e-30))
 
 
+def row_rel_err(got, ref) -> float:
+    """The worst row of the same measure taken row by row (rows = the last axis):
+    max over rows of max |got_row - ref_row| / max |ref_row|.  A wrong row of small magnitude
+    cannot hide under the largest entry of the tensor."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    num = np.max(np.abs(got - ref), axis=-1)
+    den = np.maximum(np.max(np.abs(ref), axis=-1), 1e-30)
+    return float(np.max(num / den))
+
+
+def assert_close(got, ref, tol, what=""):
+    """Both error measures within tol: over the whole tensor and for every row."""
+    e, er = rel_err(got, ref), row_rel_err(got, ref)
+    assert e <= tol and er <= tol, "%s: relative error %.3g (tensor), %.3g (worst row) exceeds %g" % (what, e, er, tol)
+    return e, er
+
+
+GEMM_CLASSES = ("gemm_qkv", "gemm_out", "gemm_gateup", "gemm_down", "gemm_head")
+PATH_CLASSES = GEMM_CLASSES + ("attn_prefill", "attn_decode")
+
+
+def path_counts(model):
+    """{kernel class: launches per kernel family} since the last pt_profile_reset."""
+    return {c: model.pt_profile_paths(c) for c in PATH_CLASSES}
+
+
 def argmax_agrees(got_logits, ref_logits, tol) -> bool:
     """ids must match on every row whose oracle top-2 gap exceeds tol * max|row|."""
     ref = np.asarray(ref_logits, dtype=np.float64)

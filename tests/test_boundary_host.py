@@ -28,6 +28,22 @@ def test_library_loads_and_exports_every_declared_symbol():
     assert sorted(PB.EXPORTS) == names
 
 
+def test_dynamic_symbol_table_holds_only_the_declared_functions():
+    """The library is linked with hidden visibility and an export list: no internal launcher, tuning
+    variable or kernel stub is reachable from outside."""
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", PB.LIB_PATH], capture_output=True, text=True, check=True).stdout
+    exported = sorted(line.split()[-1] for line in out.splitlines() if line.strip())
+    assert exported == declared_functions()
+
+
+def test_tuning_knobs_are_validated():
+    assert PB.lib().pt_set_tuning(99, 0) == PB.PT_ERR_INVALID_ARGUMENT
+    assert "knob" in PB.pt_last_error()
+    PB.pt_set_tuning(PB.PT_TUNE_GEMM_TILE_CONFIG, -1)
+    PB.pt_set_tuning(PB.PT_TUNE_SKINNY_PLAN, 0)
+
+
 def test_config_struct_matches_the_header():
     text = open(os.path.join(ROOT, "include", "pt.h")).read()
     body = text[text.index("typedef struct pt_config {"):text.index("} pt_config;")]

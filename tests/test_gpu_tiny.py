@@ -172,3 +172,25 @@ def test_track_merge_matches_the_oracle(dtype, n, tokens, d):
     PB.pt_track_merge(dev, 0.5, out=dev[0])
     torch.cuda.synchronize()
     assert torch.equal(dev[0], out)
+
+
+def test_out_of_range_token_ids_are_reported_at_the_next_status_check(tiny):
+    """Forward calls are asynchronous and cannot return an error for data that lives on the device: a token id
+    outside the vocabulary raises a device flag that pt_sync_status turns into PT_ERR_INVALID_ARGUMENT, once."""
+    PB, cfg, W, model = tiny
+    model.pt_reset()
+    good = I.make_tokens(0, 1, 16, cfg.vocab)
+    model.pt_prefill(torch.from_numpy(good).cuda())
+    model.pt_sync_status()
+    for bad_id in (cfg.vocab, -1, 2 ** 31 - 1):
+        bad = good.copy()
+        bad[0, 5] = bad_id
+        model.pt_prefill(torch.from_numpy(bad).cuda())
+        with pytest.raises(PB.PTError) as e:
+            model.pt_sync_status()
+        assert e.value.code == PB.PT_ERR_INVALID_ARGUMENT
+        model.pt_sync_status()          # the flag was cleared
+    model.pt_prefill(torch.from_numpy(good).cuda())
+    model.pt_decode_step(torch.from_numpy(np.array([cfg.vocab + 3], np.int32)).cuda())
+    with pytest.raises(PB.PTError):
+        model.pt_sync_status()

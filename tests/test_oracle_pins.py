@@ -231,6 +231,37 @@ def test_cached_decode_equals_full_recompute():
     assert st.merge_count == 5 * (cfg.n_layers // cfg.block_depth)
 
 
+@pytest.mark.parametrize("per_track", [False, True])
+def test_cached_decode_from_hidden_states_equals_full_recompute(per_track):
+    """The hidden-state entry of the decode step ([B, d]: the same input for every track, and
+    [T, B, d]: one input per track) against a prefill of the sequence extended by those rows."""
+    cfg = cfg_of(vocab=0)
+    W = rand_weights(cfg)
+    rng = np.random.default_rng(18)
+    T, B, S, d = cfg.n_tracks, 2, 9, cfg.d_model
+    x = rng.normal(size=(T, B, S, d)) if per_track else rng.normal(size=(B, S, d))
+    full, _ = prefill(cfg, W, hidden_in=x)
+    _, st = prefill(cfg, W, hidden_in=x[..., :5, :], max_seq=16)
+    for p in range(5, S):
+        step = O.pt_decode_step(cfg, W, st, hidden_in=x[..., p, :])
+        np.testing.assert_allclose(step["hidden"], full["hidden"][:, p], rtol=1e-10, atol=1e-11)
+        assert "logits" not in step
+    assert list(st.length) == [S, S]
+    # the two forms agree when every track is handed the same rows
+    if not per_track:
+        _, st1 = prefill(cfg, W, hidden_in=x[:, :5], max_seq=16)
+        _, st2 = prefill(cfg, W, hidden_in=np.broadcast_to(x[:, :5], (T,) + x[:, :5].shape), max_seq=16)
+        a = O.pt_decode_step(cfg, W, st1, hidden_in=x[:, 5])
+        b = O.pt_decode_step(cfg, W, st2, hidden_in=np.broadcast_to(x[:, 5], (T, B, d)))
+        assert np.array_equal(a["hidden"], b["hidden"])
+    else:
+        # a per-track input must reach its own track: swapping two tracks' rows changes the result
+        _, st3 = prefill(cfg, W, hidden_in=x[..., :5, :], max_seq=16)
+        swapped = x[[1, 0, 2], :, 5, :]
+        c = O.pt_decode_step(cfg, W, st3, hidden_in=swapped)
+        assert not np.allclose(c["hidden"], full["hidden"][:, 5])
+
+
 def test_batch_independence():
     cfg = cfg_of()
     W = rand_weights(cfg)
