@@ -129,6 +129,22 @@ int pt_decode_step(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
                    int32_t hidden_tracks, int32_t B, float* dev_logits, float* dev_hidden_out,
                    int32_t* dev_argmax);
 
+/* pt_decode_step for callers that cannot allocate device memory or reserve a workspace for decoding: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * errors as pt_decode_step, but every temporary of the step (residual streams, normed activations, q, attention
+ * output, SwiGLU product, decode-attention split partials, K slices of the decode GEMMs) lives in a static
+ * device array inside the library (32 MiB per GPU, held from library load to process end) instead of the
+ * workspace arena given to pt_create; only the weight and KV arenas of the handle and the caller's input and
+ * output buffers are touched besides.  Calls no hipMalloc / hipFree or any allocating routine.
+ *   Limit: the temporaries of one step at batch B must fit the array, else PT_ERR_CAPACITY and nothing is
+ *   launched (examples that fit: Mid PT at batch 32, Large PT at batch 64, the one-GPU share at batch 64).
+ *   All calls on one GPU share that GPU's array, whatever the handle: calls that overlap in time on one GPU
+ *   (different streams or threads) race.  The array keeps the previous call's contents; nothing in it needs to
+ *   start at zero, every kernel writes what it later reads. */
+int pt_decode_step_static(pt_handle* h, const int32_t* dev_tokens, const float* dev_hidden_in,
+                          int32_t hidden_tracks, int32_t B, float* dev_logits, float* dev_hidden_out,
+                          int32_t* dev_argmax);
+
 /* The track merge of Algorithm 1 (the all-reduce, as an on-device reduction), stateless:
  *   out[t, :] = scale * (tracks[0][t, :] + ... + tracks[n-1][t, :]), fp32 accumulation in track
  *   order, for t < tokens.  host_tracks is a HOST array of n DEVICE pointers, each [tokens, d]

@@ -33,7 +33,7 @@ EXPORTS = [
     "pt_query_bytes", "pt_create", "pt_destroy", "pt_init_weights", "pt_set_weight", "pt_get_weight",
     "pt_prefill", "pt_decode_step", "pt_track_merge", "pt_set_taps", "pt_set_kernel_path", "pt_reset",
     "pt_merge_count", "pt_seq_len", "pt_last_error", "pt_profile_enable", "pt_profile_read",
-    "pt_profile_reset", "pt_profile_paths", "pt_sync_status", "pt_set_tuning", "pt_argmax",
+    "pt_profile_reset", "pt_profile_paths", "pt_sync_status", "pt_set_tuning", "pt_argmax", "pt_decode_step_static",
 ]
 
 KERNEL_CLASSES = ["embed", "rmsnorm", "gemm_qkv", "attn_prefill", "attn_decode", "gemm_out",
@@ -75,6 +75,7 @@ def lib() -> C.CDLL:
     L.pt_get_weight.argtypes = [vp, i32, i32, i32, vp]
     L.pt_prefill.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp]
     L.pt_decode_step.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp]
+    L.pt_decode_step_static.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp]
     L.pt_track_merge.argtypes = [C.POINTER(vp), i32, i64, i32, i32, C.c_float, vp, vp]
     L.pt_set_taps.argtypes = [vp, vp, vp]
     L.pt_set_kernel_path.argtypes = [vp, i32]
@@ -255,7 +256,9 @@ class PTModel:
 
     def pt_decode_step(self, tokens=None, hidden_in=None, want_logits: bool = True,
                        want_hidden: bool = False, want_argmax: bool = False, logits_out=None,
-                       argmax_out=None, hidden_out=None):
+                       argmax_out=None, hidden_out=None, static_scratch: bool = False):
+        """One decode step.  static_scratch=True calls pt_decode_step_static (temporaries in the library's
+        static device array instead of the workspace arena); the output tensors are still the caller's."""
         cfg, torch = self.cfg, self.torch
         if tokens is not None:
             B, ht = tokens.shape[0], 1
@@ -271,8 +274,8 @@ class PTModel:
         amax = argmax_out
         if amax is None and want_argmax:
             amax = torch.empty((B,), dtype=torch.int32, device=self.device)
-        _check(lib().pt_decode_step(self.h, _ptr(tokens), _ptr(hidden_in), ht, B, _ptr(logits),
-                                    _ptr(hidden), _ptr(amax)))
+        fn = lib().pt_decode_step_static if static_scratch else lib().pt_decode_step
+        _check(fn(self.h, _ptr(tokens), _ptr(hidden_in), ht, B, _ptr(logits), _ptr(hidden), _ptr(amax)))
         return logits, hidden, amax
 
     def pt_profile_enable(self, classes):

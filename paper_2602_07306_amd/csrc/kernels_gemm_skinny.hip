@@ -512,7 +512,7 @@ static sk_plan plan_skinny(const pt_gemm_args& g, int tiles, int ks_max) {
   double best_cost = 1e30;
   for (int ks = 1; ks <= ks_max; ++ks) {
     if (g.K % (ks * 4 * 128)) continue;                          // an even number of K steps per wavefront
-    if (ks > 1 && (int64_t)ks * g.batch * g.M * g.N > (int64_t)PT_SK_PART_FLOATS) break;
+    if (ks > 1 && (int64_t)ks * g.batch * g.M * g.N > g.sk_part_floats) break;
     const double steps = g.K / (ks * 256) + 6.0;
     const int wpt_min = (tiles + 3) / 4;
     // candidates: the fewest workgroups, and the grids that fill whole rounds
@@ -538,7 +538,7 @@ static sk_plan plan_skinny(const pt_gemm_args& g, int tiles, int ks_max) {
     const int fw = pt_tune_skinny_plan >> 8, fks = pt_tune_skinny_plan & 255;
     if (fw >= (tiles + 3) / 4 && fw <= tiles) best.wpt = fw;
     best.ks = 1;
-    if (fks > 1 && fks <= ks_max && g.K % (fks * 4 * 128) == 0 && (int64_t)fks * g.batch * g.M * g.N <= (int64_t)PT_SK_PART_FLOATS)
+    if (fks > 1 && fks <= ks_max && g.K % (fks * 4 * 128) == 0 && (int64_t)fks * g.batch * g.M * g.N <= g.sk_part_floats)
       best.ks = fks;
   }
   return best;

@@ -4,6 +4,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 
 #include "pt_internal.h"
@@ -68,6 +69,8 @@ int pt_compute_layout(const pt_config* c, pt_layout* l) {
   l->off_gf = off;     off = align_up(off + (size_t)(d * 4), 256);
   l->off_embed = off;  off = align_up(off + (size_t)((int64_t)c->vocab * d * es), 256);
   l->off_headT = off;  off = align_up(off + (size_t)((int64_t)c->vocab * d * es), 256);
+  l->off_rope = off;   off = align_up(off + (size_t)((int64_t)c->max_seq * hd * 4), 256);
+  l->off_flag = off;   off = align_up(off + 4, 256);
   l->weight_bytes = off;
 
   l->s_pad = (c->max_seq + 63) / 64 * 64 + 64;
@@ -77,22 +80,29 @@ int pt_compute_layout(const pt_config* c, pt_layout* l) {
   l->off_v = align_up((size_t)(T * L * B * c->n_kv_heads * k_head * es), 256);
   l->kv_bytes = align_up(l->off_v + (size_t)(T * L * B * c->n_kv_heads * v_head * es), 256);
 
-  const int64_t M = B * c->max_seq;
-  l->max_splits = 32;
-  off = 0;
-  l->off_h = off;    off = align_up(off + (size_t)(T * M * d * 4), 256);
-  l->off_hm = off;   off = align_up(off + (size_t)(M * d * 4), 256);
-  l->off_a = off;    off = align_up(off + (size_t)(T * M * d * es), 256);
-  l->off_q = off;    off = align_up(off + (size_t)(T * M * l->hq * es), 256);
-  l->off_o = off;    off = align_up(off + (size_t)(T * M * l->hq * es), 256);
-  l->off_m = off;    off = align_up(off + (size_t)(T * M * f * es), 256);
-  l->off_rope = off; off = align_up(off + (size_t)((int64_t)c->max_seq * hd * 4), 256);
-  l->off_part = off; off = align_up(off + (size_t)(T * B * c->n_heads * l->max_splits * (hd + 2) * 4), 256);
-  l->off_last = off; off = align_up(off + (size_t)(B * d * es), 256);
-  l->off_skp = off;  off = align_up(off + (size_t)PT_SK_PART_FLOATS * 4, 256);
-  l->off_flag = off; off = align_up(off + 4, 256);
-  l->ws_bytes = off;
+  pt_workspace w;
+  pt_layout_workspace(c, l, B * c->max_seq, B, PT_SK_PART_FLOATS, PT_MAX_SPLITS, &w);
+  l->ws_bytes = w.bytes;
+  (void)f;
   return PT_OK;
+}
+
+void pt_layout_workspace(const pt_config* c, const pt_layout* l, int64_t rows, int64_t batch, int64_t skp_floats,
+                         int32_t max_splits, pt_workspace* w) {
+  const int64_t T = c->n_tracks, d = c->d_model, f = c->d_ffn, hd = c->head_dim, es = l->elem_size;
+  size_t off = 0;
+  w->base = nullptr;
+  w->off_h = off;    off = align_up(off + (size_t)(T * rows * d * 4), 256);
+  w->off_hm = off;   off = align_up(off + (size_t)(rows * d * 4), 256);
+  w->off_a = off;    off = align_up(off + (size_t)(T * rows * d * es), 256);
+  w->off_q = off;    off = align_up(off + (size_t)(T * rows * l->hq * es), 256);
+  w->off_o = off;    off = align_up(off + (size_t)(T * rows * l->hq * es), 256);
+  w->off_m = off;    off = align_up(off + (size_t)(T * rows * f * es), 256);
+  w->off_part = off; off = align_up(off + (size_t)(T * batch * c->n_heads * max_splits * (hd + 2) * 4), 256);
+  w->off_skp = off;  off = align_up(off + (size_t)skp_floats * 4, 256);
+  w->bytes = off;
+  w->skp_floats = skp_floats;
+  w->max_splits = max_splits;
 }
 
 extern "C" int pt_query_bytes(const pt_config* cfg, size_t* w, size_t* kv, size_t* ws) {
@@ -131,6 +141,9 @@ extern "C" int pt_create(const pt_config* cfg, void* dev_weights, size_t weight_
   h->w = (char*)dev_weights;
   h->kv = (char*)dev_kv;
   h->ws = (char*)dev_ws;
+  pt_layout_workspace(cfg, &l, (int64_t)cfg->max_batch * cfg->max_seq, cfg->max_batch, PT_SK_PART_FLOATS, PT_MAX_SPLITS, &h->arena);
+  h->arena.base = h->ws;
+  h->active = &h->arena;
   h->stream = (hipStream_t)hip_stream;
   h->batch = 0;
   h->seq_len = 0;
@@ -331,7 +344,7 @@ extern "C" int pt_sync_status(pt_handle* h) {
     return PT_OK;
   }
   int32_t flag = 0;
-  int32_t* dev_flag = (int32_t*)(h->ws + h->lay.off_flag);
+  int32_t* dev_flag = (int32_t*)(h->w + h->lay.off_flag);
   PT_HIP_CHECK(hipMemcpyAsync(&flag, dev_flag, sizeof(flag), hipMemcpyDeviceToHost, h->stream));
   PT_HIP_CHECK(hipStreamSynchronize(h->stream));
   if (flag) {
@@ -353,7 +366,8 @@ static inline void count_family(pt_handle* h, int cls, int family) {
 static int run_gemm(pt_handle* h, const pt_gemm_args& g_in, int cls) {
   prof_scope ps(h, cls);
   pt_gemm_args g = g_in;
-  g.sk_part = (float*)(h->ws + h->lay.off_skp);
+  g.sk_part = (float*)(h->active->base + h->active->off_skp);
+  g.sk_part_floats = h->active->skp_floats;
   if (h->path == PT_PATH_AUTO) {
     int r = g.M <= 64 ? pt_launch_gemm_skinny(g, false, h->stream) : 0;
     if (r < 0) return r;
@@ -374,7 +388,8 @@ static int run_residual_gemm_norm(pt_handle* h, const pt_gemm_args& g_in, int cl
                                   int64_t gain_bstride, void* normed) {
   const pt_config& c = h->cfg;
   pt_gemm_args g = g_in;
-  g.sk_part = (float*)(h->ws + h->lay.off_skp);
+  g.sk_part = (float*)(h->active->base + h->active->off_skp);
+  g.sk_part_floats = h->active->skp_floats;
   const int64_t rows = g.M;
   int rc;
   if (h->path == PT_PATH_AUTO && g.M <= 64 && g.N == g.ldo && g.N <= 8192 && pt_gemm_skinny_ksplit(g) > 1) {
@@ -409,9 +424,10 @@ static int run_attention(pt_handle* h, const pt_attn_args& a) {
   return pt_launch_attn_generic(a, h->stream);
 }
 
-static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hidden_in,
+static int forward(pt_handle* h, const pt_workspace& w, const int32_t* dev_tokens, const float* dev_hidden_in,
                    int32_t hidden_tracks, int32_t B, int32_t S, int32_t pos0, int32_t logits_mode,
                    float* dev_logits, float* dev_hidden_out, int32_t* dev_argmax) {
+  h->active = &w;
   const pt_config& c = h->cfg;
   const pt_layout& l = h->lay;
   const int64_t T = c.n_tracks, L = c.n_layers, d = c.d_model, f = c.d_ffn;
@@ -421,20 +437,20 @@ static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
   int rc;
 
   if (!h->rope_ready) {
-    rc = pt_launch_rope_table((float*)(h->ws + l.off_rope), c.max_seq, c.head_dim, c.rope_theta, st);
+    rc = pt_launch_rope_table((float*)(h->w + l.off_rope), c.max_seq, c.head_dim, c.rope_theta, st);
     if (rc) return rc;
-    rc = pt_launch_fill_f32((float*)(h->ws + l.off_flag), 1, 0.0f, st);   // device status word: all-zero bits
+    rc = pt_launch_fill_f32((float*)(h->w + l.off_flag), 1, 0.0f, st);   // device status word: all-zero bits
     if (rc) return rc;
     h->rope_ready = true;
   }
 
-  float* hres = (float*)(h->ws + l.off_h);   // [T, rows, d]
-  float* hm = (float*)(h->ws + l.off_hm);    // [rows, d]
+  float* hres = (float*)(w.base + w.off_h);   // [T, rows, d]
+  float* hm = (float*)(w.base + w.off_hm);    // [rows, d]
   const float* merged = hm;                  // the output activation of Algorithm 1 after the last merge
-  char* abuf = h->ws + l.off_a;
-  char* qbuf = h->ws + l.off_q;
-  char* obuf = h->ws + l.off_o;
-  char* mbuf = h->ws + l.off_m;
+  char* abuf = w.base + w.off_a;
+  char* qbuf = w.base + w.off_q;
+  char* obuf = w.base + w.off_o;
+  char* mbuf = w.base + w.off_m;
   const float* gains = (const float*)(h->w + l.off_gains);
 
   // Algorithm 1, first line: every track starts from the same embedding input x.  x is kept
@@ -445,7 +461,7 @@ static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
     x = dev_hidden_in;
     x_bstride = hidden_tracks == 1 ? 0 : rows * d;
   } else {
-    { prof_scope ps(h, PT_K_EMBED); rc = pt_launch_embed(h->w + l.off_embed, c.dtype, dev_tokens, rows, (int32_t)d, c.vocab, hm, (int32_t*)(h->ws + l.off_flag), st); }
+    { prof_scope ps(h, PT_K_EMBED); rc = pt_launch_embed(h->w + l.off_embed, c.dtype, dev_tokens, rows, (int32_t)d, c.vocab, hm, (int32_t*)(h->w + l.off_flag), st); }
     if (rc) return rc;
     x = hm;
     x_bstride = 0;
@@ -493,7 +509,7 @@ static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
     g.olp = qbuf; g.olp_bstride = rows * l.hq;
     g.kc = h->kv + l.off_k + (size_t)(layer * c.max_batch * c.n_kv_heads * kv_head_k * es);
     g.vc = h->kv + l.off_v + (size_t)(layer * c.max_batch * c.n_kv_heads * kv_head_v * es);
-    g.rope = (const float*)(h->ws + l.off_rope);
+    g.rope = (const float*)(h->w + l.off_rope);
     g.H = c.n_heads; g.Hkv = c.n_kv_heads; g.hd = c.head_dim; g.S = S; g.pos0 = pos0;
     g.s_pad = (int32_t)l.s_pad;
     // cache strides are stated for K; the V^T side uses hd * s_pad per head with the same nesting
@@ -515,7 +531,7 @@ static int forward(pt_handle* h, const int32_t* dev_tokens, const float* dev_hid
     a.n_tracks = (int32_t)T; a.B = B; a.S = S; a.pos0 = pos0;
     a.H = c.n_heads; a.Hkv = c.n_kv_heads; a.hd = c.head_dim; a.s_pad = (int32_t)l.s_pad;
     a.dtype = c.dtype;
-    a.partials = (float*)(h->ws + l.off_part); a.max_splits = l.max_splits;
+    a.partials = (float*)(w.base + w.off_part); a.max_splits = w.max_splits;
     rc = run_attention(h, a);
     if (rc) return rc;
 
@@ -644,16 +660,16 @@ extern "C" int pt_prefill(pt_handle* h, const int32_t* dev_tokens, const float* 
   }
   int rc = check_inputs(h, dev_tokens, dev_hidden_in, hidden_tracks);
   if (rc) return rc;
-  rc = forward(h, dev_tokens, dev_hidden_in, hidden_tracks, B, S, 0, logits_mode, dev_logits, dev_hidden_out, nullptr);
+  rc = forward(h, h->arena, dev_tokens, dev_hidden_in, hidden_tracks, B, S, 0, logits_mode, dev_logits, dev_hidden_out, nullptr);
+  h->active = &h->arena;
   if (rc) return rc;
   h->batch = B;
   h->seq_len = S;
   return PT_OK;
 }
 
-extern "C" int pt_decode_step(pt_handle* h, const int32_t* dev_tokens, const float* dev_hidden_in,
-                              int32_t hidden_tracks, int32_t B, float* dev_logits,
-                              float* dev_hidden_out, int32_t* dev_argmax) {
+static int decode_checks(pt_handle* h, const int32_t* dev_tokens, const float* dev_hidden_in, int32_t hidden_tracks,
+                         int32_t B, const float* dev_logits, const int32_t* dev_argmax) {
   int rc = check_inputs(h, dev_tokens, dev_hidden_in, hidden_tracks);
   if (rc) return rc;
   if (h->batch == 0) return pt_set_error(PT_ERR_BAD_STATE, "decode before prefill");
@@ -661,8 +677,72 @@ extern "C" int pt_decode_step(pt_handle* h, const int32_t* dev_tokens, const flo
   if (h->seq_len + 1 > h->cfg.max_seq) return pt_set_error(PT_ERR_CAPACITY, "sequence length %d + 1 exceeds max_seq = %d", h->seq_len, h->cfg.max_seq);
   if ((dev_logits || dev_argmax) && h->cfg.vocab == 0) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "model has no vocabulary: no logits");
   if (dev_argmax && !dev_logits) return pt_set_error(PT_ERR_NULL_POINTER, "argmax needs a logits buffer");
-  rc = forward(h, dev_tokens, dev_hidden_in, hidden_tracks, B, 1, h->seq_len,
+  return PT_OK;
+}
+
+extern "C" int pt_decode_step(pt_handle* h, const int32_t* dev_tokens, const float* dev_hidden_in,
+                              int32_t hidden_tracks, int32_t B, float* dev_logits,
+                              float* dev_hidden_out, int32_t* dev_argmax) {
+  int rc = decode_checks(h, dev_tokens, dev_hidden_in, hidden_tracks, B, dev_logits, dev_argmax);
+  if (rc) return rc;
+  rc = forward(h, h->arena, dev_tokens, dev_hidden_in, hidden_tracks, B, 1, h->seq_len,
                dev_logits ? PT_LOGITS_LAST : PT_LOGITS_NONE, dev_logits, dev_hidden_out, dev_argmax);
+  h->active = &h->arena;
+  if (rc) return rc;
+  h->seq_len += 1;
+  return PT_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// pt_decode_step_static: the decode step for callers that cannot allocate.  Every temporary of the step lives
+// in `scratch`, a file-scope device array that each GPU holds from library load to process end.  In host code
+// the array's name is only a handle for hipGetSymbolAddress; the device address obtained from it (once per
+// device, with that device current) is what kernels and fills receive.
+// ---------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[PT_STATIC_SCRATCH_BYTES];
+
+enum { PT_MAX_DEVICES = 64 };
+static std::mutex g_scratch_mutex;
+static char* g_scratch_ptr[PT_MAX_DEVICES];   // device address of `scratch` on each device, once resolved
+
+static int static_scratch_base(char** out) {
+  int dev = -1;
+  PT_HIP_CHECK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= PT_MAX_DEVICES) return pt_set_error(PT_ERR_HIP, "device ordinal %d out of range", dev);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    PT_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return pt_set_error(PT_ERR_HIP, "hipGetSymbolAddress returned a null address for the static scratch array");
+    g_scratch_ptr[dev] = (char*)p;
+  }
+  *out = g_scratch_ptr[dev];
+  return PT_OK;
+}
+
+extern "C" int pt_decode_step_static(pt_handle* h, const int32_t* dev_tokens, const float* dev_hidden_in,
+                                     int32_t hidden_tracks, int32_t B, float* dev_logits,
+                                     float* dev_hidden_out, int32_t* dev_argmax) {
+  int rc = decode_checks(h, dev_tokens, dev_hidden_in, hidden_tracks, B, dev_logits, dev_argmax);
+  if (rc) return rc;
+  const pt_config& c = h->cfg;
+  // Temporaries of B rows per track.  Decode attention cuts a sequence into at most ceil(1024 / (tracks *
+  // sequences * KV heads)) key ranges; the K-slice area of the decode GEMMs gets what is left of the array.
+  const int64_t groups = (int64_t)c.n_tracks * B * c.n_kv_heads;
+  int32_t splits = (int32_t)((1024 + groups - 1) / groups);
+  if (splits > PT_MAX_SPLITS) splits = PT_MAX_SPLITS;
+  pt_workspace w;
+  pt_layout_workspace(&c, &h->lay, B, B, 0, splits, &w);
+  if (w.bytes > (size_t)PT_STATIC_SCRATCH_BYTES)
+    return pt_set_error(PT_ERR_CAPACITY, "a decode step of this model at batch %d needs %zu bytes of temporaries; the "
+                        "static scratch array holds %d", B, w.bytes, (int)PT_STATIC_SCRATCH_BYTES);
+  w.skp_floats = (int64_t)((size_t)PT_STATIC_SCRATCH_BYTES - w.bytes) / 4;
+  if (w.skp_floats > PT_SK_PART_FLOATS) w.skp_floats = PT_SK_PART_FLOATS;
+  rc = static_scratch_base(&w.base);
+  if (rc) return rc;
+  rc = forward(h, w, dev_tokens, dev_hidden_in, hidden_tracks, B, 1, h->seq_len,
+               dev_logits ? PT_LOGITS_LAST : PT_LOGITS_NONE, dev_logits, dev_hidden_out, dev_argmax);
+  h->active = &h->arena;
   if (rc) return rc;
   h->seq_len += 1;
   return PT_OK;

@@ -46,25 +46,32 @@ struct pt_layout {
   size_t off_gf;        // fp32 [d]
   size_t off_embed;     // dtype [V, d]
   size_t off_headT;     // dtype [V, d]
+  size_t off_rope;      // fp32 [max_seq, hd/2, 2] cos, sin (a constant of the model, written by the first forward call)
+  size_t off_flag;      // int32 device status word (bit 0: a token id was out of range)
   size_t weight_bytes;
   // KV arena
   int64_t kv_seq_elems;  // per (t, l, b, hkv): max_seq*hd (K) ; hd*s_pad (Vt)
   size_t off_k, off_v, kv_bytes;
-  // workspace arena (M = max_batch * max_seq rows)
-  size_t off_h;       // fp32 [T, M, d] residual streams
-  size_t off_hm;      // fp32 [M, d]    merged activation
-  size_t off_a;       // dtype [T, M, d] normed activations
-  size_t off_q;       // dtype [T, M, hq]
-  size_t off_o;       // dtype [T, M, hq] attention output
-  size_t off_m;       // dtype [T, M, f]  SwiGLU product
-  size_t off_rope;    // fp32 [max_seq, hd/2, 2] cos, sin
-  size_t off_part;    // fp32 split-K decode partials
-  size_t off_last;    // dtype [max_batch, d] normed last rows for the head
-  size_t off_skp;     // fp32 K slices of the decode residual GEMMs, [slice][T][rows][d]
-  size_t off_flag;    // int32 device status word (bit 0: a token id was out of range)
-  size_t ws_bytes;
+  size_t ws_bytes;    // workspace arena: a pt_workspace for M = max_batch * max_seq rows
   int32_t elem_size;  // 4 or 2
-  int32_t max_splits;
+};
+
+// Temporaries of one forward call over `rows` rows per track, as offsets into one block of device memory: the
+// caller's workspace arena (sized for max_batch * max_seq rows) or, for pt_decode_step_static, the library's
+// static device array (sized for the rows of that call).
+struct pt_workspace {
+  char* base;
+  size_t off_h;       // fp32 [T, rows, d] residual streams
+  size_t off_hm;      // fp32 [rows, d]    merged activation
+  size_t off_a;       // dtype [T, rows, d] normed activations
+  size_t off_q;       // dtype [T, rows, hq]
+  size_t off_o;       // dtype [T, rows, hq] attention output
+  size_t off_m;       // dtype [T, rows, f]  SwiGLU product
+  size_t off_part;    // fp32 split-K decode-attention partials, [T*B*H][max_splits][hd + 2]
+  size_t off_skp;     // fp32 K slices of the decode residual GEMMs, [slice][T][rows][d]
+  size_t bytes;
+  int64_t skp_floats; // capacity behind off_skp
+  int32_t max_splits; // capacity behind off_part, in splits per (track, sequence, head)
 };
 
 struct pt_prof_pair {
@@ -87,6 +94,8 @@ struct pt_handle {
   char* w;
   char* kv;
   char* ws;
+  pt_workspace arena;           // the caller's workspace arena, laid out for max_batch * max_seq rows
+  const pt_workspace* active;   // temporaries of the forward call in progress
   hipStream_t stream;
   int32_t batch;      // B of the live sequences (0: none)
   int32_t seq_len;    // their common length
@@ -102,6 +111,10 @@ struct pt_handle {
 int pt_set_error(int code, const char* fmt, ...);
 int pt_validate_config(const pt_config* c);
 int pt_compute_layout(const pt_config* c, pt_layout* l);
+// Lays out the temporaries of a forward call over `rows` rows per track (`batch` sequences) from offset 0;
+// skp_floats and max_splits are the capacities wanted for the two split scratch areas.
+void pt_layout_workspace(const pt_config* c, const pt_layout* l, int64_t rows, int64_t batch, int64_t skp_floats,
+                         int32_t max_splits, pt_workspace* w);
 
 // ---------------------------------------------------------------------------------------------
 // GEMM: C[b] (M x N) = A[b] (M x K, row-major, lda) * W[b]^T, W[b] is [N, K] row-major (ldb),
@@ -135,8 +148,9 @@ struct pt_gemm_args {
   // kv_head_elems = max_seq * hd elements of K and hd * s_pad elements of V^T
   int64_t kv_bstride, kv_seq_stride, kv_head_elems;
   int32_t H, Hkv, hd, S, pos0, s_pad;
-  // K-slice scratch of the decode kernel, PT_SK_PART_FLOATS floats (may be null: K is not split over workgroups)
+  // K-slice scratch of the decode kernel, sk_part_floats floats (may be null: K is not split over workgroups)
   float* sk_part;
+  int64_t sk_part_floats;
   // Optional, honoured only where pt_gemm_fuses_norm(g) holds: A is not read; row m of track b is
   // RMSNorm(norm_src[b][m][0..K)) * norm_gain[b][0..K), formed by the kernel itself.
   const float* norm_src;
@@ -145,7 +159,9 @@ struct pt_gemm_args {
   float norm_eps;
 };
 
-enum { PT_SK_PART_FLOATS = 16 << 20 };
+enum { PT_SK_PART_FLOATS = 16 << 20 };   // K-slice scratch inside the caller's workspace arena
+enum { PT_MAX_SPLITS = 32 };
+enum { PT_STATIC_SCRATCH_BYTES = 32 << 20 };   // the static device array behind pt_decode_step_static             // decode-attention splits per (track, sequence, head)
 
 int pt_launch_gemm_generic(const pt_gemm_args& g, hipStream_t s);
 // Tuned launchers return 0 if they do not cover the problem (nothing launched), a negative PT_ERR_* code,

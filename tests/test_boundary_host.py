@@ -76,7 +76,8 @@ def test_arena_sizes():
     w, kv, ws = PB.pt_query_bytes(cfg)
     T, L, d, f, V = 4, 16, 1024, 4096, 32000
     params = T * L * (4 * d * d + 3 * d * f) + 2 * V * d
-    assert params * 2 <= w <= params * 2 + T * L * 2 * d * 4 + d * 4 + 64 * 1024
+    rope_table = 1024 * 64 * 4          # max_seq x head_dim/2 x (cos, sin), kept with the weights
+    assert params * 2 <= w <= params * 2 + T * L * 2 * d * 4 + d * 4 + rope_table + 64 * 1024
     tokens = 4 * 1024
     assert kv >= 2 * T * L * tokens * 16 * 64 * 2
     assert kv <= 2.2 * T * L * tokens * 16 * 64 * 2
