@@ -300,6 +300,58 @@ def run_cpu_baseline(I):
                       "equal layers, not a measurement of the full depth" % (t_layer, t_head, t_layer, t_head)}
 
 
+def run_ceilings(torch, I):
+    """Sustained rates of bare loops on this GPU (libpt_ceilings.so, include/pt_ceilings.h): the matrix-core loop
+    on all-zero operands and on operands distributed like the model's (N(0,1) activations against N(0,0.02)
+    weights), a streaming read, a streaming copy and an LDS read loop.  Context for the roofline fractions: the
+    published peaks are what a kernel is priced against, these are what the chip holds under load."""
+    import ctypes as C
+    import numpy as np
+    path = os.path.join(ROOT, "paper_2602_07306_amd", "libpt_ceilings.so")
+    if not os.path.exists(path):
+        raise ImportError("%s is missing: build it with `python -m paper_2602_07306_amd.build`" % path)
+    L = C.CDLL(path)
+    vp, i32, dbl = C.c_void_p, C.c_int32, C.c_double
+    L.pt_ceiling_mfma_bf16.argtypes = [vp, vp, i32, i32, i32, vp, C.POINTER(dbl)]
+    L.pt_ceiling_hbm_read.argtypes = [vp, C.c_size_t, vp, i32, vp, C.POINTER(dbl)]
+    L.pt_ceiling_hbm_copy.argtypes = [vp, vp, C.c_size_t, i32, vp, C.POINTER(dbl)]
+    L.pt_ceiling_lds_read.argtypes = [vp, i32, i32, i32, vp, dbl, C.POINTER(dbl), C.POINTER(dbl)]
+    st = torch.cuda.current_stream().cuda_stream
+    sink = torch.zeros(1 << 20, dtype=torch.float32, device="cuda")
+    x = I.make_hidden(9, 0, 8192, 1024).reshape(-1, 8, 8)        # 8 Mi values: 16-byte entries in groups of 8
+    x[:, 4:, :] *= 0.02                                          # entries 4..7 of a group feed the weight operand
+    ops = {"zeros": torch.zeros(1 << 23, dtype=torch.bfloat16, device="cuda"),
+           "model-like (N(0,1) x N(0,0.02))": torch.from_numpy(I.round_to_dtype(x.reshape(-1), I.PT_BF16)).cuda().to(torch.bfloat16)}
+    out = {"mfma_bf16_TFLOPs": {}, "published": {"mfma_bf16_TFLOPs": MFMA_BF16_PEAK_TFLOPS, "hbm_GBs": HBM_PEAK_GBS}}
+
+    def check(rc):
+        if rc != 0:
+            raise RuntimeError("libpt_ceilings call failed with %d" % rc)
+
+    for name, buf in ops.items():
+        for wps in (1, 2):
+            v = dbl()
+            check(L.pt_ceiling_mfma_bf16(buf.data_ptr(), sink.data_ptr(), wps, 40000, 5, st, C.byref(v)))
+            out["mfma_bf16_TFLOPs"]["%s, %d wavefront(s) per SIMD" % (name, wps)] = v.value
+            log("MFMA loop, %s, %d wavefront(s) per SIMD: %.0f TFLOP/s" % (name, wps, v.value))
+    nbytes = 8 << 30
+    src = torch.ones(nbytes // 4, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    v = dbl()
+    check(L.pt_ceiling_hbm_read(src.data_ptr(), nbytes, sink.data_ptr(), 10, st, C.byref(v)))
+    out["hbm_read_GBs"] = v.value
+    check(L.pt_ceiling_hbm_copy(src.data_ptr(), dst.data_ptr(), nbytes, 10, st, C.byref(v)))
+    out["hbm_copy_GBs_read_plus_write"] = v.value
+    log("streaming read %.0f GB/s, copy %.0f GB/s (read + write)" % (out["hbm_read_GBs"], v.value))
+    out["lds_read"] = {}
+    for wps in (1, 2, 4):
+        bpc, g = dbl(), dbl()
+        check(L.pt_ceiling_lds_read(sink.data_ptr(), wps, 20000, 3, st, 2.4, C.byref(bpc), C.byref(g)))
+        out["lds_read"]["%d wavefront(s) per SIMD" % wps] = {"bytes_per_clk_per_cu_at_2.4GHz": bpc.value, "GBs": g.value}
+        log("LDS ds_read_b128, %d wavefront(s) per SIMD: %.0f B/clk/CU at 2.4 GHz" % (wps, bpc.value))
+    return out
+
+
 def run_paper_sweep(args, torch, PB, I):
     """Latency-mode shape of the paper's serving tables (Section 3.3: batch 1, input lengths 1024 ... 63488,
     30B-shaped PT model, track block depth 1, 2, 4, 8, and the dense model of matched size) on one GPU with all 8
@@ -360,6 +412,8 @@ def main():
     ap.add_argument("--mid-decode-steps", type=int, default=128)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference for the HBM byte counters)")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="instead of the benchmark: sustained MFMA / HBM / LDS rates of bare loops (one JSON line)")
     ap.add_argument("--paper-sweep", action="store_true",
                     help="instead of the benchmark: TTFT / TPOT at batch 1 over input lengths for the "
                          "30B-shaped PT model at track block depth 2, 4, 8 (one JSON line)")
@@ -391,6 +445,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    if args.ceilings:
+        print(json.dumps({"ceilings": run_ceilings(torch, I), "n_gpus": 1, "dtype": "bf16", "data": "synthetic"}), flush=True)
+        return
     if args.paper_sweep:
         print(json.dumps({"paper_sweep": run_paper_sweep(args, torch, PB, I), "n_gpus": 1, "dtype": "bf16",
                           "data": "synthetic",

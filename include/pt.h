@@ -118,9 +118,27 @@ int pt_prefill(pt_handle* h, const int32_t* dev_tokens, const float* dev_hidden_
                int32_t hidden_tracks, int32_t B, int32_t S, int32_t logits_mode,
                float* dev_logits, float* dev_hidden_out);
 
+/* Prefill of a batch of sequences of different lengths (the throughput mode of Section 3.3, Tables 5 and 8:
+ * large batches of mixed input lengths).  Sequence b has host_lens[b] tokens, 1 <= host_lens[b] <= max_seq
+ * (host_lens is a HOST array of B entries).  Inputs and outputs are packed, sequence after sequence, without
+ * padding; n = host_lens[0] + ... + host_lens[B-1]:
+ *   dev_tokens     int32 [n]; or dev_hidden_in fp32 [hidden_tracks, n, d]
+ *   dev_logits     fp32 [B, V] (PT_LOGITS_LAST: each sequence's own last token) or [n, V] (PT_LOGITS_ALL)
+ *   dev_hidden_out fp32 [n, d]
+ *   taps set by pt_set_taps hold rows = n packed rows per merge.
+ * Every sequence sees only its own tokens (positions 0 .. len-1, causal).  Afterwards pt_decode_step appends
+ * one token to every sequence at that sequence's own position; pt_seq_lens reports the lengths and pt_seq_len
+ * the longest.  Inside, each sequence is padded to a multiple of 64 rows with zero-vector rows that run
+ * through the layers like appended tokens (the causal mask keeps them from every real position); their cache
+ * entries are overwritten by the decode steps that reach those positions.
+ * Errors as pt_prefill; INVALID_ARGUMENT for a length below 1, CAPACITY for one above max_seq. */
+int pt_prefill_ragged(pt_handle* h, const int32_t* dev_tokens, const float* dev_hidden_in, int32_t hidden_tracks,
+                      int32_t B, const int32_t* host_lens, int32_t logits_mode, float* dev_logits,
+                      float* dev_hidden_out);
+
 /* One KV-cached decode step: one new row per sequence at position len, appended to the cache.
  *   dev_tokens int32 [B] or dev_hidden_in fp32 [hidden_tracks, B, d]; B must equal the B of the
- *   preceding prefill.  dev_logits fp32 [B, V], dev_hidden_out fp32 [B, d], dev_argmax int32 [B]
+ *   preceding prefill.  After pt_prefill_ragged every sequence continues at its own length.  dev_logits fp32 [B, V], dev_hidden_out fp32 [B, d], dev_argmax int32 [B]
  *   (lowest id on ties); dev_logits and dev_hidden_out may each be NULL; dev_argmax may be NULL
  *   and, when given, needs dev_logits as well (the ids are taken from the stored logits).
  * Errors as pt_prefill; CAPACITY when len + 1 > max_seq; BAD_STATE before a prefill;
@@ -186,8 +204,11 @@ int pt_reset(pt_handle* h);
  * block: L/D per forward pass, against 2L sync points of tensor parallelism; Section 2.2). */
 int64_t pt_merge_count(const pt_handle* h);
 
-/* Current sequence length (identical for all sequences of the batch), or a negative error. */
+/* Current sequence length (after pt_prefill: identical for all sequences; after pt_prefill_ragged: the
+ * longest), or a negative error. */
 int32_t pt_seq_len(const pt_handle* h);
+/* Writes the current length of every live sequence to host_out (HOST array of at least B entries). */
+int pt_seq_lens(const pt_handle* h, int32_t* host_out);
 
 /* Per-kernel timing with HIP events on the handle's stream.  Kernel classes: */
 enum {
@@ -223,8 +244,11 @@ int pt_profile_paths(pt_handle* h, int32_t kernel_class, int64_t* counts);
  *                              of the MFMA GEMM wherever it fits the shape
  *   PT_TUNE_SKINNY_PLAN        value 0 (default): automatic; else 256 * workgroups per track +
  *                              K slices for the weight-streaming GEMM (where the shape allows)
+ *   PT_TUNE_FOLD_RMSNORM       value 1 (default): in prefill the RMSNorm between two GEMMs is folded into
+ *                              them (scaled bf16 copy and row sums from the producer's epilogue, row factor in
+ *                              the consumer's); 0: a separate RMSNorm kernel runs instead
  * Not thread-safe against concurrent forward calls.  Errors: INVALID_ARGUMENT (unknown knob). */
-enum { PT_TUNE_GEMM_TILE_CONFIG = 0, PT_TUNE_SKINNY_PLAN = 1 };
+enum { PT_TUNE_GEMM_TILE_CONFIG = 0, PT_TUNE_SKINNY_PLAN = 1, PT_TUNE_FOLD_RMSNORM = 2 };
 int pt_set_tuning(int32_t knob, int32_t value);
 
 const char* pt_last_error(void);

@@ -1,0 +1,47 @@
+/*
+ * pt_ceilings.h - C ABI of libpt_ceilings.so: bare loops that measure what one MI355X sustains, so that a
+ * kernel's rate can be read against a measured ceiling next to the published peak (bench.py --ceilings).
+ * Not part of the forward library; nothing here computes any step of the model.
+ *
+ * Every function takes caller-owned device buffers, enqueues `reps` timed launches on the given hipStream_t
+ * (NULL = default stream) bracketed by HIP events, synchronises and writes the mean rate of one launch.
+ * Returns 0 on success, a negative number on a HIP error or a bad argument.  Nothing is allocated.
+ */
+#ifndef PT_CEILINGS_H_
+#define PT_CEILINGS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Dense bf16 matrix-core loop: every wavefront keeps 16 accumulator tiles of 32x32 and issues
+ * v_mfma_f32_32x32x16_bf16 on register operands only (no memory traffic inside the loop), one workgroup of
+ * `waves_per_simd` * 4 wavefronts per compute unit (1 or 2).  dev_operands: at least 16 MiB of bf16 values the
+ * operands are taken from (all-zero data lets the chip hold its top clock; the model's kind of data does not);
+ * dev_sink: at least 4 MiB.  *tflops receives 2*32*32*16 FLOPs per instruction over the launch time. */
+int pt_ceiling_mfma_bf16(const void* dev_operands, void* dev_sink, int32_t waves_per_simd, int32_t iters,
+                         int32_t reps, void* hip_stream, double* tflops);
+
+/* Streaming read of `bytes` (a multiple of 1 MiB) from dev_src with 16-byte loads, every byte once;
+ * dev_sink: at least 4 MiB.  *gbs receives bytes / time in GB/s. */
+int pt_ceiling_hbm_read(const void* dev_src, size_t bytes, void* dev_sink, int32_t reps, void* hip_stream,
+                        double* gbs);
+
+/* Streaming copy of `bytes` (a multiple of 1 MiB) from dev_src to dev_dst; *gbs receives (read + written
+ * bytes) / time in GB/s. */
+int pt_ceiling_hbm_copy(const void* dev_src, void* dev_dst, size_t bytes, int32_t reps, void* hip_stream,
+                        double* gbs);
+
+/* LDS read loop: ds_read_b128 on conflict-free addresses, `waves_per_simd` * 4 wavefronts per compute unit
+ * (1, 2 or 4); *bytes_per_clk_cu receives bytes per compute unit per shader clock at clock_ghz (the caller's
+ * figure for the clock), *gbs the aggregate rate.  dev_sink: at least 4 MiB. */
+int pt_ceiling_lds_read(void* dev_sink, int32_t waves_per_simd, int32_t iters, int32_t reps, void* hip_stream,
+                        double clock_ghz, double* bytes_per_clk_cu, double* gbs);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PT_CEILINGS_H_ */

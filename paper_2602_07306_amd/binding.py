@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libpt.so")
 
 PT_LOGITS_NONE, PT_LOGITS_LAST, PT_LOGITS_ALL = 0, 1, 2
 PT_FAMILY_GENERIC, PT_FAMILY_COUNT = 0, 4
-PT_TUNE_GEMM_TILE_CONFIG, PT_TUNE_SKINNY_PLAN = 0, 1
+PT_TUNE_GEMM_TILE_CONFIG, PT_TUNE_SKINNY_PLAN, PT_TUNE_FOLD_RMSNORM = 0, 1, 2
 PT_PATH_AUTO, PT_PATH_GENERIC = 0, 1
 PT_W_EMBED, PT_W_HEAD, PT_W_Q, PT_W_K, PT_W_V, PT_W_O, PT_W_G, PT_W_U, PT_W_D, PT_W_G1, PT_W_G2, PT_W_GF = range(1, 13)
 WEIGHT_IDS = {"embed": PT_W_EMBED, "head": PT_W_HEAD, "wq": PT_W_Q, "wk": PT_W_K, "wv": PT_W_V,
@@ -33,7 +33,7 @@ EXPORTS = [
     "pt_query_bytes", "pt_create", "pt_destroy", "pt_init_weights", "pt_set_weight", "pt_get_weight",
     "pt_prefill", "pt_decode_step", "pt_track_merge", "pt_set_taps", "pt_set_kernel_path", "pt_reset",
     "pt_merge_count", "pt_seq_len", "pt_last_error", "pt_profile_enable", "pt_profile_read",
-    "pt_profile_reset", "pt_profile_paths", "pt_sync_status", "pt_set_tuning", "pt_argmax", "pt_decode_step_static",
+    "pt_profile_reset", "pt_profile_paths", "pt_sync_status", "pt_set_tuning", "pt_argmax", "pt_decode_step_static", "pt_prefill_ragged", "pt_seq_lens",
 ]
 
 KERNEL_CLASSES = ["embed", "rmsnorm", "gemm_qkv", "attn_prefill", "attn_decode", "gemm_out",
@@ -76,6 +76,8 @@ def lib() -> C.CDLL:
     L.pt_prefill.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp]
     L.pt_decode_step.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp]
     L.pt_decode_step_static.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp]
+    L.pt_prefill_ragged.argtypes = [vp, vp, vp, i32, i32, C.POINTER(i32), i32, vp, vp]
+    L.pt_seq_lens.argtypes = [vp, C.POINTER(i32)]
     L.pt_track_merge.argtypes = [C.POINTER(vp), i32, i64, i32, i32, C.c_float, vp, vp]
     L.pt_set_taps.argtypes = [vp, vp, vp]
     L.pt_set_kernel_path.argtypes = [vp, i32]
@@ -253,6 +255,33 @@ class PTModel:
         _check(lib().pt_prefill(self.h, _ptr(tokens), _ptr(hidden_in), ht, B, S, logits_mode,
                                 _ptr(logits), _ptr(hidden)))
         return logits, hidden
+
+    def pt_prefill_ragged(self, lens, tokens=None, hidden_in=None, logits_mode: int = PT_LOGITS_LAST,
+                          want_hidden: bool = False, logits_out=None):
+        """Prefill of sequences of different lengths.  lens: host list of B lengths; tokens: int32 device tensor
+        [sum(lens)] (packed); hidden_in: float32 device tensor [sum(lens), d] or [T, sum(lens), d].  Returns
+        (logits or None, hidden or None) as device tensors, packed the same way."""
+        cfg, torch = self.cfg, self.torch
+        B, n = len(lens), int(sum(lens))
+        ht = 1
+        if tokens is None:
+            ht = 1 if hidden_in.dim() == 2 else hidden_in.shape[0]
+            assert hidden_in.shape[-2] == n
+        else:
+            assert tokens.numel() == n
+        logits = logits_out
+        if logits_mode != PT_LOGITS_NONE and logits is None:
+            logits = torch.empty((B if logits_mode == PT_LOGITS_LAST else n, cfg.vocab), dtype=torch.float32, device=self.device)
+        hidden = torch.empty((n, cfg.d_model), dtype=torch.float32, device=self.device) if want_hidden else None
+        arr = (C.c_int32 * B)(*[int(x) for x in lens])
+        _check(lib().pt_prefill_ragged(self.h, _ptr(tokens), _ptr(hidden_in), ht, B, arr, logits_mode, _ptr(logits), _ptr(hidden)))
+        return logits, hidden
+
+    def pt_seq_lens(self):
+        B = 0
+        arr = (C.c_int32 * max(self.cfg.max_batch, 1))()
+        _check(lib().pt_seq_lens(self.h, arr))
+        return list(arr)
 
     def pt_decode_step(self, tokens=None, hidden_in=None, want_logits: bool = True,
                        want_hidden: bool = False, want_argmax: bool = False, logits_out=None,

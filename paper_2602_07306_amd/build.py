@@ -16,6 +16,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpt.so")
+CEILINGS_LIB = os.path.join(HERE, "libpt_ceilings.so")   # bench.py --ceilings only
+CEILINGS_SOURCES = ["bench_ceilings.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 SOURCES = [
@@ -71,12 +73,14 @@ def _compile(src: str, force: bool) -> str:
 def build(force: bool = False, jobs: int = 8) -> str:
     os.makedirs(BUILD, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
-        objs = list(ex.map(lambda s: _compile(s, force), SOURCES))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC",
-           "-Wl,--version-script=" + os.path.join(CSRC, "libpt.map"), "-o", LIB] + objs
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("link failed:\n%s\n%s" % (r.stdout, r.stderr))
+        all_objs = list(ex.map(lambda s: _compile(s, force), SOURCES + CEILINGS_SOURCES))
+    objs, cobjs = all_objs[:len(SOURCES)], all_objs[len(SOURCES):]
+    for lib, olist, extra in ((LIB, objs, ["-Wl,--version-script=" + os.path.join(CSRC, "libpt.map")]),
+                              (CEILINGS_LIB, cobjs, [])):
+        cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC"] + extra + ["-o", lib] + olist
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("link failed:\n%s\n%s" % (r.stdout, r.stderr))
     return LIB
 
 

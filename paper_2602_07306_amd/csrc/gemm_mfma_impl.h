@@ -30,6 +30,24 @@ __device__ __forceinline__ float silu_fast(float z) {
   return z * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * z));
 }
 
+// Sum of x over each group of LANES (16 or 32) consecutive lanes with data-parallel-primitive adds (no LDS
+// traffic): a prefix sum by doubling inside every row of 16 lanes, then lane 15's total carried into the
+// next row.  The total of a group is valid in its last lane only.
+template <int LANES>
+__device__ __forceinline__ float group_sum_last_lane(float x) {
+  static_assert(LANES == 16 || LANES == 32, "group width");
+  auto shr = [](float v, auto CTRL) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), decltype(CTRL)::value, 0xf, 0xf, true));
+  };
+  x += shr(x, std::integral_constant<int, 0x111>{});   // row_shr:1
+  x += shr(x, std::integral_constant<int, 0x112>{});   // row_shr:2
+  x += shr(x, std::integral_constant<int, 0x114>{});   // row_shr:4
+  x += shr(x, std::integral_constant<int, 0x118>{});   // row_shr:8
+  if constexpr (LANES == 32)                            // row_bcast:15 into rows 1 and 3
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x142, 0xa, 0xf, false));
+  return x;
+}
+
 #define GM_BK 64   // largest K step; K must be a multiple of 2 * GM_BK
 
 template <int N, typename F>
@@ -74,13 +92,18 @@ __device__ __forceinline__ tile_coord decode_tile(int id, int tiles_m, int tiles
 // 8*(v/4) + 4*(l/32) + v%4).  `stage` is the wavefront's private LDS patch (STAGE_ELEMS bf16 elements),
 // usable once the K loop is over; wave_m / wave_n are the first row / column of the wavefront's tile.
 // ------------------------------------------------------------------------------------------------
+// `rs`, when given, holds one factor per row of the wavefront's tile (LDS, index = row - wave_m): the folded
+// RMSNorm scale that the QKV and SwiGLU epilogues apply to the accumulators of that row.
 template <int MI, int NI, int EPI, bool STAGED, int STAGE_ELEMS>
 __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&acc)[MI][NI], bf16_t* stage, int b,
-                                              int wave_m, int wave_n, int lane) {
+                                              int wave_m, int wave_n, int lane, const float* rs) {
   constexpr int TN = NI * 32;
   const int col_l = lane & 31;
   const int row_l = 4 * (lane >> 5);
   (void)stage;
+  // factor of the row that register v of block mi holds
+  auto row_scale = [&](int mi, int v) { return rs ? rs[mi * 32 + 8 * (v >> 2) + row_l + (v & 3)] : 1.0f; };
+  (void)row_scale;
   if constexpr (EPI == EPI_STORE_F32 || EPI == EPI_RESIDUAL) {
     float* out = g.out + b * g.out_bstride;
     const float* res = EPI == EPI_RESIDUAL ? g.res + b * g.res_bstride : nullptr;
@@ -106,6 +129,10 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
         });
         const int c4 = (lane % LPR) * 4, n = wave_n + c4;
         constexpr int BATCH = ITS < 8 ? ITS : 8;
+        // folded RMSNorm, producer side: bf16(h * gain) and the row's sum of squares over this wavefront's columns
+        const bool fold = EPI == EPI_RESIDUAL && g.nf_out != nullptr;
+        f32x4_t gain4 = {1.f, 1.f, 1.f, 1.f};
+        if (fold && n < g.N) gain4 = *(const f32x4_t*)(g.nf_gain + b * g.nf_gain_bstride + n);
         static_for<ITS / BATCH>([&](auto B_) {
           constexpr int it0 = decltype(B_)::value * BATCH;
           f32x4_t r4[BATCH];
@@ -123,6 +150,21 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
             f32x4_t x = *(const f32x4_t*)(fst + row_in * FPITCH + c4);
             if constexpr (EPI == EPI_RESIDUAL) x += r4[i];
             if (m < g.M && n < g.N) *(f32x4_t*)(out + (int64_t)m * g.ldo + n) = x;
+            if constexpr (EPI == EPI_RESIDUAL) {
+              if (fold) {
+                float ss = n < g.N ? x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w : 0.f;
+                ss = group_sum_last_lane<LPR>(ss);
+                if (m < g.M) {
+                  if (n < g.N) {
+                    uint2 pk;
+                    pk.x = pack_bf16x2(x.x * gain4.x, x.y * gain4.y);
+                    pk.y = pack_bf16x2(x.z * gain4.z, x.w * gain4.w);
+                    *(uint2*)((bf16_t*)g.nf_out + b * g.nf_out_bstride + (int64_t)m * g.N + n) = pk;
+                  }
+                  if (lane % LPR == LPR - 1) g.nf_ss[b * g.nf_ss_bstride + (int64_t)m * g.nf_parts + wave_n / TN] = ss;
+                }
+              }
+            }
           });
         });
       });
@@ -159,9 +201,10 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
         static_for<16>([&](auto V_) {
           constexpr int v = decltype(V_)::value;
           const int row_in = 8 * (v >> 2) + row_l + (v & 3);
+          const float rsc = row_scale(mi, v);
           static_for<NI / 2>([&](auto P_) {
             constexpr int pp = decltype(P_)::value;
-            stage[row_in * PITCH + 32 * pp + col_l] = f32_to_bf16(silu_fast(acc[mi][2 * pp][v]) * acc[mi][2 * pp + 1][v]);
+            stage[row_in * PITCH + 32 * pp + col_l] = f32_to_bf16(silu_fast(rsc * acc[mi][2 * pp][v]) * (rsc * acc[mi][2 * pp + 1][v]));
           });
           if constexpr ((v & 3) == 3) __builtin_amdgcn_sched_barrier(0);   // bounds the scheduler's window (register pressure)
         });
@@ -184,7 +227,8 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
 #pragma unroll
             for (int ni = 0; ni < NI; ni += 2) {
               const int j = ((wave_n + ni * 32) >> 1) + col_l;   // (phys/64)*32 + lane column
-              if (2 * j < g.N) o[(int64_t)m * ldo + j] = f32_to_bf16(silu_fast(acc[mi][ni][v]) * acc[mi][ni + 1][v]);
+              const float rsc = row_scale(mi, v);
+              if (2 * j < g.N) o[(int64_t)m * ldo + j] = f32_to_bf16(silu_fast(rsc * acc[mi][ni][v]) * (rsc * acc[mi][ni + 1][v]));
             }
           }
         }
@@ -193,7 +237,8 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
     const int hd = g.hd, half = hd >> 1, hq = g.H * hd, hk = g.Hkv * hd;
     const bool wide = hd == 128;     // partner tile distance (hd/2)/32: 1 for hd 64, 2 for hd 128
     const int hd_sh = wide ? 7 : 6;  // hd is 64 or 128 here: shifts and masks instead of runtime divisions
-    const bool s4 = (g.S & 3) == 0;  // 4 consecutive rows of a register group lie in one sequence
+    // 4 consecutive rows of a register group lie in one sequence, at consecutive positions
+    const bool s4 = g.row_map ? g.row_blocks != 0 : (g.S & 3) == 0;
     constexpr int QPITCH = TN + 8;   // bf16 elements per staged row of q / k
     constexpr int VPITCH = 32 + 8;   // bf16 elements per staged V^T row (32 positions)
     constexpr bool CAN_STAGE = STAGED && 32 * QPITCH <= STAGE_ELEMS && TN * VPITCH <= STAGE_ELEMS;
@@ -203,7 +248,7 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
       // time go through the wavefront's LDS patch.  q and k are rotated in registers, staged row-major
       // and leave as 16-byte row pieces; v is staged transposed and leaves as 16-byte pieces of V^T
       // rows (8 consecutive positions of one head-dim index).
-      if ((g.S & 31) == 0 && (g.pos0 & 7) == 0 && wave_n < g.N) {
+      if ((g.row_map ? g.row_blocks != 0 : (g.S & 31) == 0) && (g.pos0 & 7) == 0 && wave_n < g.N) {
         staged_done = true;
         const bool is_qk = wave_n < hq + hk, is_q = wave_n < hq;
         // cos/sin of (position, column): the table is read once per 32-row block, for the lane's first row;
@@ -221,7 +266,7 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
           static_for<MI>([&](auto MI_) {
             constexpr int mi = decltype(MI_)::value;
             const int mrow0 = min(wave_m + mi * 32, g.M - 32);
-            const int seq = mrow0 / g.S, pos0b = g.pos0 + (mrow0 - seq * g.S);
+            const int pos0b = gemm_row_pos(g, mrow0).pos;
             const float2* rp = tab + (int64_t)(pos0b + row_l) * half;
             cs_base[mi][0] = rp[0];
             if (wide) cs_base[mi][1] = rp[32];
@@ -231,12 +276,14 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
           constexpr int mi = decltype(MI_)::value;
           const int mrow0 = wave_m + mi * 32;           // first row of the block
           if (mrow0 < g.M) {
-            const int seq = mrow0 / g.S, pos0b = g.pos0 + (mrow0 - seq * g.S);
+            const pt_rowpos rp0 = gemm_row_pos(g, mrow0);
+            const int seq = rp0.seq, pos0b = rp0.pos;
             if (is_qk) {
               float2 cs_cur[2] = {cs_base[mi][0], wide ? cs_base[mi][1] : cs_base[mi][0]};
               static_for<16>([&](auto V_) {
                 constexpr int v = decltype(V_)::value;
                 const int row_in = 8 * (v >> 2) + row_l + (v & 3);
+                const float rsc = row_scale(mi, v);
                 if constexpr (v > 0) {
 #pragma unroll
                   for (int w = 0; w < 2; ++w) {
@@ -253,8 +300,8 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
                   const int jb = (wave_n + ni * 32) & (hd - 1);   // wave-uniform
                   if (jb < half) {
                     const float2 cs = jb == 0 ? cs_cur[0] : cs_cur[1];
-                    const float lo = acc[mi][ni][v];
-                    const float hi = wide ? acc[mi][p2][v] : acc[mi][p1][v];
+                    const float lo = rsc * acc[mi][ni][v];
+                    const float hi = rsc * (wide ? acc[mi][p2][v] : acc[mi][p1][v]);
                     stage[row_in * QPITCH + ni * 32 + col_l] = f32_to_bf16(lo * cs.x - hi * cs.y);
                     stage[row_in * QPITCH + ni * 32 + col_l + half] = f32_to_bf16(hi * cs.x + lo * cs.y);
                   }
@@ -281,8 +328,8 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
                 static_for<NI>([&](auto NI_) {
                   constexpr int ni = decltype(NI_)::value;
                   uint2 pk;
-                  pk.x = pack_bf16x2(acc[mi][ni][vg * 4 + 0], acc[mi][ni][vg * 4 + 1]);
-                  pk.y = pack_bf16x2(acc[mi][ni][vg * 4 + 2], acc[mi][ni][vg * 4 + 3]);
+                  pk.x = pack_bf16x2(row_scale(mi, vg * 4 + 0) * acc[mi][ni][vg * 4 + 0], row_scale(mi, vg * 4 + 1) * acc[mi][ni][vg * 4 + 1]);
+                  pk.y = pack_bf16x2(row_scale(mi, vg * 4 + 2) * acc[mi][ni][vg * 4 + 2], row_scale(mi, vg * 4 + 3) * acc[mi][ni][vg * 4 + 3]);
                   *(uint2*)(stage + (ni * 32 + col_l) * VPITCH + 8 * vg + row_l) = pk;
                 });
               });
@@ -309,8 +356,9 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
         const int mb = wave_m + mi * 32 + 8 * vg + row_l;   // rows mb .. mb+3
         int seq4 = 0, pos4 = 0;
         if (s4) {
-          seq4 = mb / g.S;
-          pos4 = g.pos0 + (mb - seq4 * g.S);
+          const pt_rowpos rp4 = gemm_row_pos(g, min(mb, g.M - 1));
+          seq4 = rp4.seq;
+          pos4 = rp4.pos;
         }
         static_for<NI>([&](auto NI_) {
           constexpr int ni = decltype(NI_)::value;
@@ -329,10 +377,11 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
                 if (m < g.M) {
                   int seq, pos;
                   if (s4) { seq = seq4; pos = pos4 + r; }
-                  else { seq = m / g.S; pos = g.pos0 + (m - seq * g.S); }
+                  else { const pt_rowpos rpm = gemm_row_pos(g, m); seq = rpm.seq; pos = rpm.pos; }
                   const float2 cs = ((const float2*)g.rope)[(int64_t)pos * half + j];
-                  const float lo = acc[mi][ni][vg * 4 + r];
-                  const float hi = wide ? acc[mi][p2][vg * 4 + r] : acc[mi][p1][vg * 4 + r];
+                  const float rsc = row_scale(mi, vg * 4 + r);
+                  const float lo = rsc * acc[mi][ni][vg * 4 + r];
+                  const float hi = rsc * (wide ? acc[mi][p2][vg * 4 + r] : acc[mi][p1][vg * 4 + r]);
                   const bf16_t rlo = f32_to_bf16(lo * cs.x - hi * cs.y);
                   const bf16_t rhi = f32_to_bf16(hi * cs.x + lo * cs.y);
                   if (is_q) {
@@ -356,17 +405,18 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
               const int64_t hidx = b * g.kv_bstride + seq4 * g.kv_seq_stride + head;
               bf16_t* v = (bf16_t*)g.vc + hidx * ((int64_t)hd * g.s_pad) + (int64_t)j * g.s_pad + pos4;
               uint2 pk;
-              pk.x = pack_bf16x2(acc[mi][ni][vg * 4 + 0], acc[mi][ni][vg * 4 + 1]);
-              pk.y = pack_bf16x2(acc[mi][ni][vg * 4 + 2], acc[mi][ni][vg * 4 + 3]);
+              pk.x = pack_bf16x2(row_scale(mi, vg * 4 + 0) * acc[mi][ni][vg * 4 + 0], row_scale(mi, vg * 4 + 1) * acc[mi][ni][vg * 4 + 1]);
+              pk.y = pack_bf16x2(row_scale(mi, vg * 4 + 2) * acc[mi][ni][vg * 4 + 2], row_scale(mi, vg * 4 + 3) * acc[mi][ni][vg * 4 + 3]);
               *(uint2*)v = pk;
             } else {
               static_for<4>([&](auto R_) {
                 constexpr int r = decltype(R_)::value;
                 const int m = mb + r;
                 if (m < g.M) {
-                  const int seq = m / g.S, pos = g.pos0 + (m - seq * g.S);
+                  const pt_rowpos rpm = gemm_row_pos(g, m);
+                  const int seq = rpm.seq, pos = rpm.pos;
                   const int64_t hidx = b * g.kv_bstride + seq * g.kv_seq_stride + head;
-                  ((bf16_t*)g.vc)[hidx * ((int64_t)hd * g.s_pad) + (int64_t)j * g.s_pad + pos] = f32_to_bf16(acc[mi][ni][vg * 4 + r]);
+                  ((bf16_t*)g.vc)[hidx * ((int64_t)hd * g.s_pad) + (int64_t)j * g.s_pad + pos] = f32_to_bf16(row_scale(mi, vg * 4 + r) * acc[mi][ni][vg * 4 + r]);
                 }
               });
             }
@@ -397,6 +447,14 @@ gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
   const int wm = wave / WN, wn = wave % WN;
   const tile_coord tc = decode_tile(logical_tile(blockIdx.x, gridDim.x), tiles_m, tiles_n);
   const int m0 = tc.tm * BM, n0 = tc.tn * BN, b = tc.b;
+
+  // folded RMSNorm, consumer side: one factor per tile row (1/rms of the row, from pt_launch_row_inv_rms).  The
+  // load is issued here and parked in LDS only after the K loop, so nothing waits for it.
+  __shared__ float rs_inv[BM];
+  const bool has_rs = (EPI == EPI_QKV || EPI == EPI_SWIGLU) && g.rs_inv != nullptr;
+  static_assert(BM <= NT, "one factor per thread");
+  float rs_mine = 1.0f;
+  if (has_rs && tid < BM) rs_mine = g.rs_inv[b * g.rs_bstride + min(m0 + tid, g.M - 1)];
 
   // global -> register staging: chunk id = tid + i*NT; row = id/CPR, 16-byte chunk = id%CPR.
   // Rows of one thread are NT/CPR apart, a multiple of 16, so they share the swizzle and the LDS
@@ -435,9 +493,11 @@ gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
   }
 
   // Software pipeline (K step = 64).  In every iteration the MFMAs run out of LDS buffer `cur` while
-  //   sub-steps 0,1: the next K step (staging set cur^1, loaded two iterations ago) is stored into the
-  //                  other LDS buffer,
-  //   sub-steps 2,3: the K step three ahead is loaded from global memory into the set just freed,
+  //   sub-steps 0..2: the next K step (staging set cur^1, loaded two iterations ago) is stored into the
+  //                   other LDS buffer chunk by chunk, and every chunk's register is refilled right away
+  //                   from global memory with the K step three ahead: a load has two whole iterations to
+  //                   arrive, which matters because about a fifth of them miss the XCD's L2 (measured:
+  //                   +2.4 % on model data, +4.8 % on zeros over refilling in sub-steps 2 and 3),
   //   every sub-step: the operand fragments of the next sub-step are read from LDS,
   // and every memory instruction is issued between two MFMAs, so no queue sees a burst.  The one
   // barrier of the iteration sits in front of sub-step 3: after it the first fragments of the next
@@ -468,8 +528,8 @@ gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
   constexpr int NM = MI * NI;                  // MFMAs per sub-step
   constexpr int FR = MI + NI;                  // fragment reads per sub-step
   constexpr int EX = A_CH + B_CH;              // staging chunks per K step
-  constexpr int HS = SS / 2;                   // sub-steps that store, then as many that load
-  constexpr int EXH = (EX + HS - 1) / HS;      // staging chunks handled per sub-step
+  constexpr int NS = SS - 1;                   // sub-steps in front of the barrier: each parks its share of the staging chunks and refills them
+  constexpr int EXS = (EX + NS - 1) / NS;      // staging chunks handled per such sub-step
 
   f32x16_t acc[MI][NI];
 
@@ -484,7 +544,7 @@ gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
     static_for<SS>([&](auto KK) {
       constexpr int kk = decltype(KK)::value;
       constexpr int fb = (kk + 1) & 1;                  // fragment buffer being filled
-      constexpr int R = FR + EXH;                       // memory instructions of this sub-step
+      constexpr int R = kk < NS ? FR + 2 * EXS : FR;   // memory instructions of this sub-step
       if constexpr (kk == SS - 1) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
       static_for<NM>([&](auto J) {
         constexpr int j = decltype(J)::value;
@@ -500,9 +560,9 @@ gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
             const bf16_t* src = kk == SS - 1 ? Bn + b_fr[0] : Bc + b_fr[(kk + 1) % SS];
             bfr[fb][r - MI] = *(const bf16x8_t*)(src + (r - MI) * 32 * BK);
           } else {
-            constexpr int e = (kk % HS) * EXH + (r - FR);   // staging chunk
-            if constexpr (e < EX) {
-              if constexpr (kk < HS) {
+            constexpr int e = kk * EXS + (r - FR) / 2;   // staging chunk: parked, then refilled right away
+            if constexpr (e < EX && kk < NS) {
+              if constexpr ((r - FR) % 2 == 0) {
                 if constexpr (e < A_CH) *(u32x4_t*)(An + st_dst + e * ST_STRIDE) = a_reg[wset][e];
                 else *(u32x4_t*)(Bn + st_dst + (e - A_CH) * ST_STRIDE) = w_reg[wset][e - A_CH];
               } else {
@@ -527,6 +587,7 @@ gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
     iteration(std::integral_constant<int, 0>{}, kt);
     iteration(std::integral_constant<int, 1>{}, kt + 1);
   }
+  if (has_rs && tid < BM) rs_inv[tid] = rs_mine;
   __syncthreads();   // LDS is free for the staged epilogues
 
   // ------------------------------------------------------------------ epilogue
@@ -538,7 +599,7 @@ gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
   const int wave_n = n0 + wn * TN;
   const int wave_m = m0 + wm * TM;
 
-  gemm_epilogue<MI, NI, EPI, STAGED, STAGE_ELEMS>(g, acc, stage, b, wave_m, wave_n, lane);
+  gemm_epilogue<MI, NI, EPI, STAGED, STAGE_ELEMS>(g, acc, stage, b, wave_m, wave_n, lane, has_rs ? rs_inv + wm * TM : nullptr);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -567,6 +628,14 @@ gemm_dl_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
   const tile_coord tc = decode_tile(logical_tile(blockIdx.x, gridDim.x), tiles_m, tiles_n);
   const int m0 = tc.tm * BM, n0 = tc.tn * BN, b = tc.b;
   const int KT = g.K / BK;   // multiple of 4
+
+  // folded RMSNorm, consumer side: one factor per tile row (1/rms of the row, from pt_launch_row_inv_rms).  The
+  // load is issued here and parked in LDS only after the K loop, so nothing waits for it.
+  __shared__ float rs_inv[BM];
+  const bool has_rs = (EPI == EPI_QKV || EPI == EPI_SWIGLU) && g.rs_inv != nullptr;
+  static_assert(BM <= (NW * 64), "one factor per thread");
+  float rs_mine = 1.0f;
+  if (has_rs && tid < BM) rs_mine = g.rs_inv[b * g.rs_bstride + min(m0 + tid, g.M - 1)];
 
   // direct loads: group grp covers tile rows grp*16 .. +15; this lane fetches row L/4, logical chunk (L%4)^swz
   const int rr = lane >> 2, pc = lane & 3;
@@ -666,12 +735,13 @@ gemm_dl_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
     iteration(std::integral_constant<int, 2>{}, kt + 2);
     iteration(std::integral_constant<int, 3>{}, kt + 3);
   }
+  if (has_rs && tid < BM) rs_inv[tid] = rs_mine;
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");   // no load may still be landing in LDS
 
   constexpr bool STAGED = true;
   constexpr int STAGE_ELEMS = NSTG * STG / NW;   // per wavefront
   bf16_t* stage = lds + wave * STAGE_ELEMS;
-  gemm_epilogue<MI, NI, EPI, STAGED, STAGE_ELEMS>(g, acc, stage, b, m0 + wm * TM, n0 + wn * TN, lane);
+  gemm_epilogue<MI, NI, EPI, STAGED, STAGE_ELEMS>(g, acc, stage, b, m0 + wm * TM, n0 + wn * TN, lane, has_rs ? rs_inv + wm * TM : nullptr);
 }
 
 template <int BM, int BN, int WM, int WN, int EPI>

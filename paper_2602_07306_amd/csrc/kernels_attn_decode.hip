@@ -27,7 +27,7 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(const pt_attn_args a, 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int split = blockIdx.x, head = blockIdx.y;
   const int t = blockIdx.z / a.B, seq = blockIdx.z - t * a.B;
-  const int nkeys = a.pos0 + 1;
+  const int nkeys = (a.row_map ? a.row_map[seq].y : a.pos0) + 1;   // ragged batch: this sequence's own length
   const int k0 = split * keys_per_split;
   const int k1 = min(nkeys, k0 + keys_per_split);
   const int n = k1 - k0;
@@ -228,9 +228,20 @@ __global__ void __launch_bounds__(256) attn_decode_tiled_kernel(const pt_attn_ar
   const int split = blockIdx.x, kvh = blockIdx.y;
   const int t = blockIdx.z / a.B, seq = blockIdx.z - t * a.B;
   const int G = a.H / a.Hkv;
-  const int nkeys = a.pos0 + 1;
+  const int nkeys = (a.row_map ? a.row_map[seq].y : a.pos0) + 1;   // ragged batch: this sequence's own length
   const int k0 = split * keys_per_split;
   const int k1 = min(nkeys, k0 + keys_per_split);
+  if (k0 >= nkeys) {
+    // a shorter sequence of a ragged batch has no key in this range: the neutral element of the combine
+    // (whole workgroup, ahead of every barrier; split 0 is never empty)
+    for (int e = tid; e < HD * G; e += 256) {
+      const int g = e / HD, r = e - g * HD;
+      float* part = a.partials + (((int64_t)blockIdx.z * a.H + kvh * G + g) * nsplit + split) * (HD + 2);
+      if (r == 0) { part[0] = -INFINITY; part[1] = 0.f; }
+      part[2 + r] = 0.f;
+    }
+    return;
+  }
   const int64_t hidx = t * a.kv_bstride + seq * a.kv_seq_stride + kvh;
   const char* K = (const char*)((const bf16_t*)a.kc + hidx * a.kv_head_elems);
   const char* Vt = (const char*)((const bf16_t*)a.vc + hidx * ((int64_t)HD * a.s_pad));
@@ -409,7 +420,7 @@ int pt_launch_attn_decode(const pt_attn_args& a, hipStream_t s) {
   if ((a.q_bstride & 7) || (((uintptr_t)a.q | (uintptr_t)a.kc | (uintptr_t)a.vc) & 15)) return 0;
   const int64_t z = (int64_t)a.n_tracks * a.B;
   if (z > 65535 || a.H > 65535) return 0;
-  const int nkeys = a.pos0 + 1;
+  const int nkeys = (a.row_map ? a.max_pos : a.pos0) + 1;   // the longest sequence decides the ranges
   const int G = a.H / a.Hkv;
   if (G <= DEC_GMAX && (a.s_pad & 7) == 0) {   // measured at least as fast as the VALU kernel for G = 1 too
     const int64_t gbase = z * a.Hkv;

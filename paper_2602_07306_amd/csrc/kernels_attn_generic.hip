@@ -9,7 +9,15 @@ __global__ void __launch_bounds__(64) attn_generic_kernel(pt_attn_args a) {
   const int lane = threadIdx.x;
   const int m = blockIdx.x, head = blockIdx.y, t = blockIdx.z;
   const int hd = a.hd;
-  const int seq = m / a.S, pos = a.pos0 + (m - seq * a.S);
+  int seq, pos;
+  if (a.row_map) {   // ragged batch: decode rows are indexed by sequence, prefill rows by packed row
+    const int2 e = a.row_map[m];
+    seq = e.x;
+    pos = e.y;
+  } else {
+    seq = m / a.S;
+    pos = a.pos0 + (m - seq * a.S);
+  }
   const int nkeys = pos + 1;
   const int kvh = head / (a.H / a.Hkv);
   const int64_t hidx = t * a.kv_bstride + seq * a.kv_seq_stride + kvh;
@@ -58,7 +66,7 @@ __global__ void __launch_bounds__(64) attn_generic_kernel(pt_attn_args a) {
 }
 
 int pt_launch_attn_generic(const pt_attn_args& a, hipStream_t s) {
-  const int64_t rows = (int64_t)a.B * a.S;
+  const int64_t rows = a.seq_info ? a.rows : (int64_t)a.B * a.S;
   if (rows <= 0) return PT_OK;
   if (a.hd > 256) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "head_dim > 256");
   dim3 grid((unsigned)rows, (unsigned)a.H, (unsigned)a.n_tracks);

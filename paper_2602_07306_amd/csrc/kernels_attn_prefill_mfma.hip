@@ -179,11 +179,20 @@ __global__ void __launch_bounds__(256, HD == 64 ? 3 : 2) attn_prefill_lds_kernel
   const int tb = combo / a.H;
   const int t = tb / a.B, seq = tb - t * a.B;
   const int kvh = head / (a.H / a.Hkv);
+  // rows of this sequence: S of them from row seq * S, or (ragged batch) its padded length from its first packed row
+  int64_t row0 = (int64_t)seq * a.S;
+  int slen = a.S;
+  if (a.seq_info) {
+    const int4 si = a.seq_info[seq];
+    row0 = si.x;
+    slen = si.y;
+    if (qb * 128 >= slen) return;         // a shorter sequence has fewer query blocks (whole workgroup)
+  }
   const int64_t hidx = t * a.kv_bstride + seq * a.kv_seq_stride + kvh;
   const bf16_t* K = (const bf16_t*)a.kc + hidx * a.kv_head_elems;
   const bf16_t* Vt = (const bf16_t*)a.vc + hidx * ((int64_t)HD * a.s_pad);
-  const bool active = q0 < a.S;            // the last workgroup of a sequence may be partly empty
-  const int64_t row = (int64_t)seq * a.S + min(q0 + l32, a.S - 1);
+  const bool active = q0 < slen;           // the last workgroup of a sequence may be partly empty
+  const int64_t row = row0 + min(q0 + l32, slen - 1);
   const int64_t qoff = t * a.q_bstride + row * (a.H * HD) + head * HD;
 
   bf16x8_t qf[KS];
@@ -230,7 +239,7 @@ __global__ void __launch_bounds__(256, HD == 64 ? 3 : 2) attn_prefill_lds_kernel
     for (int v = 0; v < 16; ++v) oacc[hb][v] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;   // running max of the raw scores, running sum
 
-  const int ntiles = min((qb * 128 + 128), a.S) / 64;      // key tiles this workgroup walks
+  const int ntiles = min((qb * 128 + 128), slen) / 64;     // key tiles this workgroup walks
 #pragma unroll
   for (int i = 0; i < KCH; ++i) k_reg[i] = *(const u32x4_t*)(k_src[i]);
 #pragma unroll
@@ -344,7 +353,7 @@ __global__ void __launch_bounds__(256, HD == 64 ? 3 : 2) attn_prefill_lds_kernel
 
 template <int HD>
 static int launch_lds(const pt_attn_args& a, hipStream_t s) {
-  const int nqb = (a.S + 127) / 128;
+  const int nqb = ((a.seq_info ? a.max_plen : a.S) + 127) / 128;
   const int64_t total = (int64_t)a.n_tracks * a.B * a.H * nqb;
   if (total > 0x7fffffff) return 0;
   const dim3 grid((unsigned)total);
@@ -359,6 +368,10 @@ static int launch_lds(const pt_attn_args& a, hipStream_t s) {
 int pt_launch_attn_prefill_mfma(const pt_attn_args& a, hipStream_t s) {
   if (a.dtype != PT_BF16 || a.pos0 != 0) return 0;
   if (a.hd != 64 && a.hd != 128) return 0;
+  if (a.seq_info) {   // ragged batch: every padded length is a multiple of 64, which the LDS-tiled kernel walks
+    if ((a.s_pad & 7) || (a.q_bstride & 7) || (((uintptr_t)a.q | (uintptr_t)a.o | (uintptr_t)a.kc | (uintptr_t)a.vc) & 15)) return 0;
+    return a.hd == 64 ? launch_lds<64>(a, s) : launch_lds<128>(a, s);
+  }
   if (a.S < 32 || a.S % 32) return 0;
   if ((a.q_bstride & 7) || (((uintptr_t)a.q | (uintptr_t)a.o | (uintptr_t)a.kc | (uintptr_t)a.vc) & 15)) return 0;
   const int64_t z = (int64_t)a.n_tracks * a.B;

@@ -34,6 +34,130 @@ int pt_launch_embed(const void* embed, int32_t dtype, const int32_t* tokens, int
 }
 
 // ------------------------------------------------------------------------------------------
+// Ragged batches (sequences of different lengths in one prefill).  Inside the library the rows of a ragged
+// prefill are packed sequence after sequence, each padded to a multiple of 64 rows; padding rows carry the zero
+// vector as their input and run through the layers like appended tokens, which the causal mask keeps away from
+// every real position.  seq_info[b] = (first packed row, padded length, length, first token of the packed input).
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) embed_ragged_kernel(const T* __restrict__ E, const int32_t* __restrict__ tok,
+                                                           const int2* __restrict__ row_map, const int4* __restrict__ seq_info,
+                                                           int64_t rows, int32_t d, int32_t vocab, float* __restrict__ h,
+                                                           int32_t* __restrict__ flag) {
+  const int64_t row = blockIdx.x;
+  if (row >= rows) return;
+  const int2 rp = row_map[row];
+  const int4 si = seq_info[rp.x];
+  float* dst = h + row * d;
+  if (rp.y >= si.z) {
+    for (int c = threadIdx.x; c < d; c += 256) dst[c] = 0.f;
+    return;
+  }
+  int32_t id = tok[si.w + rp.y];
+  if (id < 0 || id >= vocab) {
+    if (threadIdx.x == 0 && flag) atomicOr(flag, 1);
+    id = id < 0 ? 0 : vocab - 1;
+  }
+  const T* src = E + (int64_t)id * d;
+  for (int c = threadIdx.x; c < d; c += 256) dst[c] = elem<T>::ld(src + c);
+}
+
+int pt_launch_embed_ragged(const void* embed, int32_t dtype, const int32_t* tokens, const int2* row_map,
+                           const int4* seq_info, int64_t rows, int32_t d, int32_t vocab, float* h, int32_t* flag,
+                           hipStream_t s) {
+  if (rows <= 0) return PT_OK;
+  if (dtype == PT_F32)
+    hipLaunchKernelGGL(embed_ragged_kernel<float>, dim3((unsigned)rows), dim3(256), 0, s, (const float*)embed, tokens, row_map, seq_info, rows, d, vocab, h, flag);
+  else
+    hipLaunchKernelGGL(embed_ragged_kernel<bf16_t>, dim3((unsigned)rows), dim3(256), 0, s, (const bf16_t*)embed, tokens, row_map, seq_info, rows, d, vocab, h, flag);
+  PT_HIP_CHECK(hipGetLastError());
+  return PT_OK;
+}
+
+__global__ void __launch_bounds__(256) scatter_rows_kernel(const float* __restrict__ src, int64_t src_bstride,
+                                                           const int2* __restrict__ row_map, const int4* __restrict__ seq_info,
+                                                           int32_t d, float* __restrict__ dst, int64_t dst_bstride) {
+  const int64_t row = blockIdx.x;
+  const int b = blockIdx.y;
+  const int2 rp = row_map[row];
+  const int4 si = seq_info[rp.x];
+  float4* o = (float4*)(dst + b * dst_bstride + row * d);
+  if (rp.y >= si.z) {
+    for (int c = threadIdx.x; c < (d >> 2); c += 256) o[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+    return;
+  }
+  const float4* in = (const float4*)(src + b * src_bstride + (int64_t)(si.w + rp.y) * d);
+  for (int c = threadIdx.x; c < (d >> 2); c += 256) o[c] = in[c];
+}
+
+int pt_launch_scatter_rows(const float* src, int64_t src_bstride, const int2* row_map, const int4* seq_info,
+                           int64_t rows, int32_t d, int32_t batch, float* dst, int64_t dst_bstride, hipStream_t s) {
+  if (rows <= 0 || batch <= 0) return PT_OK;
+  hipLaunchKernelGGL(scatter_rows_kernel, dim3((unsigned)rows, (unsigned)batch), dim3(256), 0, s, src, src_bstride, row_map,
+                     seq_info, d, dst, dst_bstride);
+  PT_HIP_CHECK(hipGetLastError());
+  return PT_OK;
+}
+
+__global__ void __launch_bounds__(256) gather_rows_kernel(const float* __restrict__ src, const int32_t* __restrict__ idx,
+                                                          int32_t d, float* __restrict__ dst) {
+  const int64_t i = blockIdx.x;
+  const float4* in = (const float4*)(src + (int64_t)idx[i] * d);
+  float4* o = (float4*)(dst + i * d);
+  for (int c = threadIdx.x; c < (d >> 2); c += 256) o[c] = in[c];
+}
+
+int pt_launch_gather_rows(const float* src, const int32_t* idx, int64_t n, int32_t d, float* dst, hipStream_t s) {
+  if (n <= 0) return PT_OK;
+  hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)n), dim3(256), 0, s, src, idx, d, dst);
+  PT_HIP_CHECK(hipGetLastError());
+  return PT_OK;
+}
+
+// One workgroup per sequence: its packed rows get (sequence, position), its real tokens their packed row.
+__global__ void __launch_bounds__(256) ragged_maps_kernel(const int4* __restrict__ seq_info, int2* __restrict__ row_map,
+                                                          int32_t* __restrict__ valid, int32_t* __restrict__ last) {
+  const int b = blockIdx.x;
+  const int4 si = seq_info[b];
+  for (int p = threadIdx.x; p < si.y; p += 256) row_map[si.x + p] = make_int2(b, p);
+  for (int p = threadIdx.x; p < si.z; p += 256) valid[si.w + p] = si.x + p;
+  if (threadIdx.x == 0) last[b] = si.x + si.z - 1;
+}
+
+int pt_launch_ragged_maps(const int4* seq_info, int32_t B, int64_t rows, int2* row_map, int32_t* valid, int32_t* last,
+                          hipStream_t s) {
+  (void)rows;
+  if (B <= 0) return PT_OK;
+  hipLaunchKernelGGL(ragged_maps_kernel, dim3((unsigned)B), dim3(256), 0, s, seq_info, row_map, valid, last);
+  PT_HIP_CHECK(hipGetLastError());
+  return PT_OK;
+}
+
+__global__ void __launch_bounds__(256) decode_rowmap_kernel(const int4* __restrict__ seq_info, int32_t B, int2* __restrict__ row_map) {
+  const int b = blockIdx.x * 256 + threadIdx.x;
+  if (b < B) row_map[b] = make_int2(b, seq_info[b].z);
+}
+
+__global__ void __launch_bounds__(256) advance_lens_kernel(int4* __restrict__ seq_info, int32_t B) {
+  const int b = blockIdx.x * 256 + threadIdx.x;
+  if (b < B) seq_info[b].z += 1;
+}
+
+int pt_launch_decode_rowmap(int4* seq_info, int32_t B, int2* row_map, hipStream_t s) {
+  if (B <= 0) return PT_OK;
+  hipLaunchKernelGGL(decode_rowmap_kernel, dim3((unsigned)((B + 255) / 256)), dim3(256), 0, s, seq_info, B, row_map);
+  PT_HIP_CHECK(hipGetLastError());
+  return PT_OK;
+}
+
+int pt_launch_advance_lens(int4* seq_info, int32_t B, hipStream_t s) {
+  if (B <= 0) return PT_OK;
+  hipLaunchKernelGGL(advance_lens_kernel, dim3((unsigned)((B + 255) / 256)), dim3(256), 0, s, seq_info, B);
+  PT_HIP_CHECK(hipGetLastError());
+  return PT_OK;
+}
+
+// ------------------------------------------------------------------------------------------
 // RMSNorm: out = h * g / sqrt(mean(h^2) + eps); fp32 statistics; one wavefront per row.
 // Row r of track b reads h + b*h_bstride + row_index(r)*d with row_index(r) = r*row_step + row_off.
 // ------------------------------------------------------------------------------------------
@@ -51,12 +175,14 @@ template <typename T>
 __global__ void __launch_bounds__(256) rmsnorm_kernel(const float* __restrict__ h, int64_t h_bstride,
                                                       const float* __restrict__ gains, int64_t g_bstride,
                                                       T* __restrict__ out, int64_t out_bstride, int64_t rows,
-                                                      int64_t row_step, int64_t row_off, int32_t d, float eps) {
+                                                      int64_t row_step, int64_t row_off,
+                                                      const int32_t* __restrict__ row_idx, int32_t d, float eps) {
   const int lane = threadIdx.x & 63;
   const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int b = blockIdx.y;
   if (r >= rows) return;
-  const float4* src = (const float4*)(h + b * h_bstride + (r * row_step + row_off) * d);
+  const int64_t sr = row_idx ? (int64_t)row_idx[r] : r * row_step + row_off;
+  const float4* src = (const float4*)(h + b * h_bstride + sr * d);
   const float4* g = (const float4*)(gains + b * g_bstride);
   const int n4 = d >> 2;
   float ss = 0.f;
@@ -79,11 +205,13 @@ template <typename T>
 __global__ void __launch_bounds__(256) rmsnorm_row_kernel(const float* __restrict__ h, int64_t h_bstride,
                                                           const float* __restrict__ gains, int64_t g_bstride,
                                                           T* __restrict__ out, int64_t out_bstride, int64_t rows,
-                                                          int64_t row_step, int64_t row_off, int32_t d, float eps) {
+                                                          int64_t row_step, int64_t row_off,
+                                                          const int32_t* __restrict__ row_idx, int32_t d, float eps) {
   __shared__ float s_part[4];
   const int64_t r = blockIdx.x;
   const int b = blockIdx.y;
-  const float4* src = (const float4*)(h + b * h_bstride + (r * row_step + row_off) * d);
+  const int64_t sr = row_idx ? (int64_t)row_idx[r] : r * row_step + row_off;
+  const float4* src = (const float4*)(h + b * h_bstride + sr * d);
   const float4* g = (const float4*)(gains + b * g_bstride);
   const int n4 = d >> 2;
   float ss = 0.f;
@@ -170,26 +298,26 @@ int pt_launch_resnorm(const float* part, int32_t slices, const float* res, int64
 
 static int launch_rmsnorm(const float* h, int64_t h_bstride, const float* gains, int64_t g_bstride, void* out,
                           int64_t out_bstride, int32_t dtype, int32_t batch, int64_t rows, int64_t row_step,
-                          int64_t row_off, int32_t d, float eps, hipStream_t s) {
+                          int64_t row_off, const int32_t* row_idx, int32_t d, float eps, hipStream_t s) {
   if (rows <= 0 || batch <= 0) return PT_OK;
   if (rows * batch <= 2048 && d >= 1024) {
     dim3 grid((unsigned)rows, (unsigned)batch);
     if (dtype == PT_F32)
       hipLaunchKernelGGL(rmsnorm_row_kernel<float>, grid, dim3(256), 0, s, h, h_bstride, gains, g_bstride, (float*)out,
-                         out_bstride, rows, row_step, row_off, d, eps);
+                         out_bstride, rows, row_step, row_off, row_idx, d, eps);
     else
       hipLaunchKernelGGL(rmsnorm_row_kernel<bf16_t>, grid, dim3(256), 0, s, h, h_bstride, gains, g_bstride, (bf16_t*)out,
-                         out_bstride, rows, row_step, row_off, d, eps);
+                         out_bstride, rows, row_step, row_off, row_idx, d, eps);
     PT_HIP_CHECK(hipGetLastError());
     return PT_OK;
   }
   dim3 grid((unsigned)((rows + 3) / 4), (unsigned)batch);
   if (dtype == PT_F32)
     hipLaunchKernelGGL(rmsnorm_kernel<float>, grid, dim3(256), 0, s, h, h_bstride, gains, g_bstride, (float*)out,
-                       out_bstride, rows, row_step, row_off, d, eps);
+                       out_bstride, rows, row_step, row_off, row_idx, d, eps);
   else
     hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, grid, dim3(256), 0, s, h, h_bstride, gains, g_bstride, (bf16_t*)out,
-                       out_bstride, rows, row_step, row_off, d, eps);
+                       out_bstride, rows, row_step, row_off, row_idx, d, eps);
   PT_HIP_CHECK(hipGetLastError());
   return PT_OK;
 }
@@ -197,12 +325,12 @@ static int launch_rmsnorm(const float* h, int64_t h_bstride, const float* gains,
 int pt_launch_rmsnorm(const float* h, int64_t h_bstride, const float* gains, int64_t g_bstride, void* out,
                       int64_t out_bstride, int32_t dtype, int32_t batch, int64_t rows, int32_t d, float eps,
                       hipStream_t s) {
-  return launch_rmsnorm(h, h_bstride, gains, g_bstride, out, out_bstride, dtype, batch, rows, 1, 0, d, eps, s);
+  return launch_rmsnorm(h, h_bstride, gains, g_bstride, out, out_bstride, dtype, batch, rows, 1, 0, nullptr, d, eps, s);
 }
 
 int pt_launch_rmsnorm_rows(const float* h, const float* gain, void* out, int32_t dtype, int64_t rows,
-                           int64_t row_step, int64_t row_off, int32_t d, float eps, hipStream_t s) {
-  return launch_rmsnorm(h, 0, gain, 0, out, 0, dtype, 1, rows, row_step, row_off, d, eps, s);
+                           int64_t row_step, int64_t row_off, const int32_t* row_idx, int32_t d, float eps, hipStream_t s) {
+  return launch_rmsnorm(h, 0, gain, 0, out, 0, dtype, 1, rows, row_step, row_off, row_idx, d, eps, s);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -308,6 +436,26 @@ int pt_launch_copy_f32(const float* src, float* dst, int64_t elems, hipStream_t 
 __global__ void __launch_bounds__(256) fill_f32_kernel(float* __restrict__ dst, int64_t n, float v) {
   const int64_t stride = (int64_t)gridDim.x * 256;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) dst[i] = v;
+}
+
+// RMSNorm folded into the GEMMs around it: the residual GEMM leaves `parts` partial sums of squares per row; this
+// turns them into the row's factor 1 / sqrt(mean + eps), summed in part order.
+__global__ void __launch_bounds__(256) row_inv_rms_kernel(const float* __restrict__ ss, int32_t parts, int64_t rows,
+                                                          float inv_d, float eps, float* __restrict__ out) {
+  const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (r >= rows) return;
+  const float* p = ss + r * parts;
+  float acc = 0.f;
+  for (int q = 0; q < parts; ++q) acc += p[q];
+  out[r] = 1.0f / sqrtf(acc * inv_d + eps);
+}
+
+int pt_launch_row_inv_rms(const float* ss, int32_t parts, int64_t rows, int32_t d, float eps, float* out, hipStream_t s) {
+  if (rows <= 0) return PT_OK;
+  hipLaunchKernelGGL(row_inv_rms_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, s, ss, parts, rows,
+                     1.0f / (float)d, eps, out);
+  PT_HIP_CHECK(hipGetLastError());
+  return PT_OK;
 }
 
 int pt_launch_fill_f32(float* dst, int64_t n, float v, hipStream_t s) {

@@ -42,15 +42,16 @@ static bool cfg_fits(const pt_gemm_args& g, int cfg) {
   return true;
 }
 
-int pt_launch_gemm_mfma(const pt_gemm_args& g, hipStream_t s) {
-  if (g.dtype != PT_BF16) return 0;
-  if (g.M <= 0 || g.N <= 0 || g.batch <= 0) return 1;
-  if (g.K < 2 * GM_BK || g.K % (2 * GM_BK)) return 0;
-  if ((g.lda & 7) || (g.ldb & 7) || (g.a_bstride & 7) || (g.w_bstride & 7)) return 0;
-  if (((uintptr_t)g.A | (uintptr_t)g.W) & 15) return 0;
+// The tile configuration for a problem, or -1 if the family does not cover it (-2: nothing to do).
+static int choose_cfg(const pt_gemm_args& g) {
+  if (g.dtype != PT_BF16) return -1;
+  if (g.M <= 0 || g.N <= 0 || g.batch <= 0) return -2;
+  if (g.K < 2 * GM_BK || g.K % (2 * GM_BK)) return -1;
+  if ((g.lda & 7) || (g.ldb & 7) || (g.a_bstride & 7) || (g.w_bstride & 7)) return -1;
+  if (((uintptr_t)g.A | (uintptr_t)g.W) & 15) return -1;
   if ((g.epi == EPI_STORE_F32 || g.epi == EPI_RESIDUAL) &&
-      ((g.ldo & 3) || (g.N & 3) || (g.out_bstride & 3) || (g.res_bstride & 3) || (((uintptr_t)g.out | (uintptr_t)g.res) & 15))) return 0;
-  if (g.epi == EPI_SWIGLU && ((g.olp_bstride & 7) || ((uintptr_t)g.olp & 15))) return 0;
+      ((g.ldo & 3) || (g.N & 3) || (g.out_bstride & 3) || (g.res_bstride & 3) || (((uintptr_t)g.out | (uintptr_t)g.res) & 15))) return -1;
+  if (g.epi == EPI_SWIGLU && ((g.olp_bstride & 7) || ((uintptr_t)g.olp & 15))) return -1;
   // measured: the direct-to-LDS variant (10) wins for the QKV epilogue and, at short K, for SwiGLU
   static const int big[] = {0, 4, 2, -1}, big_qkv[] = {10, 8, 0, 4, 2, -1}, big_dl[] = {10, 0, 4, 2, -1}, mid[] = {4, 2, -1}, m64[] = {3, 6, -1}, m32[] = {5, 7, -1};
   const int* cand;
@@ -58,14 +59,30 @@ int pt_launch_gemm_mfma(const pt_gemm_args& g, hipStream_t s) {
   else if (g.M <= 64) cand = m64;
   else if (g.M <= 128 || (int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256) * g.batch < 200) cand = mid;
   else cand = g.epi == EPI_QKV ? big_qkv : (g.epi == EPI_SWIGLU && g.K <= 1024) ? big_dl : big;
-  int cfg = -1;
-  if (pt_tune_gemm_cfg >= 0 && pt_tune_gemm_cfg < GM_NCFG) {
-    if (cfg_fits(g, pt_tune_gemm_cfg)) cfg = pt_tune_gemm_cfg;
-  } else {
-    for (; *cand >= 0; ++cand)
-      if (cfg_fits(g, *cand)) { cfg = *cand; break; }
-  }
+  if (pt_tune_gemm_cfg >= 0 && pt_tune_gemm_cfg < GM_NCFG) return cfg_fits(g, pt_tune_gemm_cfg) ? pt_tune_gemm_cfg : -1;
+  for (; *cand >= 0; ++cand)
+    if (cfg_fits(g, *cand)) return *cand;
+  return -1;
+}
+
+bool pt_gemm_mfma_covers(const pt_gemm_args& g) { return choose_cfg(g) >= 0; }
+
+// Configurations whose tile is at least 128 x 128 run the LDS-staged residual epilogue, which can also emit the
+// scaled bf16 copy and the per-row sums of squares; one block of sums per wavefront column range.
+int pt_gemm_mfma_fold_parts(const pt_gemm_args& g) {
+  if (g.epi != EPI_RESIDUAL) return 0;
+  const int cfg = choose_cfg(g);
+  static const bool staged[GM_NCFG] = {true, true, true, false, true, false, false, false, true, true, true, true};
+  if (cfg < 0 || !staged[cfg] || g.N % kWaveN[cfg]) return 0;
+  return g.N / kWaveN[cfg];
+}
+
+int pt_launch_gemm_mfma(const pt_gemm_args& g, hipStream_t s) {
+  const int cfg = choose_cfg(g);
+  if (cfg == -2) return 1;
   if (cfg < 0) return 0;
+  if (g.nf_out && g.nf_parts != pt_gemm_mfma_fold_parts(g))
+    return pt_set_error(PT_ERR_INVALID_ARGUMENT, "folded RMSNorm asked of a GEMM configuration that cannot emit it");
   switch (g.epi) {
     case EPI_STORE_F32: return launch_epi<EPI_STORE_F32>(g, s, cfg);
     case EPI_RESIDUAL: return launch_epi<EPI_RESIDUAL>(g, s, cfg);

@@ -88,7 +88,8 @@ __device__ __forceinline__ void sk_finish(const pt_gemm_args& g, int b, int tile
     pk.y = pack_bf16x2(silu_f(lo[2]) * hi[2], silu_f(lo[3]) * hi[3]);
     *(uint2*)o = pk;
   } else {  // EPI_QKV
-    const int seq = m / g.S, pos = g.pos0 + (m - seq * g.S);
+    const pt_rowpos rp = gemm_row_pos(g, m);
+    const int seq = rp.seq, pos = rp.pos;
     const int hd = g.hd, half_hd = hd >> 1, hq = g.H * hd;
     if (tl.rot) {
       const int j = j0 + off;

@@ -10,6 +10,7 @@
 #include "pt_internal.h"
 
 static thread_local char g_err[512] = "";
+static bool g_fold_rmsnorm = true;   // pt_set_tuning(PT_TUNE_FOLD_RMSNORM)
 
 int pt_set_error(int code, const char* fmt, ...) {
   va_list ap;
@@ -69,19 +70,21 @@ int pt_compute_layout(const pt_config* c, pt_layout* l) {
   l->off_gf = off;     off = align_up(off + (size_t)(d * 4), 256);
   l->off_embed = off;  off = align_up(off + (size_t)((int64_t)c->vocab * d * es), 256);
   l->off_headT = off;  off = align_up(off + (size_t)((int64_t)c->vocab * d * es), 256);
-  l->off_rope = off;   off = align_up(off + (size_t)((int64_t)c->max_seq * hd * 4), 256);
+  l->s_k = (c->max_seq + 63) / 64 * 64;
+  l->off_rope = off;   off = align_up(off + (size_t)(l->s_k * hd * 4), 256);
   l->off_flag = off;   off = align_up(off + 4, 256);
   l->weight_bytes = off;
 
-  l->s_pad = (c->max_seq + 63) / 64 * 64 + 64;
+  l->s_pad = l->s_k + 64;
   const int64_t B = c->max_batch;
-  const int64_t k_head = (int64_t)c->max_seq * hd, v_head = hd * l->s_pad;
+  const int64_t k_head = l->s_k * hd, v_head = hd * l->s_pad;
   l->off_k = 0;
   l->off_v = align_up((size_t)(T * L * B * c->n_kv_heads * k_head * es), 256);
-  l->kv_bytes = align_up(l->off_v + (size_t)(T * L * B * c->n_kv_heads * v_head * es), 256);
+  l->off_seq = align_up(l->off_v + (size_t)(T * L * B * c->n_kv_heads * v_head * es), 256);
+  l->kv_bytes = align_up(l->off_seq + (size_t)(B * 16), 256);
 
   pt_workspace w;
-  pt_layout_workspace(c, l, B * c->max_seq, B, PT_SK_PART_FLOATS, PT_MAX_SPLITS, &w);
+  pt_layout_workspace(c, l, B * l->s_k, B, PT_SK_PART_FLOATS, PT_MAX_SPLITS, &w);
   l->ws_bytes = w.bytes;
   (void)f;
   return PT_OK;
@@ -99,6 +102,10 @@ void pt_layout_workspace(const pt_config* c, const pt_layout* l, int64_t rows, i
   w->off_o = off;    off = align_up(off + (size_t)(T * rows * l->hq * es), 256);
   w->off_m = off;    off = align_up(off + (size_t)(T * rows * f * es), 256);
   w->off_part = off; off = align_up(off + (size_t)(T * batch * c->n_heads * max_splits * (hd + 2) * 4), 256);
+  w->off_ss = off;   off = align_up(off + (size_t)(T * rows * ((d + 63) / 64) * 4), 256);
+  w->off_rinv = off; off = align_up(off + (size_t)(T * rows * 4), 256);
+  w->off_rowmap = off; off = align_up(off + (size_t)(rows * 8), 256);
+  w->off_rowidx = off; off = align_up(off + (size_t)((batch + rows) * 4), 256);
   w->off_skp = off;  off = align_up(off + (size_t)skp_floats * 4, 256);
   w->bytes = off;
   w->skp_floats = skp_floats;
@@ -141,12 +148,13 @@ extern "C" int pt_create(const pt_config* cfg, void* dev_weights, size_t weight_
   h->w = (char*)dev_weights;
   h->kv = (char*)dev_kv;
   h->ws = (char*)dev_ws;
-  pt_layout_workspace(cfg, &l, (int64_t)cfg->max_batch * cfg->max_seq, cfg->max_batch, PT_SK_PART_FLOATS, PT_MAX_SPLITS, &h->arena);
+  pt_layout_workspace(cfg, &l, (int64_t)cfg->max_batch * l.s_k, cfg->max_batch, PT_SK_PART_FLOATS, PT_MAX_SPLITS, &h->arena);
   h->arena.base = h->ws;
   h->active = &h->arena;
   h->stream = (hipStream_t)hip_stream;
   h->batch = 0;
   h->seq_len = 0;
+  h->ragged = false;
   h->merges = 0;
   h->weights_ready = false;
   h->rope_ready = false;
@@ -169,6 +177,8 @@ extern "C" int pt_reset(pt_handle* h) {
   if (!h) return pt_set_error(PT_ERR_NULL_POINTER, "handle is NULL");
   h->batch = 0;
   h->seq_len = 0;
+  h->ragged = false;
+  h->seqs.clear();
   return PT_OK;
 }
 
@@ -333,6 +343,7 @@ extern "C" int pt_profile_paths(pt_handle* h, int32_t kernel_class, int64_t* cou
 extern "C" int pt_set_tuning(int32_t knob, int32_t value) {
   if (knob == PT_TUNE_GEMM_TILE_CONFIG) pt_tune_gemm_cfg = value;
   else if (knob == PT_TUNE_SKINNY_PLAN) pt_tune_skinny_plan = value;
+  else if (knob == PT_TUNE_FOLD_RMSNORM) g_fold_rmsnorm = value != 0;
   else return pt_set_error(PT_ERR_INVALID_ARGUMENT, "unknown tuning knob %d", knob);
   return PT_OK;
 }
@@ -384,14 +395,36 @@ static int run_gemm(pt_handle* h, const pt_gemm_args& g_in, int cls) {
 // Residual GEMM (out = res + A W^T) followed, when gain is given, by the RMSNorm of the new residual stream
 // into `normed`.  In decode the GEMM may split K over workgroups; the kernel that adds the slices also adds the
 // residual and normalises.
+//
+// Prefill (more than 64 rows, MFMA tile kernels on both sides): the norm is folded into the two GEMMs instead.
+// The residual GEMM's epilogue also stores bf16(h * gain) into `normed` and per-row partial sums of squares;
+// the GEMM that consumes `normed` (`next`: its shape) multiplies its accumulators by the row's 1/rms.
+// A small kernel turns the partial sums into one factor per row.  *folded_parts > 0 tells the caller that
+// `normed` is unnormalised and the consumer must apply those factors (0: `normed` holds the finished RMSNorm).
 static int run_residual_gemm_norm(pt_handle* h, const pt_gemm_args& g_in, int cls, const float* gain,
-                                  int64_t gain_bstride, void* normed) {
+                                  int64_t gain_bstride, void* normed, const pt_gemm_args* next, int* folded_parts) {
   const pt_config& c = h->cfg;
   pt_gemm_args g = g_in;
   g.sk_part = (float*)(h->active->base + h->active->off_skp);
   g.sk_part_floats = h->active->skp_floats;
   const int64_t rows = g.M;
   int rc;
+  *folded_parts = 0;
+  if (h->path == PT_PATH_AUTO && g_fold_rmsnorm && gain && next && g.M > 64 && g.N == g.ldo && pt_gemm_mfma_covers(*next)) {
+    const int parts = pt_gemm_mfma_fold_parts(g);
+    if (parts > 0 && parts <= (g.N + 63) / 64) {
+      g.nf_out = normed; g.nf_out_bstride = rows * g.N;
+      g.nf_gain = gain; g.nf_gain_bstride = gain_bstride;
+      g.nf_ss = (float*)(h->active->base + h->active->off_ss); g.nf_ss_bstride = rows * parts;
+      g.nf_parts = parts;
+      rc = run_gemm(h, g, cls);
+      if (rc) return rc;
+      *folded_parts = parts;
+      prof_scope ps(h, PT_K_RMSNORM);
+      return pt_launch_row_inv_rms(g.nf_ss, parts, (int64_t)g.batch * rows, g.N, c.rms_eps,
+                                   (float*)(h->active->base + h->active->off_rinv), h->stream);
+    }
+  }
   if (h->path == PT_PATH_AUTO && g.M <= 64 && g.N == g.ldo && g.N <= 8192 && pt_gemm_skinny_ksplit(g) > 1) {
     const int slices = pt_gemm_skinny_ksplit(g);
     {
@@ -424,20 +457,33 @@ static int run_attention(pt_handle* h, const pt_attn_args& a) {
   return pt_launch_attn_generic(a, h->stream);
 }
 
+// A ragged batch as the forward pass sees it (device pointers).  Prefill: the padded-packed row layout
+// (seq_info, row_map over `rows` packed rows, `valid`: packed row of every real token in input order, `last`:
+// packed row of each sequence's last token).  Decode: row_map[b] = (b, length of b) only.
+struct ragged_ctx {
+  const int4* seq_info;
+  const int2* row_map;
+  const int32_t* valid;
+  const int32_t* last;
+  int64_t rows, n_valid;
+  int32_t max_plen, max_pos;
+};
+
 static int forward(pt_handle* h, const pt_workspace& w, const int32_t* dev_tokens, const float* dev_hidden_in,
                    int32_t hidden_tracks, int32_t B, int32_t S, int32_t pos0, int32_t logits_mode,
-                   float* dev_logits, float* dev_hidden_out, int32_t* dev_argmax) {
+                   float* dev_logits, float* dev_hidden_out, int32_t* dev_argmax, const ragged_ctx* rg = nullptr) {
   h->active = &w;
+  const bool ragged_prefill = rg && S != 1;
   const pt_config& c = h->cfg;
   const pt_layout& l = h->lay;
   const int64_t T = c.n_tracks, L = c.n_layers, d = c.d_model, f = c.d_ffn;
-  const int64_t rows = (int64_t)B * S;
+  const int64_t rows = ragged_prefill ? rg->rows : (int64_t)B * S;
   const int64_t es = l.elem_size;
   hipStream_t st = h->stream;
   int rc;
 
   if (!h->rope_ready) {
-    rc = pt_launch_rope_table((float*)(h->w + l.off_rope), c.max_seq, c.head_dim, c.rope_theta, st);
+    rc = pt_launch_rope_table((float*)(h->w + l.off_rope), (int32_t)l.s_k, c.head_dim, c.rope_theta, st);
     if (rc) return rc;
     rc = pt_launch_fill_f32((float*)(h->w + l.off_flag), 1, 0.0f, st);   // device status word: all-zero bits
     if (rc) return rc;
@@ -457,9 +503,23 @@ static int forward(pt_handle* h, const pt_workspace& w, const int32_t* dev_token
   // once; the first layer of a block reads it with a zero track stride.
   const float* x;
   int64_t x_bstride;
-  if (dev_hidden_in) {
+  if (dev_hidden_in && ragged_prefill) {
+    // the caller's rows are packed without padding: spread them over the padded rows (zeros in between).  Per-track
+    // inputs go to the residual buffer, which the first layer reads and then overwrites element by element.
+    float* xp = hidden_tracks == 1 ? hm : hres;
+    rc = pt_launch_scatter_rows(dev_hidden_in, hidden_tracks == 1 ? 0 : rg->n_valid * d, rg->row_map, rg->seq_info, rows,
+                                (int32_t)d, hidden_tracks, xp, rows * d, st);
+    if (rc) return rc;
+    x = xp;
+    x_bstride = hidden_tracks == 1 ? 0 : rows * d;
+  } else if (dev_hidden_in) {
     x = dev_hidden_in;
     x_bstride = hidden_tracks == 1 ? 0 : rows * d;
+  } else if (ragged_prefill) {
+    { prof_scope ps(h, PT_K_EMBED); rc = pt_launch_embed_ragged(h->w + l.off_embed, c.dtype, dev_tokens, rg->row_map, rg->seq_info, rows, (int32_t)d, c.vocab, hm, (int32_t*)(h->w + l.off_flag), st); }
+    if (rc) return rc;
+    x = hm;
+    x_bstride = 0;
   } else {
     { prof_scope ps(h, PT_K_EMBED); rc = pt_launch_embed(h->w + l.off_embed, c.dtype, dev_tokens, rows, (int32_t)d, c.vocab, hm, (int32_t*)(h->w + l.off_flag), st); }
     if (rc) return rc;
@@ -467,13 +527,17 @@ static int forward(pt_handle* h, const pt_workspace& w, const int32_t* dev_token
     x_bstride = 0;
   }
 
-  const int64_t kv_head_k = (int64_t)c.max_seq * c.head_dim;
+  const int64_t kv_head_k = l.s_k * c.head_dim;
   const int64_t kv_head_v = (int64_t)c.head_dim * l.s_pad;
   int merge_idx = 0;
   bool normed = false;   // abuf already holds the normalised input of this layer's attention half
   // Latency-mode decode (a handful of rows): the QKV and gate/up kernels form their RMSNorm-ed operand
   // themselves, which saves two launches per layer.  The decision depends on shapes only.
   bool fuse_qkv_norm = false, fuse_ffn_norm = false;
+  pt_gemm_args qkv_proto, gu_proto;   // shapes of the two GEMMs that consume a normalised activation
+  memset(&qkv_proto, 0, sizeof(qkv_proto));
+  memset(&gu_proto, 0, sizeof(gu_proto));
+  int qkv_rs_parts = 0;   // > 0: abuf holds bf16(h * gain) and the QKV GEMM applies the row scale (folded RMSNorm)
   if (h->path == PT_PATH_AUTO) {
     pt_gemm_args p;
     memset(&p, 0, sizeof(p));
@@ -482,9 +546,12 @@ static int forward(pt_handle* h, const pt_workspace& w, const int32_t* dev_token
     p.M = (int32_t)rows; p.batch = (int32_t)T; p.dtype = c.dtype;
     p.N = (int32_t)l.n_qkv; p.epi = EPI_QKV; p.olp = qbuf; p.olp_bstride = rows * l.hq;
     p.H = c.n_heads; p.Hkv = c.n_kv_heads; p.hd = c.head_dim; p.S = S; p.s_pad = (int32_t)l.s_pad;
+    p.row_map = rg ? rg->row_map : nullptr; p.row_blocks = ragged_prefill;
     fuse_qkv_norm = pt_gemm_fuses_norm(p);
+    qkv_proto = p;
     p.N = (int32_t)(2 * f); p.epi = EPI_SWIGLU; p.olp = mbuf; p.olp_bstride = rows * f;
     fuse_ffn_norm = pt_gemm_fuses_norm(p);
+    gu_proto = p;
   }
   for (int64_t layer = 0; layer < L; ++layer) {
     const bool first = (layer % c.block_depth) == 0;
@@ -512,6 +579,7 @@ static int forward(pt_handle* h, const pt_workspace& w, const int32_t* dev_token
     g.rope = (const float*)(h->w + l.off_rope);
     g.H = c.n_heads; g.Hkv = c.n_kv_heads; g.hd = c.head_dim; g.S = S; g.pos0 = pos0;
     g.s_pad = (int32_t)l.s_pad;
+    g.row_map = rg ? rg->row_map : nullptr; g.row_blocks = ragged_prefill;
     // cache strides are stated for K; the V^T side uses hd * s_pad per head with the same nesting
     g.kv_bstride = L * c.max_batch * c.n_kv_heads;   // in heads; kernels scale by the head size
     g.kv_seq_stride = c.n_kv_heads;                  // in heads
@@ -519,6 +587,9 @@ static int forward(pt_handle* h, const pt_workspace& w, const int32_t* dev_token
     if (fuse_qkv_norm) {
       g.norm_src = src; g.norm_bstride = src_bstride;
       g.norm_gain = gains + (layer * 2 + 0) * d; g.norm_gbstride = L * 2 * d; g.norm_eps = c.rms_eps;
+    }
+    if (qkv_rs_parts > 0) {
+      g.rs_inv = (const float*)(w.base + w.off_rinv); g.rs_bstride = rows;
     }
     rc = run_gemm(h, g, PT_K_GEMM_QKV);
     if (rc) return rc;
@@ -532,6 +603,10 @@ static int forward(pt_handle* h, const pt_workspace& w, const int32_t* dev_token
     a.H = c.n_heads; a.Hkv = c.n_kv_heads; a.hd = c.head_dim; a.s_pad = (int32_t)l.s_pad;
     a.dtype = c.dtype;
     a.partials = (float*)(w.base + w.off_part); a.max_splits = w.max_splits;
+    if (rg) {
+      a.row_map = rg->row_map; a.seq_info = ragged_prefill ? rg->seq_info : nullptr;
+      a.max_pos = rg->max_pos; a.max_plen = rg->max_plen; a.rows = rows;
+    }
     rc = run_attention(h, a);
     if (rc) return rc;
 
@@ -543,7 +618,9 @@ static int forward(pt_handle* h, const pt_workspace& w, const int32_t* dev_token
     g.out = hres; g.out_bstride = rows * d; g.ldo = (int32_t)d;
     g.res = src; g.res_bstride = src_bstride;
     // ... and the RMSNorm that opens the feed-forward half
-    rc = run_residual_gemm_norm(h, g, PT_K_GEMM_OUT, fuse_ffn_norm ? nullptr : gains + (layer * 2 + 1) * d, L * 2 * d, abuf);
+    int gu_rs_parts = 0;
+    rc = run_residual_gemm_norm(h, g, PT_K_GEMM_OUT, fuse_ffn_norm ? nullptr : gains + (layer * 2 + 1) * d, L * 2 * d, abuf,
+                                &gu_proto, &gu_rs_parts);
     if (rc) return rc;
 
     // feed-forward half
@@ -556,6 +633,9 @@ static int forward(pt_handle* h, const pt_workspace& w, const int32_t* dev_token
     if (fuse_ffn_norm) {
       g.norm_src = hres; g.norm_bstride = rows * d;
       g.norm_gain = gains + (layer * 2 + 1) * d; g.norm_gbstride = L * 2 * d; g.norm_eps = c.rms_eps;
+    }
+    if (gu_rs_parts > 0) {
+      g.rs_inv = (const float*)(w.base + w.off_rinv); g.rs_bstride = rows;
     }
     rc = run_gemm(h, g, PT_K_GEMM_GATEUP);
     if (rc) return rc;
@@ -570,7 +650,7 @@ static int forward(pt_handle* h, const pt_workspace& w, const int32_t* dev_token
     const bool block_end = (layer + 1) % c.block_depth == 0;
     const bool norm_next = !block_end && !fuse_qkv_norm;
     rc = run_residual_gemm_norm(h, g, PT_K_GEMM_DOWN, norm_next ? gains + ((layer + 1) * 2 + 0) * d : nullptr,
-                                L * 2 * d, abuf);
+                                L * 2 * d, abuf, &qkv_proto, &qkv_rs_parts);
     if (rc) return rc;
     normed = norm_next;
 
@@ -579,12 +659,21 @@ static int forward(pt_handle* h, const pt_workspace& w, const int32_t* dev_token
     if ((layer + 1) % c.block_depth == 0) {
       const void* tr[16];
       for (int64_t t = 0; t < T; ++t) tr[t] = hres + t * rows * d;
+      // observation points: all rows, or (ragged prefill) the rows of the real tokens in input order
+      const int64_t tap_rows = ragged_prefill ? rg->n_valid : rows;
       if (h->track_taps) {
-        rc = pt_launch_copy_f32(hres, h->track_taps + (int64_t)merge_idx * T * rows * d, T * rows * d, st);
+        float* tt = h->track_taps + (int64_t)merge_idx * T * tap_rows * d;
+        if (ragged_prefill) {
+          for (int64_t t = 0; t < T && !rc; ++t) rc = pt_launch_gather_rows(hres + t * rows * d, rg->valid, tap_rows, (int32_t)d, tt + t * tap_rows * d, st);
+        } else {
+          rc = pt_launch_copy_f32(hres, tt, T * rows * d, st);
+        }
         if (rc) return rc;
       }
-      float* tap = h->taps ? h->taps + (int64_t)merge_idx * rows * d : nullptr;
-      if (T == 1 && c.merge_scale == 1.0f && !tap) {
+      float* tap = h->taps ? h->taps + (int64_t)merge_idx * tap_rows * d : nullptr;
+      float* tap_gather = nullptr;
+      if (ragged_prefill && tap) { tap_gather = tap; tap = nullptr; }
+      if (T == 1 && c.merge_scale == 1.0f && !tap && !tap_gather) {
         // one track, plain sum: the all-reduce is the identity and the track simply continues
         merged = hres;
         x = hres;
@@ -595,6 +684,10 @@ static int forward(pt_handle* h, const pt_workspace& w, const int32_t* dev_token
           rc = pt_launch_merge(tr, (int32_t)T, rows * d, PT_F32, c.merge_scale, hm, tap, st);
         }
         if (rc) return rc;
+        if (tap_gather) {
+          rc = pt_launch_gather_rows(hm, rg->valid, tap_rows, (int32_t)d, tap_gather, st);
+          if (rc) return rc;
+        }
         merged = hm;
         x = hm;
         x_bstride = 0;
@@ -605,16 +698,20 @@ static int forward(pt_handle* h, const pt_workspace& w, const int32_t* dev_token
   }
 
   if (dev_hidden_out) {
-    rc = pt_launch_copy_f32(merged, dev_hidden_out, rows * d, st);
+    rc = ragged_prefill ? pt_launch_gather_rows(merged, rg->valid, rg->n_valid, (int32_t)d, dev_hidden_out, st)
+                        : pt_launch_copy_f32(merged, dev_hidden_out, rows * d, st);
     if (rc) return rc;
   }
   if (logits_mode != PT_LOGITS_NONE && (dev_logits || dev_argmax)) {
-    const int64_t lrows = logits_mode == PT_LOGITS_ALL ? rows : B;
+    const int64_t lrows = logits_mode == PT_LOGITS_ALL ? (ragged_prefill ? rg->n_valid : rows) : B;
     const float* gf = (const float*)(h->w + l.off_gf);
-    if (logits_mode == PT_LOGITS_ALL)
-      rc = pt_launch_rmsnorm_rows(merged, gf, abuf, c.dtype, lrows, 1, 0, (int32_t)d, c.rms_eps, st);
+    if (ragged_prefill)   // the rows of the real tokens (all of them, or each sequence's last one), gathered by index
+      rc = pt_launch_rmsnorm_rows(merged, gf, abuf, c.dtype, lrows, 0, 0, logits_mode == PT_LOGITS_ALL ? rg->valid : rg->last,
+                                  (int32_t)d, c.rms_eps, st);
+    else if (logits_mode == PT_LOGITS_ALL)
+      rc = pt_launch_rmsnorm_rows(merged, gf, abuf, c.dtype, lrows, 1, 0, nullptr, (int32_t)d, c.rms_eps, st);
     else
-      rc = pt_launch_rmsnorm_rows(merged, gf, abuf, c.dtype, lrows, S, S - 1, (int32_t)d, c.rms_eps, st);
+      rc = pt_launch_rmsnorm_rows(merged, gf, abuf, c.dtype, lrows, S, S - 1, nullptr, (int32_t)d, c.rms_eps, st);
     if (rc) return rc;
     float* lg = dev_logits;
     if (!lg) return pt_set_error(PT_ERR_NULL_POINTER, "argmax needs a logits buffer");
@@ -665,6 +762,66 @@ extern "C" int pt_prefill(pt_handle* h, const int32_t* dev_tokens, const float* 
   if (rc) return rc;
   h->batch = B;
   h->seq_len = S;
+  h->ragged = false;
+  h->seqs.clear();
+  return PT_OK;
+}
+
+extern "C" int pt_prefill_ragged(pt_handle* h, const int32_t* dev_tokens, const float* dev_hidden_in,
+                                 int32_t hidden_tracks, int32_t B, const int32_t* host_lens, int32_t logits_mode,
+                                 float* dev_logits, float* dev_hidden_out) {
+  if (!h) return pt_set_error(PT_ERR_NULL_POINTER, "handle is NULL");
+  if (!host_lens) return pt_set_error(PT_ERR_NULL_POINTER, "host_lens is NULL");
+  if (B < 1) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "B must be >= 1");
+  if (B > h->cfg.max_batch) return pt_set_error(PT_ERR_CAPACITY, "B = %d exceeds max_batch = %d", B, h->cfg.max_batch);
+  if (logits_mode < PT_LOGITS_NONE || logits_mode > PT_LOGITS_ALL) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "bad logits_mode");
+  if (logits_mode != PT_LOGITS_NONE) {
+    if (h->cfg.vocab == 0) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "model has no vocabulary: no logits");
+    if (!dev_logits) return pt_set_error(PT_ERR_NULL_POINTER, "logits requested but dev_logits is NULL");
+  }
+  int rc = check_inputs(h, dev_tokens, dev_hidden_in, hidden_tracks);
+  if (rc) return rc;
+  // padded-packed layout: every sequence starts on a multiple of 64 rows
+  std::vector<pt_seq> seqs((size_t)B);
+  int64_t rows = 0, n_valid = 0;
+  int32_t max_len = 0;
+  for (int b = 0; b < B; ++b) {
+    const int32_t len = host_lens[b];
+    if (len < 1) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "host_lens[%d] = %d, need >= 1", b, len);
+    if (len > h->cfg.max_seq) return pt_set_error(PT_ERR_CAPACITY, "host_lens[%d] = %d exceeds max_seq = %d", b, len, h->cfg.max_seq);
+    const int32_t plen = (len + 63) / 64 * 64;
+    if (rows + plen > 0x7fffffff || n_valid + len > 0x7fffffff) return pt_set_error(PT_ERR_CAPACITY, "batch too large");
+    seqs[b] = {(int32_t)rows, plen, len, (int32_t)n_valid};
+    rows += plen;
+    n_valid += len;
+    if (len > max_len) max_len = len;
+  }
+  h->seqs.swap(seqs);
+  const pt_workspace& w = h->arena;
+  int4* seq_info = (int4*)(h->kv + h->lay.off_seq);
+  PT_HIP_CHECK(hipMemcpyAsync(seq_info, h->seqs.data(), (size_t)B * sizeof(pt_seq), hipMemcpyHostToDevice, h->stream));
+  int2* row_map = (int2*)(w.base + w.off_rowmap);
+  int32_t* last = (int32_t*)(w.base + w.off_rowidx);
+  int32_t* valid = last + h->cfg.max_batch;
+  rc = pt_launch_ragged_maps(seq_info, B, rows, row_map, valid, last, h->stream);
+  if (rc) return rc;
+  ragged_ctx rg;
+  rg.seq_info = seq_info; rg.row_map = row_map; rg.valid = valid; rg.last = last;
+  rg.rows = rows; rg.n_valid = n_valid;
+  rg.max_plen = (max_len + 63) / 64 * 64; rg.max_pos = max_len - 1;
+  rc = forward(h, w, dev_tokens, dev_hidden_in, hidden_tracks, B, rg.max_plen, 0, logits_mode, dev_logits, dev_hidden_out,
+               nullptr, &rg);
+  h->active = &h->arena;
+  if (rc) { h->batch = 0; h->ragged = false; return rc; }
+  h->batch = B;
+  h->seq_len = max_len;
+  h->ragged = true;
+  return PT_OK;
+}
+
+extern "C" int pt_seq_lens(const pt_handle* h, int32_t* host_out) {
+  if (!h || !host_out) return pt_set_error(PT_ERR_NULL_POINTER, "handle or out is NULL");
+  for (int b = 0; b < h->batch; ++b) host_out[b] = h->ragged ? h->seqs[(size_t)b].len : h->seq_len;
   return PT_OK;
 }
 
@@ -680,17 +837,42 @@ static int decode_checks(pt_handle* h, const int32_t* dev_tokens, const float* d
   return PT_OK;
 }
 
+// One decode step over the temporaries `w`.  A ragged batch first writes (sequence, own length) per row for the
+// kernels and lets every length grow by one afterwards, on the device and in the host copy.
+static int decode_forward(pt_handle* h, const pt_workspace& w, const int32_t* dev_tokens, const float* dev_hidden_in,
+                          int32_t hidden_tracks, int32_t B, float* dev_logits, float* dev_hidden_out, int32_t* dev_argmax) {
+  int rc;
+  const int mode = dev_logits ? PT_LOGITS_LAST : PT_LOGITS_NONE;
+  if (h->ragged) {
+    int4* seq_info = (int4*)(h->kv + h->lay.off_seq);
+    int2* row_map = (int2*)(w.base + w.off_rowmap);
+    rc = pt_launch_decode_rowmap(seq_info, B, row_map, h->stream);
+    if (rc) return rc;
+    ragged_ctx rg;
+    memset(&rg, 0, sizeof(rg));
+    rg.row_map = row_map;
+    rg.max_pos = h->seq_len;
+    rc = forward(h, w, dev_tokens, dev_hidden_in, hidden_tracks, B, 1, h->seq_len, mode, dev_logits, dev_hidden_out, dev_argmax, &rg);
+    h->active = &h->arena;
+    if (rc) return rc;
+    rc = pt_launch_advance_lens(seq_info, B, h->stream);
+    if (rc) return rc;
+    for (pt_seq& q : h->seqs) q.len += 1;
+  } else {
+    rc = forward(h, w, dev_tokens, dev_hidden_in, hidden_tracks, B, 1, h->seq_len, mode, dev_logits, dev_hidden_out, dev_argmax);
+    h->active = &h->arena;
+    if (rc) return rc;
+  }
+  h->seq_len += 1;
+  return PT_OK;
+}
+
 extern "C" int pt_decode_step(pt_handle* h, const int32_t* dev_tokens, const float* dev_hidden_in,
                               int32_t hidden_tracks, int32_t B, float* dev_logits,
                               float* dev_hidden_out, int32_t* dev_argmax) {
   int rc = decode_checks(h, dev_tokens, dev_hidden_in, hidden_tracks, B, dev_logits, dev_argmax);
   if (rc) return rc;
-  rc = forward(h, h->arena, dev_tokens, dev_hidden_in, hidden_tracks, B, 1, h->seq_len,
-               dev_logits ? PT_LOGITS_LAST : PT_LOGITS_NONE, dev_logits, dev_hidden_out, dev_argmax);
-  h->active = &h->arena;
-  if (rc) return rc;
-  h->seq_len += 1;
-  return PT_OK;
+  return decode_forward(h, h->arena, dev_tokens, dev_hidden_in, hidden_tracks, B, dev_logits, dev_hidden_out, dev_argmax);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -740,10 +922,5 @@ extern "C" int pt_decode_step_static(pt_handle* h, const int32_t* dev_tokens, co
   if (w.skp_floats > PT_SK_PART_FLOATS) w.skp_floats = PT_SK_PART_FLOATS;
   rc = static_scratch_base(&w.base);
   if (rc) return rc;
-  rc = forward(h, w, dev_tokens, dev_hidden_in, hidden_tracks, B, 1, h->seq_len,
-               dev_logits ? PT_LOGITS_LAST : PT_LOGITS_NONE, dev_logits, dev_hidden_out, dev_argmax);
-  h->active = &h->arena;
-  if (rc) return rc;
-  h->seq_len += 1;
-  return PT_OK;
+  return decode_forward(h, w, dev_tokens, dev_hidden_in, hidden_tracks, B, dev_logits, dev_hidden_out, dev_argmax);
 }

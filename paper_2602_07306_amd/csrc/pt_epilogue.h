@@ -11,6 +11,19 @@
 
 #include "pt_device.h"
 
+// (sequence, position) of GEMM row m: by the row map of a ragged batch, else m / S and pos0 + m % S
+struct pt_rowpos {
+  int seq, pos;
+};
+__device__ __forceinline__ pt_rowpos gemm_row_pos(const pt_gemm_args& g, int m) {
+  if (g.row_map) {
+    const int2 e = g.row_map[m];
+    return {e.x, e.y};
+  }
+  const int seq = m / g.S;
+  return {seq, g.pos0 + (m - seq * g.S)};
+}
+
 // gate/up physical rows sit in 64-row groups: 32 gate rows then the 32 matching up rows
 __device__ __forceinline__ int swiglu_gate_row(int j) { return (j >> 5) * 64 + (j & 31); }
 
@@ -35,7 +48,8 @@ __device__ __forceinline__ void epi_swiglu(const pt_gemm_args& g, int b, int m, 
 template <typename T>
 __device__ __forceinline__ void epi_rope_pair(const pt_gemm_args& g, int b, int m, int n0, float lo, float hi) {
   const int hq = g.H * g.hd, half = g.hd >> 1;
-  const int seq = m / g.S, pos = g.pos0 + (m - seq * g.S);
+  const pt_rowpos rp = gemm_row_pos(g, m);
+  const int seq = rp.seq, pos = rp.pos;
   const bool is_q = n0 < hq;
   const int c = is_q ? n0 : n0 - hq;
   const int head = c / g.hd, j = c - head * g.hd;
@@ -59,7 +73,8 @@ template <typename T>
 __device__ __forceinline__ void epi_v(const pt_gemm_args& g, int b, int m, int n, float acc) {
   const int c = n - (g.H + g.Hkv) * g.hd;
   const int head = c / g.hd, j = c - head * g.hd;
-  const int seq = m / g.S, pos = g.pos0 + (m - seq * g.S);
+  const pt_rowpos rp = gemm_row_pos(g, m);
+  const int seq = rp.seq, pos = rp.pos;
   const int64_t hidx = b * g.kv_bstride + seq * g.kv_seq_stride + head;
   elem<T>::st((T*)g.vc + hidx * ((int64_t)g.hd * g.s_pad) + (int64_t)j * g.s_pad + pos, acc);
 }

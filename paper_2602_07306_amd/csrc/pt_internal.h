@@ -51,7 +51,8 @@ struct pt_layout {
   size_t weight_bytes;
   // KV arena
   int64_t kv_seq_elems;  // per (t, l, b, hkv): max_seq*hd (K) ; hd*s_pad (Vt)
-  size_t off_k, off_v, kv_bytes;
+  size_t off_k, off_v, off_seq, kv_bytes;   // off_seq: int4 [max_batch] per-sequence state of a ragged batch
+  int64_t s_k;                              // K rows per head and rotary-table rows: max_seq rounded up to 64
   size_t ws_bytes;    // workspace arena: a pt_workspace for M = max_batch * max_seq rows
   int32_t elem_size;  // 4 or 2
 };
@@ -69,6 +70,10 @@ struct pt_workspace {
   size_t off_m;       // dtype [T, rows, f]  SwiGLU product
   size_t off_part;    // fp32 split-K decode-attention partials, [T*B*H][max_splits][hd + 2]
   size_t off_skp;     // fp32 K slices of the decode residual GEMMs, [slice][T][rows][d]
+  size_t off_ss;      // fp32 [T, rows, d / 64] per-row partial sums of squares (RMSNorm folded into the GEMMs)
+  size_t off_rinv;    // fp32 [T, rows] 1/rms of every row, from those sums
+  size_t off_rowmap;  // int2 [rows] (sequence, position) of every row of a ragged batch
+  size_t off_rowidx;  // int32 [rows] packed row of every valid token, then [max_batch] last rows (ragged prefill)
   size_t bytes;
   int64_t skp_floats; // capacity behind off_skp
   int32_t max_splits; // capacity behind off_part, in splits per (track, sequence, head)
@@ -88,6 +93,13 @@ struct pt_prof {
   int64_t family[PT_K_COUNT][PT_FAMILY_COUNT] = {{0}};   // launches per kernel family (see pt_profile_paths)
 };
 
+// Per-sequence state of a ragged batch, on the host; the device copy (int4 per sequence: first row of the
+// padded-packed prefill layout, padded length, length, first token of the packed input) sits at the end of the
+// KV arena.
+struct pt_seq {
+  int32_t row0, plen, len, tok0;
+};
+
 struct pt_handle {
   pt_config cfg;
   pt_layout lay;
@@ -98,7 +110,9 @@ struct pt_handle {
   const pt_workspace* active;   // temporaries of the forward call in progress
   hipStream_t stream;
   int32_t batch;      // B of the live sequences (0: none)
-  int32_t seq_len;    // their common length
+  int32_t seq_len;    // their common length (the longest one when ragged)
+  bool ragged;        // the live sequences came from pt_prefill_ragged: per-sequence lengths in seqs / on the device
+  std::vector<pt_seq> seqs;
   int64_t merges;
   bool weights_ready;
   bool rope_ready;    // the rotary table and the device status word have been written
@@ -148,6 +162,12 @@ struct pt_gemm_args {
   // kv_head_elems = max_seq * hd elements of K and hd * s_pad elements of V^T
   int64_t kv_bstride, kv_seq_stride, kv_head_elems;
   int32_t H, Hkv, hd, S, pos0, s_pad;
+  // Ragged batches (sequences of different lengths): when row_map is given, row m belongs to sequence
+  // row_map[m].x at position row_map[m].y instead of (m / S, pos0 + m % S).  row_blocks != 0 promises that
+  // every aligned block of 32 rows lies in one sequence at consecutive positions starting at a multiple of 32
+  // (the padded-packed layout of a ragged prefill), which the LDS-staged QKV epilogue relies on.
+  const int2* row_map;
+  int32_t row_blocks;
   // K-slice scratch of the decode kernel, sk_part_floats floats (may be null: K is not split over workgroups)
   float* sk_part;
   int64_t sk_part_floats;
@@ -157,6 +177,19 @@ struct pt_gemm_args {
   const float* norm_gain;
   int64_t norm_bstride, norm_gbstride;
   float norm_eps;
+  // RMSNorm folded into the two GEMMs around it (MFMA tile kernels only, see pt_gemm_mfma_fold_parts).
+  //   producer, EPI_RESIDUAL: besides out, the kernel stores bf16(out[b][m][n] * nf_gain[b][n]) to nf_out [b][m][N]
+  //   and, per row, the sum of out^2 over each block of N / nf_parts columns to nf_ss[b][m][part];
+  //   pt_launch_row_inv_rms turns the partial sums into one factor 1 / sqrt(mean(out^2) + eps) per row;
+  //   consumer, EPI_QKV / EPI_SWIGLU: the accumulators of row m are multiplied by rs_inv[b][m] before the
+  //   epilogue (A then holds bf16(h * gain), unnormalised).
+  void* nf_out;
+  const float* nf_gain;
+  float* nf_ss;
+  int64_t nf_out_bstride, nf_gain_bstride, nf_ss_bstride;
+  int32_t nf_parts;
+  const float* rs_inv;
+  int64_t rs_bstride;
 };
 
 enum { PT_SK_PART_FLOATS = 16 << 20 };   // K-slice scratch inside the caller's workspace arena
@@ -168,6 +201,11 @@ int pt_launch_gemm_generic(const pt_gemm_args& g, hipStream_t s);
 // or the kernel family that was launched (the numbering of pt_profile_paths).
 // MFMA tile kernels: returns 1 when launched.
 int pt_launch_gemm_mfma(const pt_gemm_args& g, hipStream_t s);
+// For a residual GEMM that the MFMA tile kernels would run with an LDS-staged epilogue: the number of column
+// blocks per row whose sums of squares the kernel can emit (nf_parts), else 0.  Shape fields only.
+int pt_gemm_mfma_fold_parts(const pt_gemm_args& g);
+// True if the MFMA tile kernels cover the problem (shape fields only).
+bool pt_gemm_mfma_covers(const pt_gemm_args& g);
 // Weight-streaming kernel for M <= 64 (decode): returns 2, or 3 for its matrix-vector form (M <= 4).  With
 // allow_split a residual GEMM may leave pt_gemm_skinny_ksplit(g) > 1 K slices in g.sk_part
 // ([slice][batch][M][N] fp32) instead of writing out = res + product; pt_launch_resnorm adds them up.
@@ -193,6 +231,14 @@ struct pt_attn_args {
   int32_t dtype;
   float* partials;               // split-K workspace (decode)
   int32_t max_splits;
+  // Ragged batches.  Decode (S == 1): row_map[seq].y is the position of the new row of sequence seq (its cache
+  // holds that many older positions); max_pos is the largest of them.  Prefill: seq_info[seq] = (first row,
+  // padded length, length, first token) of the padded-packed layout, rows holds their total and max_plen the
+  // longest padded length; row m of q / o is packed row m.
+  const int2* row_map;
+  const int4* seq_info;
+  int32_t max_pos, max_plen;
+  int64_t rows;
 };
 
 int pt_launch_attn_generic(const pt_attn_args& a, hipStream_t s);
@@ -210,12 +256,29 @@ extern int pt_tune_skinny_plan;
 // flag: device status word; bit 0 is set when a token id lies outside [0, vocab)
 int pt_launch_embed(const void* embed, int32_t dtype, const int32_t* tokens, int64_t rows, int32_t d,
                     int32_t vocab, float* h, int32_t* flag, hipStream_t s);
+// Ragged prefill: packed row r of sequence (row_map[r].x) at position p takes token tokens[tok0 + p] when p <
+// len, else the zero vector (padding rows).
+int pt_launch_embed_ragged(const void* embed, int32_t dtype, const int32_t* tokens, const int2* row_map,
+                           const int4* seq_info, int64_t rows, int32_t d, int32_t vocab, float* h, int32_t* flag,
+                           hipStream_t s);
+// dst[t][r][:] = (position < length) ? src[t][tok0 + position][:] : 0 over the padded-packed rows (hidden-state input)
+int pt_launch_scatter_rows(const float* src, int64_t src_bstride, const int2* row_map, const int4* seq_info,
+                           int64_t rows, int32_t d, int32_t batch, float* dst, int64_t dst_bstride, hipStream_t s);
+// dst[i][:] = src[idx[i]][:] for i < n (fp32 rows of d elements)
+int pt_launch_gather_rows(const float* src, const int32_t* idx, int64_t n, int32_t d, float* dst, hipStream_t s);
+// Bookkeeping of a ragged batch from seq_info [B]: row_map [rows] of the padded-packed prefill layout, valid [sum
+// of lengths] (packed row of every real token, in input order) and last [B] (packed row of each last token).
+int pt_launch_ragged_maps(const int4* seq_info, int32_t B, int64_t rows, int2* row_map, int32_t* valid, int32_t* last,
+                          hipStream_t s);
+// Decode step of a ragged batch: row_map[b] = (b, length of b); with advance the lengths grow by one afterwards.
+int pt_launch_decode_rowmap(int4* seq_info, int32_t B, int2* row_map, hipStream_t s);
+int pt_launch_advance_lens(int4* seq_info, int32_t B, hipStream_t s);
 int pt_launch_rmsnorm(const float* h, int64_t h_bstride, const float* gains, int64_t g_bstride,
                       void* out, int64_t out_bstride, int32_t dtype, int32_t batch, int64_t rows,
                       int32_t d, float eps, hipStream_t s);
-// rows selected by index: out[r] = norm(h[row_index(r)]), row_index(r) = r * row_step + row_off
+// rows selected by index: out[r] = norm(h[row_index(r)]), row_index(r) = row_idx ? row_idx[r] : r * row_step + row_off
 int pt_launch_rmsnorm_rows(const float* h, const float* gain, void* out, int32_t dtype, int64_t rows,
-                           int64_t row_step, int64_t row_off, int32_t d, float eps, hipStream_t s);
+                           int64_t row_step, int64_t row_off, const int32_t* row_idx, int32_t d, float eps, hipStream_t s);
 int pt_launch_merge(const void* const* tracks, int32_t n, int64_t elems, int32_t dtype, float scale,
                     void* out, float* tap, hipStream_t s);
 int pt_launch_copy_f32(const float* src, float* dst, int64_t elems, hipStream_t s);
@@ -227,6 +290,8 @@ int pt_launch_resnorm(const float* part, int32_t slices, const float* res, int64
                       int64_t h_bstride, const float* gains, int64_t g_bstride, void* out, int64_t out_bstride,
                       int32_t batch, int64_t rows, int32_t d, float eps, hipStream_t s);
 int pt_launch_fill_f32(float* dst, int64_t n, float v, hipStream_t s);
+// out[r] = 1 / sqrt(sum_p ss[r][p] / d + eps) for r < rows (rows of all tracks back to back)
+int pt_launch_row_inv_rms(const float* ss, int32_t parts, int64_t rows, int32_t d, float eps, float* out, hipStream_t s);
 // Sets attribute hipFuncAttributeMaxDynamicSharedMemorySize once per kernel (thread-safe: the result is the
 // initialiser of a function-local static at the call site).
 #define PT_SET_MAX_LDS_ONCE(kern, bytes)                                                                   \
