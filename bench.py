@@ -17,12 +17,13 @@ resident in HBM before the timed region.  One JSON line is printed on stdout:
                 for the decode-attention kernel from in-run events): Large PT at batch 64, context 4096 with
                 2 KV heads per track (as written, with 16 KV heads, the cache would need 550 GB), Large PT as
                 written at batch 16, and one GPU's share of the wide model at batch 64, context 8192
-  legs          the other workloads on the same kernels: share prefill 2 x 4096, Mid PT prefill 4 x 1024 and
-                Mid PT decode (batch 32, 2048-token prompts, 128 steps)
+  legs          the other workloads on the same kernels: share prefill 2 x 4096, Mid PT prefill 4 x 1024, Mid PT
+                decode (batch 32, 2048-token prompts, 128 steps) and the throughput mode (Mid PT, batch 256 of
+                mixed lengths: ragged prefill and decode)
   cpu_baseline  the CPU oracle (numpy float64) on a stated, bounded sample of the headline workload
 
 --legs selects a subset (comma list of large-prefill, large-decode-gqa, large-decode-mha, share-prefill,
-share-decode, mid-prefill, mid-decode, cpu; default all), which is how the per-kernel profiles under
+share-decode, mid-prefill, mid-decode, throughput, cpu; default all), which is how the per-kernel profiles under
 profiles/ are taken.  Other modes: --paper-sweep (batch-1 latency over input lengths), --ceilings (sustained
 MFMA and HBM-read rates of two bare loops).
 """
@@ -40,7 +41,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
 
 ALL_LEGS = ["large-prefill", "large-decode-gqa", "large-decode-mha", "share-prefill", "share-decode",
-            "mid-prefill", "mid-decode", "cpu"]
+            "mid-prefill", "mid-decode", "throughput", "cpu"]
 PREFILL_CLASSES = ["embed", "rmsnorm", "gemm_qkv", "attn_prefill", "gemm_out", "gemm_gateup", "gemm_down",
                    "merge", "gemm_head"]
 DECODE_CLASSES = ["embed", "rmsnorm", "gemm_qkv", "attn_decode", "gemm_out", "gemm_gateup", "gemm_down",
@@ -262,6 +263,68 @@ def run_decode_leg(torch, PB, I, name, cfg, B, ctx, seed, steps, warmup, token_s
         rec["note"] = note
     log("%s: %.3f ms/step median, %.0f GB/s of algorithmic bytes (%.1f%% of HBM peak), attention %.0f GB/s" % (
         name, med, rec["step_GBs"], 100 * rec["step_frac_of_hbm_peak"], gbs))
+    return rec
+
+
+def run_throughput_leg(torch, PB, I, steps):
+    """Throughput-mode shape of the paper's serving tables (Section 3.3, Tables 5 and 8: maximum batch 256, inputs
+    of mixed lengths) on the Mid PT model: 256 sequences of 64 .. 2048 tokens (seeded, uniform) in one ragged
+    prefill, then KV-cached decode steps at batch 256, every sequence at its own position."""
+    import numpy as np
+    B = 256
+    cfg = I.config_mid(max_batch=B, max_seq=2048 + steps + 8)
+    lens = [int(x) for x in 64 + I.make_tokens(6, 1, B, 2048 - 64 + 1)[0]]
+    n = sum(lens)
+    padded = sum((x + 63) // 64 * 64 for x in lens)
+    tok = I.make_tokens(6, 1, n, cfg.vocab, stream=1)[0]
+    model = PB.PTModel(cfg)
+    model.pt_init_weights(1)
+    tokens = torch.from_numpy(tok).cuda()
+    logits = torch.empty((B, cfg.vocab), dtype=torch.float32, device="cuda")
+    nxt = torch.empty((B,), dtype=torch.int32, device="cuda")
+    run = lambda: model.pt_prefill_ragged(lens, tokens=tokens, logits_mode=PB.PT_LOGITS_LAST, logits_out=logits)
+    run()
+    torch.cuda.synchronize()
+    reps = 3
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        run()
+    torch.cuda.synchronize()
+    pre_s = (time.perf_counter() - t0) / reps
+    PB.pt_argmax(logits, nxt, model.stream)
+    step = lambda: model.pt_decode_step(nxt, logits_out=logits, argmax_out=nxt, want_argmax=True)
+    for _ in range(2):
+        step()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    ev[0].record(model.stream)
+    for i in range(steps):
+        step()
+        ev[i + 1].record(model.stream)
+    torch.cuda.synchronize()
+    model.pt_sync_status()
+    per = [ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]
+    med = median(per)
+    # algorithmic work: GEMMs on the real tokens, causal attention over each sequence's own length
+    T, L, d, f = cfg.n_tracks, cfg.n_layers, cfg.d_model, cfg.d_ffn
+    hq, hk = cfg.n_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
+    flops = T * L * (2.0 * n * (d * (hq + 2 * hk) + hq * d + 3 * d * f) + 2.0 * sum(x * x for x in lens) * hq) + 2.0 * B * d * cfg.vocab
+    ctx = sum(lens) / B + 2 + steps / 2
+    wbytes, kv_step, _ = decode_bytes(cfg, B, ctx)
+    fam = {c: family_report(model, c) for c in ("attn_prefill", "attn_decode", "gemm_gateup")}
+    model.close()
+    del model
+    torch.cuda.empty_cache()
+    rec = {"workload": "Mid PT, throughput mode: batch 256, input lengths uniform in 64..2048 (seed 6), ragged prefill "
+                       "then %d decode steps" % steps,
+           "batch": B, "tokens": n, "padded_rows": padded, "min_len": min(lens), "max_len": max(lens),
+           "prefill_ms": pre_s * 1e3, "prefill_tokens_per_s": n / pre_s, "prefill_TFLOP/s": flops / pre_s / 1e12,
+           "prefill_frac_of_mfma_peak": flops / pre_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+           "decode_ms_per_step_median": med, "decode_ms_per_step_min": min(per), "decode_tokens_per_s": B / (med * 1e-3),
+           "decode_step_GBs": (wbytes + kv_step) / (med * 1e-3) / 1e9,
+           "decode_frac_of_hbm_peak": (wbytes + kv_step) / (med * 1e-3) / 1e9 / HBM_PEAK_GBS, "kernel_family": fam}
+    log("throughput mode (batch 256, %d tokens): prefill %.1f ms, %.0f tokens/s (%.1f%% of MFMA peak); decode %.2f ms/step, "
+        "%.0f tokens/s (%.1f%% of HBM peak)" % (n, rec["prefill_ms"], rec["prefill_tokens_per_s"], 100 * rec["prefill_frac_of_mfma_peak"],
+                                                med, rec["decode_tokens_per_s"], 100 * rec["decode_frac_of_hbm_peak"]))
     return rec
 
 
@@ -489,6 +552,8 @@ def main():
             torch, PB, I, "Mid PT decode: batch 32, 2048-token prompts, %d KV-cached steps" % args.mid_decode_steps,
             I.config_mid(max_batch=32, max_seq=2048 + args.mid_decode_steps + 64), 32, 2048, 1,
             args.mid_decode_steps, 2, token_seed=2, traffic_file="mid_decode_attn_traffic.json")
+    if "throughput" in legs:
+        other["throughput_mode"] = run_throughput_leg(torch, PB, I, 16)
     cpu = run_cpu_baseline(I) if "cpu" in legs else None
 
     cfg = I.config_large()

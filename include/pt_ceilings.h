@@ -26,7 +26,8 @@ int pt_ceiling_mfma_bf16(const void* dev_operands, void* dev_sink, int32_t waves
                          int32_t reps, void* hip_stream, double* tflops);
 
 /* Streaming read of `bytes` (a multiple of 1 MiB) from dev_src with 16-byte loads, every byte once;
- * dev_sink: at least 4 MiB.  *gbs receives bytes / time in GB/s. */
+ * dev_sink: at least 4 MiB.  Grids of 4 to 64 workgroups per compute unit are tried; *gbs receives the best
+ * bytes / time in GB/s. */
 int pt_ceiling_hbm_read(const void* dev_src, size_t bytes, void* dev_sink, int32_t reps, void* hip_stream,
                         double* gbs);
 

@@ -177,7 +177,8 @@ def logits_from_hidden(cfg, W, h: np.ndarray) -> np.ndarray:
 
 
 def pt_prefill(cfg, W, state: PTState, tokens: Optional[np.ndarray] = None,
-               hidden_in: Optional[np.ndarray] = None, collect_taps: bool = False):
+               hidden_in: Optional[np.ndarray] = None, collect_taps: bool = False,
+               lengths: Optional[np.ndarray] = None):
     """Prefill a batch from position 0.
 
     tokens [B, S] int, or hidden_in [B, S, d] (same input for every track) or
@@ -185,6 +186,11 @@ def pt_prefill(cfg, W, state: PTState, tokens: Optional[np.ndarray] = None,
     activation of Algorithm 1), ``logits`` [B, S, V] when the model has a vocabulary, and,
     if requested, ``taps``: per sequence, the merged activation after every block, and
     ``track_taps``: per sequence, the per-track activations right before every merge.
+
+    ``lengths`` [B] (optional) makes the batch ragged: sequence b consists of the first
+    lengths[b] of its S rows only (the throughput mode of Section 3.3 batches inputs of mixed
+    lengths); Algorithm 1 runs on exactly those rows, the rest of ``hidden`` / ``logits`` is
+    NaN, taps hold lengths[b] rows, and decoding continues at position lengths[b].
     """
     T, d = cfg.n_tracks, cfg.d_model
     if tokens is not None:
@@ -193,21 +199,22 @@ def pt_prefill(cfg, W, state: PTState, tokens: Optional[np.ndarray] = None,
     else:
         hidden_in = np.asarray(hidden_in, dtype=F64)
         B, S = hidden_in.shape[-3], hidden_in.shape[-2]
-    hidden = np.empty((B, S, d), dtype=F64)
+    hidden = np.full((B, S, d), np.nan, dtype=F64)
     all_taps, all_track_taps = [], []
-    pos = np.arange(S)
     for b in range(B):
+        n = S if lengths is None else int(lengths[b])
+        pos = np.arange(n)
         if tokens is not None:
-            x = _f64(W["embed"][tokens[b]])
+            x = _f64(W["embed"][tokens[b, :n]])
             xs = [x] * T
         elif hidden_in.ndim == 3:
-            xs = [hidden_in[b]] * T
+            xs = [hidden_in[b, :n]] * T
         else:
-            xs = [hidden_in[i, b] for i in range(T)]
+            xs = [hidden_in[i, b, :n] for i in range(T)]
         taps = [] if collect_taps else None
         ttaps = [] if collect_taps else None
-        hidden[b] = _run_rows(cfg, W, state, xs, b, pos, taps, ttaps)
-        state.length[b] = S
+        hidden[b, :n] = _run_rows(cfg, W, state, xs, b, pos, taps, ttaps)
+        state.length[b] = n
         all_taps.append(taps)
         all_track_taps.append(ttaps)
     state.merge_count += cfg.n_layers // cfg.block_depth

@@ -262,6 +262,40 @@ def test_cached_decode_from_hidden_states_equals_full_recompute(per_track):
         assert not np.allclose(c["hidden"], full["hidden"][:, 5])
 
 
+def test_ragged_batch_equals_each_sequence_alone():
+    """A batch of mixed lengths (the paper's throughput mode batches such inputs): every sequence of the ragged
+    batch equals the same sequence run alone, in prefill and in the cached decode steps that follow, each at its
+    own position; rows beyond a sequence's length do not exist."""
+    cfg = cfg_of()
+    W = rand_weights(cfg)
+    rng = np.random.default_rng(21)
+    lens = [7, 3, 10, 1]
+    tokens = rng.integers(0, cfg.vocab, (4, 10))
+    nxt = rng.integers(0, cfg.vocab, (2, 4))
+    st = O.PTState(cfg, 4, 16)
+    rag = O.pt_prefill(cfg, W, st, tokens=tokens, lengths=np.array(lens), collect_taps=True)
+    assert list(st.length) == lens
+    steps = [O.pt_decode_step(cfg, W, st, tokens=nxt[i]) for i in range(2)]
+    assert list(st.length) == [n + 2 for n in lens]
+    for b, n in enumerate(lens):
+        one, st1 = prefill(cfg, W, tokens[b:b + 1, :n], taps=True, max_seq=16)
+        # the head is one library product over the whole batch: equal up to its blocking, not bit for bit
+        np.testing.assert_allclose(rag["logits"][b, :n], one["logits"][0], rtol=1e-12, atol=1e-13)
+        assert np.array_equal(rag["hidden"][b, :n], one["hidden"][0])
+        assert np.all(np.isnan(rag["logits"][b, n:]))
+        for k in range(cfg.n_layers // cfg.block_depth):
+            assert rag["taps"][b][k].shape == (n, cfg.d_model)
+            assert np.array_equal(rag["taps"][b][k], one["taps"][0][k])
+        for i in range(2):
+            s1 = O.pt_decode_step(cfg, W, st1, tokens=nxt[i, b:b + 1])
+            assert np.array_equal(steps[i]["hidden"][b], s1["hidden"][0])
+            np.testing.assert_allclose(steps[i]["logits"][b], s1["logits"][0], rtol=1e-12, atol=1e-13)
+        # and the decode steps continue the sequence: they equal a prefill of the extended sequence
+        ext = np.concatenate([tokens[b, :n], nxt[:, b]])[None]
+        full, _ = prefill(cfg, W, ext)
+        np.testing.assert_allclose(steps[1]["logits"][b], full["logits"][0, n + 1], rtol=1e-10, atol=1e-11)
+
+
 def test_batch_independence():
     cfg = cfg_of()
     W = rand_weights(cfg)
