@@ -474,7 +474,7 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=16, help="timed decode steps of the large decode legs")
     ap.add_argument("--mid-decode-steps", type=int, default=128)
     ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run a plain 1 GiB device copy three times (reference for the HBM byte counters)")
+                    help="also run a plain 1 GiB device copy kernel (reference for the HBM byte counters of a rocprofv3 --pmc pass)")
     ap.add_argument("--ceilings", action="store_true",
                     help="instead of the benchmark: sustained MFMA / HBM / LDS rates of bare loops (one JSON line)")
     ap.add_argument("--paper-sweep", action="store_true",
@@ -502,10 +502,15 @@ def main():
         sys.exit(2)
     PB.lib()
     if args.copy_calibration:
+        # the plain copy kernel of known size that the HBM byte counters are scaled by: 1 GiB read, 1 GiB written
+        import ctypes as C
+        L = C.CDLL(os.path.join(ROOT, "paper_2602_07306_amd", "libpt_ceilings.so"))
+        L.pt_ceiling_hbm_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.POINTER(C.c_double)]
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
+        v = C.c_double()
+        if L.pt_ceiling_hbm_copy(src.data_ptr(), dst.data_ptr(), 1 << 30, 2, torch.cuda.current_stream().cuda_stream, C.byref(v)) != 0:
+            raise RuntimeError("copy calibration failed")
         torch.cuda.synchronize()
         del src, dst
     if args.ceilings:

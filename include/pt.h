@@ -247,8 +247,11 @@ int pt_profile_paths(pt_handle* h, int32_t kernel_class, int64_t* counts);
  *   PT_TUNE_FOLD_RMSNORM       value 1 (default): in prefill the RMSNorm between two GEMMs is folded into
  *                              them (scaled bf16 copy and row sums from the producer's epilogue, row factor in
  *                              the consumer's); 0: a separate RMSNorm kernel runs instead
+ *   PT_TUNE_ATTN_PREFILL       value 0 (default): the LDS-tiled flash prefill kernel; 1: its software-pipelined
+ *                              form (8 wavefronts per workgroup, four direct-to-LDS stages, softmax slices
+ *                              interleaved with the MFMAs; measured slower, kept for comparison)
  * Not thread-safe against concurrent forward calls.  Errors: INVALID_ARGUMENT (unknown knob). */
-enum { PT_TUNE_GEMM_TILE_CONFIG = 0, PT_TUNE_SKINNY_PLAN = 1, PT_TUNE_FOLD_RMSNORM = 2 };
+enum { PT_TUNE_GEMM_TILE_CONFIG = 0, PT_TUNE_SKINNY_PLAN = 1, PT_TUNE_FOLD_RMSNORM = 2, PT_TUNE_ATTN_PREFILL = 3 };
 int pt_set_tuning(int32_t knob, int32_t value);
 
 const char* pt_last_error(void);

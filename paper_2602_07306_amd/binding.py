@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libpt.so")
 
 PT_LOGITS_NONE, PT_LOGITS_LAST, PT_LOGITS_ALL = 0, 1, 2
 PT_FAMILY_GENERIC, PT_FAMILY_COUNT = 0, 4
-PT_TUNE_GEMM_TILE_CONFIG, PT_TUNE_SKINNY_PLAN, PT_TUNE_FOLD_RMSNORM = 0, 1, 2
+PT_TUNE_GEMM_TILE_CONFIG, PT_TUNE_SKINNY_PLAN, PT_TUNE_FOLD_RMSNORM, PT_TUNE_ATTN_PREFILL = 0, 1, 2, 3
 PT_PATH_AUTO, PT_PATH_GENERIC = 0, 1
 PT_W_EMBED, PT_W_HEAD, PT_W_Q, PT_W_K, PT_W_V, PT_W_O, PT_W_G, PT_W_U, PT_W_D, PT_W_G1, PT_W_G2, PT_W_GF = range(1, 13)
 WEIGHT_IDS = {"embed": PT_W_EMBED, "head": PT_W_HEAD, "wq": PT_W_Q, "wk": PT_W_K, "wv": PT_W_V,

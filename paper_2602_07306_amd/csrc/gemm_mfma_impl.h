@@ -62,28 +62,52 @@ struct tile_coord {
   int b, tm, tn;
 };
 
-// Workgroup ids are dealt round-robin to the 8 XCDs (XCD = id % 8).  Regrouping them so that each XCD
-// (own L2) walks a contiguous range of logical tile ids keeps the A and W slabs that concurrently
-// resident workgroups of one XCD share few.
-__device__ __forceinline__ int logical_tile(int id, int total) {
-  return (total & 7) == 0 ? (id & 7) * (total >> 3) + (id >> 3) : id;
-}
-
-// Logical id -> (track, m-tile, n-tile): groups of 4 m-tiles x all n-tiles, column-major inside a
-// group, so that concurrently resident workgroups share few A and W slabs.
-__device__ __forceinline__ tile_coord decode_tile(int id, int tiles_m, int tiles_n) {
-  const int per_b = tiles_m * tiles_n;
+// Workgroup ids are dealt round-robin to the 8 XCDs (XCD = id % 8), each with its own L2; workgroups of one XCD
+// start in id order.  map_tile turns a workgroup id into (track, m-tile, n-tile) such that
+//  - the 32 tiles an XCD has in flight form a block of 4 m-tiles x 8 n-tiles (column-major walk through groups of
+//    4 m-tiles x all n-tiles): every chunk of A is shared by 8 and every chunk of W by 4 of its workgroups;
+//  - when a track's tile grid divides evenly over the XCDs, all XCDs work on the same track at the same time,
+//    each on its own range of m-tiles (and, for few m-tiles, of n-tiles).  The weight matrix of that track is then the only W in flight on the whole
+//    chip: the Infinity Cache holds it, so the re-reads of W by later m-tile groups stay out of HBM (with one track
+//    per XCD, eight weight matrices stream at once and every re-read goes to HBM).
+__device__ __forceinline__ tile_coord decode_group(int r, int first_m, int tiles_m, int tiles_n) {
   tile_coord c;
-  c.b = id / per_b;
-  int r = id - c.b * per_b;
+  c.b = 0;
   const int GMg = 4;
   const int group_sz = GMg * tiles_n;
   const int grp = r / group_sz;
-  const int first_m = grp * GMg;
-  const int rows_in = min(GMg, tiles_m - first_m);
+  const int gm = grp * GMg;
+  const int rows_in = min(GMg, tiles_m - gm);
   r -= grp * group_sz;
-  c.tm = first_m + r % rows_in;
+  c.tm = first_m + gm + r % rows_in;
   c.tn = r / rows_in;
+  return c;
+}
+
+__device__ __forceinline__ tile_coord map_tile(int id, int total, int tiles_m, int tiles_n) {
+  const int per_b = tiles_m * tiles_n;
+  tile_coord c;
+  // Split of a track's tile grid over the 8 XCDs, xm ranges of m-tiles by 8 / xm ranges of n-tiles: the most ranges
+  // of m-tiles that still leave every XCD four m-tiles (a full 4 x 8 block in flight).
+  int xm = 0;
+#pragma unroll
+  for (int t = 8; t >= 1; t >>= 1)
+    if (xm == 0 && tiles_m % t == 0 && tiles_m / t >= 4 && tiles_n % (8 / t) == 0) xm = t;
+  if (xm > 0) {
+    const int xcd = id & 7, j = id >> 3;          // j-th workgroup of this XCD
+    const int per_x = per_b >> 3;                  // tiles of one track that this XCD owns
+    const int b = j / per_x;
+    const int tm_per = tiles_m / xm, tn_per = tiles_n / (8 / xm);
+    c = decode_group(j - b * per_x, (xcd % xm) * tm_per, tm_per, tn_per);
+    c.tn += (xcd / xm) * tn_per;
+    c.b = b;
+    return c;
+  }
+  // contiguous range of logical ids per XCD
+  const int lid = (total & 7) == 0 ? (id & 7) * (total >> 3) + (id >> 3) : id;
+  const int b = lid / per_b;
+  c = decode_group(lid - b * per_b, 0, tiles_m, tiles_n);
+  c.b = b;
   return c;
 }
 
@@ -445,7 +469,7 @@ gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
   bf16_t* Bs = As + 2 * BM * BK;      // [2][BN][BK]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
-  const tile_coord tc = decode_tile(logical_tile(blockIdx.x, gridDim.x), tiles_m, tiles_n);
+  const tile_coord tc = map_tile(blockIdx.x, gridDim.x, tiles_m, tiles_n);
   const int m0 = tc.tm * BM, n0 = tc.tn * BN, b = tc.b;
 
   // folded RMSNorm, consumer side: one factor per tile row (1/rms of the row, from pt_launch_row_inv_rms).  The
@@ -625,7 +649,7 @@ gemm_dl_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
-  const tile_coord tc = decode_tile(logical_tile(blockIdx.x, gridDim.x), tiles_m, tiles_n);
+  const tile_coord tc = map_tile(blockIdx.x, gridDim.x, tiles_m, tiles_n);
   const int m0 = tc.tm * BM, n0 = tc.tn * BN, b = tc.b;
   const int KT = g.K / BK;   // multiple of 4
 

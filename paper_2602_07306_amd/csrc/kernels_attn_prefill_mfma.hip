@@ -16,10 +16,20 @@
 // Key order inside a block: MFMA row r of S^T is loaded from key pi(r) (r with bits 2 and 3 swapped),
 // which makes the 8 probabilities a half-wave feeds to one PV MFMA eight consecutive keys - one 16-byte
 // read of a V^T row.
+#include <type_traits>
+
 #include "pt_device.h"
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (N > 0) {
+    static_for<N - 1>(f);
+    f(std::integral_constant<int, N - 1>{});
+  }
+}
 
 union pk8 {
   bf16x8_t v;
@@ -351,16 +361,293 @@ __global__ void __launch_bounds__(256, HD == 64 ? 3 : 2) attn_prefill_lds_kernel
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Software-pipelined form of the LDS-tiled kernel.  Same tiling (128 queries per workgroup, 32 per wavefront, key
+// tiles of 64, transposed products), but the two matrix products of a tile no longer wait for the softmax between
+// them; a wavefront issues instructions in order, so vector work only overlaps matrix work when the two are
+// interleaved in the instruction stream:
+//   phase A  the score product of tile t+1 (K_{t+1} . Q^T) is issued one MFMA at a time, and after every MFMA a
+//            slice of tile t's softmax (scale, exp2, row sum, bf16 packing) follows;
+//   phase B  the value product of tile t (V^T_t . P^T_t) is issued the same way, with the running-maximum search
+//            over the fresh scores of tile t+1 between its MFMAs.
+// K and V^T tiles arrive by direct global -> LDS loads (no staging registers, which the second set of score
+// registers needs), two tiles ahead for K and one ahead for V^T, with one barrier per tile.
+// ------------------------------------------------------------------------------------------------
+template <int HD, int NW, int NSTG>
+__global__ void __launch_bounds__(NW * 64, 2) attn_prefill_pipe_kernel(const pt_attn_args a, int nqb) {
+  constexpr int QB = NW * 32;           // queries per workgroup
+  constexpr int LEAD = NSTG - 1;        // tiles a load is issued ahead of its use
+  constexpr int KS = HD / 16;           // MFMAs per 32-key block of S^T
+  constexpr int HB = HD / 32;           // 32-row blocks of O^T
+  constexpr int NS = 2 * KS;            // score MFMAs per tile
+  constexpr int NPV = HB * 4;           // value MFMAs per tile
+  constexpr int KROWB = HD * 2;         // bytes of a K row
+  constexpr int K_CPR = KROWB / 16;     // 16-byte chunks per K row
+  constexpr int K_RPI = 64 / K_CPR;     // K rows per direct-load instruction (64 lanes x 16 B = 1 KiB)
+  constexpr int K_NI = 64 / K_RPI / NW; // direct-load instructions per wavefront for a K tile
+  constexpr int V_NI = HD / 8 / NW;     // ... for a V^T tile (rows of 128 B: 8 per instruction)
+  static_assert(K_NI >= 1 && V_NI >= 1, "more wavefronts than direct-load instructions per tile");
+  constexpr int TILE_B = 64 * HD * 2;   // bytes of a K tile = bytes of a V^T tile
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  unsigned char* Ks = smem;                     // [NSTG][64][HD]
+  unsigned char* Vs = smem + NSTG * TILE_B;     // [NSTG][HD][64]
+  auto kswz = [](int row) { return HD == 64 ? ((row >> 1) & 7) : (row & 15); };
+  auto vswz = [](int row) { return (row >> 1) & 7; };
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int combos = a.n_tracks * a.B * a.H;
+  int combo, qb;
+  if ((combos & 7) == 0) {
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    combo = xcd + 8 * (j / nqb);
+    qb = nqb - 1 - (j % nqb);
+  } else {
+    combo = blockIdx.x / nqb;
+    qb = nqb - 1 - (blockIdx.x % nqb);
+  }
+  const int q0 = qb * QB + wave * 32;
+  const int head = combo % a.H;
+  const int tb = combo / a.H;
+  const int t_ = tb / a.B, seq = tb - t_ * a.B;
+  const int kvh = head / (a.H / a.Hkv);
+  int64_t row0 = (int64_t)seq * a.S;
+  int slen = a.S;
+  if (a.seq_info) {
+    const int4 si = a.seq_info[seq];
+    row0 = si.x;
+    slen = si.y;
+    if (qb * QB >= slen) return;
+  }
+  const int64_t hidx = t_ * a.kv_bstride + seq * a.kv_seq_stride + kvh;
+  const char* K = (const char*)((const bf16_t*)a.kc + hidx * a.kv_head_elems);
+  const char* Vt = (const char*)((const bf16_t*)a.vc + hidx * ((int64_t)HD * a.s_pad));
+  const bool active = q0 < slen;
+  const int64_t row = row0 + min(q0 + l32, slen - 1);
+  const int64_t qoff = t_ * a.q_bstride + row * (a.H * HD) + head * HD;
+
+  bf16x8_t qf[KS];
+#pragma unroll
+  for (int kk = 0; kk < KS; ++kk) qf[kk] = *(const bf16x8_t*)((const bf16_t*)a.q + qoff + kk * 16 + half * 8);
+
+  const int ntiles = min(qb * QB + QB, slen) / 64;                // key tiles the workgroup walks
+  const int nt_w = active ? min(ntiles, (q0 + 31) / 64 + 1) : 0;  // ... of which this wavefront needs the first nt_w
+
+  // direct loads: instruction i of this wavefront covers rows (wave * NI + i) * RPI ... of the tile; a lane fetches
+  // the logical chunk that belongs at its LDS position under the XOR swizzle
+  typedef const __attribute__((address_space(1))) void* gptr_t;
+  typedef __attribute__((address_space(3))) void* lptr_t;
+  uint32_t k_off[K_NI], v_off[V_NI];
+#pragma unroll
+  for (int i = 0; i < K_NI; ++i) {
+    const int r = (wave * K_NI + i) * K_RPI + lane / K_CPR;
+    k_off[i] = (uint32_t)(r * KROWB + (((lane % K_CPR) ^ kswz(r)) * 16));
+  }
+#pragma unroll
+  for (int i = 0; i < V_NI; ++i) {
+    const int r = (wave * V_NI + i) * 8 + (lane >> 3);
+    v_off[i] = (uint32_t)(r * a.s_pad * 2 + (((lane & 7) ^ vswz(r)) * 16));
+  }
+  auto load_k = [&](int tile, int buf) {
+#pragma unroll
+    for (int i = 0; i < K_NI; ++i)
+      __builtin_amdgcn_global_load_lds((gptr_t)(K + (size_t)tile * TILE_B + k_off[i]),
+                                       (lptr_t)(Ks + buf * TILE_B + (wave * K_NI + i) * 1024), 16, 0, 0);
+  };
+  auto load_v = [&](int tile, int buf) {
+#pragma unroll
+    for (int i = 0; i < V_NI; ++i)
+      __builtin_amdgcn_global_load_lds((gptr_t)(Vt + (size_t)tile * 128 + v_off[i]),
+                                       (lptr_t)(Vs + buf * TILE_B + (wave * V_NI + i) * 1024), 16, 0, 0);
+  };
+
+  // fragment addresses: K row pi(l32) (+32 for the second block), 16-byte chunk (2 kk + half) ^ swizzle; the swizzle of
+  // a lane's row is the same in both blocks, so one XOR with a per-lane constant forms every chunk index
+  const int krow = (l32 & ~12) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);   // MFMA row r of S^T holds key pi(r)
+  const int k_base = krow * KROWB, k_x = half ^ kswz(krow);
+  const int v_base = l32 * 128, v_x = half ^ vswz(l32);                  // rows l32 + 32 hb share the swizzle
+  auto k_frag = [&](const unsigned char* Kt, int j) {   // j = rb * KS + kk
+    const int rb = j / KS, kk = j % KS;
+    return *(const bf16x8_t*)(Kt + rb * 32 * KROWB + k_base + (((2 * kk) ^ k_x) * 16));
+  };
+  auto v_frag = [&](const unsigned char* Vtile, int j) {   // j = hb * 4 + st
+    const int hb = j / 4, st = j % 4;
+    return *(const bf16x8_t*)(Vtile + hb * 32 * 128 + v_base + (((2 * st) ^ v_x) * 16));
+  };
+
+  const float c_log2 = 1.4426950408889634f / sqrtf((float)HD);
+  const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  f32x16_t oacc[HB];
+#pragma unroll
+  for (int hb = 0; hb < HB; ++hb) oacc[hb] = zero16;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  // register v of score block rb: key tile * 64 + rb * 32 + 16 (v / 8) + 8 half + v % 8, query q0 + l32
+  auto mask_tile = [&](f32x16_t (&s)[2], int tile) {
+    if (tile * 64 + 63 > q0) {
+      const int qrel = q0 + l32 - tile * 64;
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          if (rb * 32 + 16 * (v >> 3) + 8 * half + (v & 7) > qrel) s[rb][v] = -INFINITY;
+    }
+  };
+  // The reference of the exponentials moves to a new maximum only when that exceeds it by more than 8 binary orders
+  // (always on the first tile); until then the probabilities stay below 2^8, which fp32 sums and bf16 operands hold,
+  // and the accumulators need no rescaling.
+  auto new_reference = [&](float mx) {
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const bool grow = (mx - m_run) * c_log2 > 8.0f;
+    if (__any(grow)) {
+      const float m_new = grow ? mx : m_run;
+      const float corr = __builtin_amdgcn_exp2f((m_run - m_new) * c_log2);
+      l_run *= corr;
+      m_run = m_new;
+#pragma unroll
+      for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) oacc[hb][v] *= corr;
+    }
+  };
+
+  // prologue: V^T of tiles 0 .. LEAD-1 and K of tiles 0 .. LEAD into LDS (tile u lives in stage u % NSTG), scores of tile 0
+#pragma unroll
+  for (int u = 0; u < NSTG; ++u) {
+    if (u < ntiles) load_k(u, u);
+    if (u < LEAD && u < ntiles) load_v(u, u);
+  }
+  asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+  f32x16_t s_a[2], s_b[2];
+  if (nt_w > 0) {
+#pragma unroll
+    for (int j = 0; j < NS; ++j) s_a[j / KS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_frag(Ks, j), qf[j % KS], j % KS == 0 ? zero16 : s_a[j / KS], 0, 0, 0);
+    mask_tile(s_a, 0);
+    float mx = -INFINITY;
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s_a[rb][v]);
+    new_reference(mx);
+  }
+  __syncthreads();   // every wavefront has read tile 0 of K: its buffer may be refilled
+
+  // one tile: s_cur holds the scores of tile t (reference already moved), s_nxt receives those of tile t + 1.
+  // NXT: this wavefront also needs tile t + 1.  Operand fragments are read from LDS three MFMAs ahead.
+  constexpr int PF = 3;   // fragment ring depth
+  auto compute = [&](auto NXT_, f32x16_t (&s_cur)[2], f32x16_t (&s_nxt)[2], const unsigned char* Kn, const unsigned char* Vc, int t) {
+    constexpr bool NXT = decltype(NXT_)::value;
+    const float mc = m_run * c_log2;
+    float psum = 0.f;
+    pk8 pf[4];
+    bf16x8_t fr[PF];
+    // ---- phase A: score MFMAs of tile t + 1, a slice of tile t's exponentials after each
+    constexpr int CH = 32 / NS;   // scores per slice
+    if constexpr (NXT) {
+#pragma unroll
+      for (int j = 0; j < PF - 1; ++j) fr[j] = k_frag(Kn, j);
+    }
+    static_for<NS>([&](auto J) {
+      constexpr int j = decltype(J)::value;
+      if constexpr (NXT) {
+        if constexpr (j + PF - 1 < NS) fr[(j + PF - 1) % PF] = k_frag(Kn, j + PF - 1);
+        s_nxt[j / KS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j % PF], qf[j % KS], j % KS == 0 ? zero16 : s_nxt[j / KS], 0, 0, 0);
+      }
+      static_for<CH / 2>([&](auto C_) {
+        constexpr int idx = j * CH + 2 * decltype(C_)::value;   // score pair (idx, idx + 1): block idx / 16, register idx % 16
+        constexpr int rb = idx / 16, v = idx % 16;
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(s_cur[rb][v], c_log2, -mc));
+        const float p1 = __builtin_amdgcn_exp2f(fmaf(s_cur[rb][v + 1], c_log2, -mc));
+        psum += p0 + p1;
+        pf[idx / 8].u[(idx % 8) / 2] = pack_bf16x2(p0, p1);
+      });
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    l_run += psum;
+    // ---- phase B: value MFMAs of tile t, a slice of the maximum search over tile t + 1 after each
+    if constexpr (NXT) mask_tile(s_nxt, t + 1);
+    float mx = -INFINITY;
+    constexpr int MCH = 32 / NPV;
+#pragma unroll
+    for (int j = 0; j < PF - 1; ++j) fr[j] = v_frag(Vc, j);
+    static_for<NPV>([&](auto J) {
+      constexpr int j = decltype(J)::value;
+      if constexpr (j + PF - 1 < NPV) fr[(j + PF - 1) % PF] = v_frag(Vc, j + PF - 1);
+      oacc[j / 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j % PF], pf[j % 4].v, oacc[j / 4], 0, 0, 0);
+      if constexpr (NXT) {
+        static_for<MCH>([&](auto C_) {
+          constexpr int idx = j * MCH + decltype(C_)::value;
+          mx = fmaxf(mx, s_nxt[idx / 16][idx % 16]);
+        });
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    if constexpr (NXT) new_reference(mx);
+  };
+  auto iteration = [&](f32x16_t (&s_cur)[2], f32x16_t (&s_nxt)[2], int t) {
+    // K of tile t + LEAD + 1 replaces K of tile t (read one iteration ago), V^T of tile t + LEAD that of tile t - 1
+    const bool more_k = t + LEAD + 1 < ntiles, more_v = t + LEAD < ntiles;
+    if (more_k) load_k(t + LEAD + 1, (t + LEAD + 1) % NSTG);
+    if (more_v) load_v(t + LEAD, (t + LEAD) % NSTG);
+    const unsigned char* Kn = Ks + ((t + 1) % NSTG) * TILE_B;
+    const unsigned char* Vc = Vs + (t % NSTG) * TILE_B;
+    if (t + 1 < nt_w) compute(std::true_type{}, s_cur, s_nxt, Kn, Vc, t);
+    else if (t < nt_w) compute(std::false_type{}, s_cur, s_nxt, Kn, Vc, t);
+    // the next iteration needs K of tile t + 2 and V^T of tile t + 1: everything but the loads of the last LEAD - 1
+    // iterations (loads complete in order); near the end, where fewer loads are issued, simply everything
+    if (more_k && more_v) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((LEAD - 1) * (K_NI + V_NI)) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+  };
+  for (int t = 0; t < ntiles; t += 2) {
+    iteration(s_a, s_b, t);
+    if (t + 1 < ntiles) iteration(s_b, s_a, t + 1);
+  }
+  if (!active) return;
+  const float l = l_run + __shfl_xor(l_run, 32, 64);
+  const float inv = 1.0f / l;
+  bf16_t* orow = (bf16_t*)a.o + qoff;
+#pragma unroll
+  for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+    for (int vg = 0; vg < 4; ++vg) {
+      uint2 pk;
+      pk.x = pack_bf16x2(oacc[hb][vg * 4 + 0] * inv, oacc[hb][vg * 4 + 1] * inv);
+      pk.y = pack_bf16x2(oacc[hb][vg * 4 + 2] * inv, oacc[hb][vg * 4 + 3] * inv);
+      *(uint2*)(orow + hb * 32 + 8 * vg + 4 * half) = pk;
+    }
+}
+
+// 0: the plain LDS-tiled kernel (default), 1: the software-pipelined kernel (pt_set_tuning).  Measured on the
+// Large PT shape (16 heads x 128, 8 x 4096 tokens, 8 tracks): 5.5 ms per launch for the plain kernel, 7.3 - 7.9 ms for
+// the pipelined one, so the plain kernel stays the default.
+int pt_tune_attn_prefill = 0;
+
 template <int HD>
 static int launch_lds(const pt_attn_args& a, hipStream_t s) {
-  const int nqb = ((a.seq_info ? a.max_plen : a.S) + 127) / 128;
+  const int slen_max = a.seq_info ? a.max_plen : a.S;
+  if (pt_tune_attn_prefill == 1) {
+    // software-pipelined kernel: 8 wavefronts (256 queries) per workgroup, four K / V^T stages in LDS
+    constexpr int NW = 8, NSTG = 4;
+    const int nqb = (slen_max + NW * 32 - 1) / (NW * 32);
+    const int64_t total = (int64_t)a.n_tracks * a.B * a.H * nqb;
+    if (total > 0x7fffffff) return 0;
+    const size_t lds = (size_t)NSTG * 2 * 64 * HD * sizeof(bf16_t);
+    auto kern = attn_prefill_pipe_kernel<HD, NW, NSTG>;
+    PT_SET_MAX_LDS_ONCE(kern, lds);
+    hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(NW * 64), lds, s, a, nqb);
+    PT_HIP_CHECK(hipGetLastError());
+    return 1;
+  }
+  const int nqb = (slen_max + 127) / 128;
   const int64_t total = (int64_t)a.n_tracks * a.B * a.H * nqb;
   if (total > 0x7fffffff) return 0;
   const dim3 grid((unsigned)total);
   const size_t lds = (size_t)2 * (64 * HD + HD * 64) * sizeof(bf16_t);
-  auto kern = attn_prefill_lds_kernel<HD>;
-  PT_SET_MAX_LDS_ONCE(kern, lds);
-  hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, a, nqb);
+  {
+    auto kern = attn_prefill_lds_kernel<HD>;
+    PT_SET_MAX_LDS_ONCE(kern, lds);
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, a, nqb);
+  }
   PT_HIP_CHECK(hipGetLastError());
   return 1;
 }

@@ -344,6 +344,7 @@ extern "C" int pt_set_tuning(int32_t knob, int32_t value) {
   if (knob == PT_TUNE_GEMM_TILE_CONFIG) pt_tune_gemm_cfg = value;
   else if (knob == PT_TUNE_SKINNY_PLAN) pt_tune_skinny_plan = value;
   else if (knob == PT_TUNE_FOLD_RMSNORM) g_fold_rmsnorm = value != 0;
+  else if (knob == PT_TUNE_ATTN_PREFILL) pt_tune_attn_prefill = value != 0;
   else return pt_set_error(PT_ERR_INVALID_ARGUMENT, "unknown tuning knob %d", knob);
   return PT_OK;
 }

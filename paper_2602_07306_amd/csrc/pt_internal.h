@@ -249,6 +249,7 @@ int pt_launch_attn_decode(const pt_attn_args& a, hipStream_t s);        // 1: ma
 // weight-streaming GEMM (0 = by shape).
 extern int pt_tune_gemm_cfg;
 extern int pt_tune_skinny_plan;
+extern int pt_tune_attn_prefill;   // 0: plain LDS-tiled flash kernel, 1: software-pipelined flash kernel
 
 // ---------------------------------------------------------------------------------------------
 // Elementwise / bandwidth-bound kernels.

@@ -452,3 +452,21 @@ def test_long_context_decode_with_32_splits():
     for i in range(steps):
         r = O.pt_decode_step(cfg, W, st, tokens=feed[i])
         assert_close(got[1 + i], r["logits"], BF16_TOL, "decode step %d" % i)
+
+
+@pytest.mark.parametrize("over,B,S", [
+    (dict(max_batch=2, max_seq=640), 2, 576),                                              # head_dim 64, 9 key tiles
+    (dict(head_dim=128, n_heads=4, n_kv_heads=2, d_model=512, max_batch=1, max_seq=1100), 1, 1088),
+])
+def test_software_pipelined_prefill_attention_matches_the_oracle(over, B, S):
+    """The alternative flash prefill kernel behind PT_TUNE_ATTN_PREFILL (8 wavefronts per workgroup, four
+    direct-to-LDS stages, softmax slices between the MFMAs): slower than the default, kept selectable, and held to
+    the same parity bar."""
+    from paper_2602_07306_amd import binding as PB
+    cfg = small_bf16_config(n_layers=2, block_depth=2, **over)
+    PB.pt_set_tuning(PB.PT_TUNE_ATTN_PREFILL, 1)
+    try:
+        outs, counts = run_case(cfg, 77, B, S, 1, (PB.PT_PATH_AUTO,))
+        assert counts[PB.PT_PATH_AUTO][0]["attn_prefill"] == [0, cfg.n_layers, 0, 0]
+    finally:
+        PB.pt_set_tuning(PB.PT_TUNE_ATTN_PREFILL, 0)
