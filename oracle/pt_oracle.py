@@ -19,6 +19,12 @@ What it follows
   The layer used here is the common pre-norm decoder layer: RMSNorm, rotary
   position embedding with rotate-half pairing, causal softmax attention with
   grouped KV heads, a SwiGLU feed-forward network, no biases.
+* PT-MoE (Section 2.2, "Contrast with MoE / expert parallelism", and the Conclusion): MoE sparsity is applied
+  within tracks, i.e. the dense feed-forward network of a layer is replaced by a routed mixture of experts while
+  tracks and merges stay as they are.  The paper gives no formula; the routing used here is the sparsely-gated
+  form of the work it cites: router logits r = a W_r, the k largest logits select the experts (lowest index on
+  exact ties), the gates are the softmax over those k logits, every expert is a SwiGLU network, no shared expert,
+  no capacity limit.  A model is a PT-MoE model when cfg.n_experts > 0 (cfg.top_k experts per token).
 * All arithmetic is float64 on numpy arrays.  Matrix products use ``@`` as a
   library step; attention materialises the full score matrix and uses a
   two-pass softmax, so it is also the brute force that flash-style and split-K
@@ -26,7 +32,8 @@ What it follows
 
 Weights are passed in as a dict of arrays in the logical ``x @ W`` layouts
 ``wq [T,L,d,H*hd]``, ``wk, wv [T,L,d,Hkv*hd]``, ``wo [T,L,H*hd,d]``,
-``wg, wu [T,L,d,f]``, ``wd [T,L,f,d]``, ``g1, g2 [T,L,d]``, ``gf [d]``,
+``wg, wu [T,L,d,f]``, ``wd [T,L,f,d]`` (PT-MoE: ``wg, wu [T,L,E,d,f]``, ``wd [T,L,E,f,d]`` and the
+router ``wr [T,L,d,E]``), ``g1, g2 [T,L,d]``, ``gf [d]``,
 ``embed [V,d]``, ``head [d,V]``.  ``cfg`` is any object with the attributes
 n_tracks, n_layers, block_depth, d_model, n_heads, n_kv_heads, head_dim, d_ffn,
 vocab, merge_scale, rms_eps, rope_theta.
@@ -107,6 +114,39 @@ def silu(z: np.ndarray) -> np.ndarray:
     return z / (1.0 + np.exp(-z))
 
 
+def top_k_route(r: np.ndarray, k: int):
+    """Sparse gating over router logits r [S, E]: the indices of the k largest logits of every row in decreasing
+    order of logit (lowest index first on exact ties) and the softmax over just those k logits."""
+    S, E = r.shape
+    ids = np.empty((S, k), dtype=np.int64)
+    for s in range(S):
+        ids[s] = sorted(range(E), key=lambda e: (-r[s, e], e))[:k]
+    sel = np.take_along_axis(r, ids, axis=1)
+    return ids, softmax_rows(sel)
+
+
+def moe_ffn(cfg, W, i: int, l: int, a: np.ndarray, routes: Optional[list], forced: Optional[np.ndarray]) -> np.ndarray:
+    """Routed mixture of SwiGLU experts on the normalised rows a [S, d] of track i, layer l.  `forced` [S, k]
+    replaces the selection (the gates are still the softmax of the router's logits at the forced experts);
+    `routes`, when given, receives the selection that was used."""
+    r = a @ _f64(W["wr"][i, l])
+    ids, gates = top_k_route(r, cfg.top_k)
+    if forced is not None:
+        ids = np.asarray(forced, dtype=np.int64)
+        gates = softmax_rows(np.take_along_axis(r, ids, axis=1))
+    if routes is not None:
+        routes.append(ids.copy())
+    out = np.zeros_like(a)
+    for e in range(cfg.n_experts):
+        rows, slot = np.nonzero(ids == e)
+        if rows.size == 0:
+            continue
+        x = a[rows]
+        y = (silu(x @ _f64(W["wg"][i, l, e])) * (x @ _f64(W["wu"][i, l, e]))) @ _f64(W["wd"][i, l, e])
+        out[rows] += gates[rows, slot][:, None] * y
+    return out
+
+
 def track_merge(hs: List[np.ndarray], scale: float) -> np.ndarray:
     """The all-reduce of Algorithm 1 on one device: scale * (h_1 + ... + h_n), summed in
     track order."""
@@ -129,7 +169,7 @@ class PTState:
 
 
 def _layer(cfg, W: Dict[str, np.ndarray], i: int, l: int, h: np.ndarray, pos: np.ndarray,
-           state: PTState, b: int) -> np.ndarray:
+           state: PTState, b: int, routes: Optional[list] = None, forced: Optional[np.ndarray] = None) -> np.ndarray:
     """One transformer layer of track i on the rows ``h [S, d]`` of sequence b, which sit
     at absolute positions ``pos``.  Appends this layer's keys and values to the cache."""
     H, Hkv, hd = cfg.n_heads, cfg.n_kv_heads, cfg.head_dim
@@ -146,6 +186,8 @@ def _layer(cfg, W: Dict[str, np.ndarray], i: int, l: int, h: np.ndarray, pos: np
     o = causal_attention(q, state.k[i, l, b, :ctx], state.v[i, l, b, :ctx], pos)
     h = h + o.reshape(S, H * hd) @ _f64(W["wo"][i, l])
     a2 = rmsnorm(h, W["g2"][i, l], cfg.rms_eps)
+    if getattr(cfg, "n_experts", 0) > 0:
+        return h + moe_ffn(cfg, W, i, l, a2, routes, forced)
     gate = a2 @ _f64(W["wg"][i, l])
     up = a2 @ _f64(W["wu"][i, l])
     h = h + (silu(gate) * up) @ _f64(W["wd"][i, l])
@@ -153,14 +195,16 @@ def _layer(cfg, W: Dict[str, np.ndarray], i: int, l: int, h: np.ndarray, pos: np
 
 
 def _run_rows(cfg, W, state: PTState, x_tracks: List[np.ndarray], b: int, pos: np.ndarray,
-              taps: Optional[list], track_taps: Optional[list]):
-    """Algorithm 1 on the rows of one sequence.  x_tracks: per-track input [S, d]."""
+              taps: Optional[list], track_taps: Optional[list], routes: Optional[list] = None,
+              forced: Optional[np.ndarray] = None):
+    """Algorithm 1 on the rows of one sequence.  x_tracks: per-track input [S, d].  PT-MoE: `routes` collects the
+    expert selection of every (layer, track) in that order; `forced` [L, T, S, k] prescribes it."""
     T, L, D = cfg.n_tracks, cfg.n_layers, cfg.block_depth
     hs = [np.array(x, dtype=F64, copy=True) for x in x_tracks]
     h = None
     for l in range(L):
         for i in range(T):
-            hs[i] = _layer(cfg, W, i, l, hs[i], pos, state, b)
+            hs[i] = _layer(cfg, W, i, l, hs[i], pos, state, b, routes, None if forced is None else forced[l][i])
         if (l + 1) % D == 0:
             if track_taps is not None:
                 track_taps.append([t.copy() for t in hs])
@@ -178,7 +222,7 @@ def logits_from_hidden(cfg, W, h: np.ndarray) -> np.ndarray:
 
 def pt_prefill(cfg, W, state: PTState, tokens: Optional[np.ndarray] = None,
                hidden_in: Optional[np.ndarray] = None, collect_taps: bool = False,
-               lengths: Optional[np.ndarray] = None):
+               lengths: Optional[np.ndarray] = None, forced_routes: Optional[list] = None):
     """Prefill a batch from position 0.
 
     tokens [B, S] int, or hidden_in [B, S, d] (same input for every track) or
@@ -191,6 +235,9 @@ def pt_prefill(cfg, W, state: PTState, tokens: Optional[np.ndarray] = None,
     lengths[b] of its S rows only (the throughput mode of Section 3.3 batches inputs of mixed
     lengths); Algorithm 1 runs on exactly those rows, the rest of ``hidden`` / ``logits`` is
     NaN, taps hold lengths[b] rows, and decoding continues at position lengths[b].
+
+    PT-MoE models also return ``routes``: per sequence an int array [L, T, S, k] with the experts every token
+    was sent to; ``forced_routes`` (same shape per sequence) prescribes the selection instead.
     """
     T, d = cfg.n_tracks, cfg.d_model
     if tokens is not None:
@@ -200,7 +247,7 @@ def pt_prefill(cfg, W, state: PTState, tokens: Optional[np.ndarray] = None,
         hidden_in = np.asarray(hidden_in, dtype=F64)
         B, S = hidden_in.shape[-3], hidden_in.shape[-2]
     hidden = np.full((B, S, d), np.nan, dtype=F64)
-    all_taps, all_track_taps = [], []
+    all_taps, all_track_taps, all_routes = [], [], []
     for b in range(B):
         n = S if lengths is None else int(lengths[b])
         pos = np.arange(n)
@@ -213,10 +260,15 @@ def pt_prefill(cfg, W, state: PTState, tokens: Optional[np.ndarray] = None,
             xs = [hidden_in[i, b, :n] for i in range(T)]
         taps = [] if collect_taps else None
         ttaps = [] if collect_taps else None
-        hidden[b, :n] = _run_rows(cfg, W, state, xs, b, pos, taps, ttaps)
+        moe = getattr(cfg, "n_experts", 0) > 0
+        routes = [] if moe else None
+        hidden[b, :n] = _run_rows(cfg, W, state, xs, b, pos, taps, ttaps, routes,
+                                  None if forced_routes is None else forced_routes[b])
         state.length[b] = n
         all_taps.append(taps)
         all_track_taps.append(ttaps)
+        if moe:
+            all_routes.append(np.stack(routes).reshape(cfg.n_layers, T, n, cfg.top_k))
     state.merge_count += cfg.n_layers // cfg.block_depth
     out = {"hidden": hidden}
     if cfg.vocab > 0:
@@ -224,18 +276,23 @@ def pt_prefill(cfg, W, state: PTState, tokens: Optional[np.ndarray] = None,
     if collect_taps:
         out["taps"] = all_taps
         out["track_taps"] = all_track_taps
+    if all_routes:
+        out["routes"] = all_routes
     return out
 
 
 def pt_decode_step(cfg, W, state: PTState, tokens: Optional[np.ndarray] = None,
-                   hidden_in: Optional[np.ndarray] = None):
+                   hidden_in: Optional[np.ndarray] = None, forced_routes: Optional[np.ndarray] = None):
     """One KV-cached decode step: one new row per sequence at position length[b].
 
     tokens [B] int, or hidden_in [B, d] / [T, B, d].  Returns ``hidden`` [B, d], and with a
-    vocabulary ``logits`` [B, V] and ``argmax`` [B] (lowest id on exact ties)."""
+    vocabulary ``logits`` [B, V] and ``argmax`` [B] (lowest id on exact ties).  PT-MoE: ``routes`` [L, T, B, k];
+    ``forced_routes`` (same shape) prescribes the expert selection."""
     T, d = cfg.n_tracks, cfg.d_model
     B = len(tokens) if tokens is not None else np.asarray(hidden_in).shape[-2]
     hidden = np.empty((B, d), dtype=F64)
+    moe = getattr(cfg, "n_experts", 0) > 0
+    all_routes = []
     for b in range(B):
         pos = np.array([state.length[b]])
         if tokens is not None:
@@ -244,13 +301,19 @@ def pt_decode_step(cfg, W, state: PTState, tokens: Optional[np.ndarray] = None,
         else:
             hin = np.asarray(hidden_in, dtype=F64)
             xs = [hin[b][None, :]] * T if hin.ndim == 2 else [hin[i, b][None, :] for i in range(T)]
-        hidden[b] = _run_rows(cfg, W, state, xs, b, pos, None, None)[0]
+        routes = [] if moe else None
+        forced = None if forced_routes is None else np.asarray(forced_routes)[:, :, b:b + 1]
+        hidden[b] = _run_rows(cfg, W, state, xs, b, pos, None, None, routes, forced)[0]
         state.length[b] += 1
+        if moe:
+            all_routes.append(np.stack(routes).reshape(cfg.n_layers, T, 1, cfg.top_k))
     state.merge_count += cfg.n_layers // cfg.block_depth
     out = {"hidden": hidden}
     if cfg.vocab > 0:
         out["logits"] = logits_from_hidden(cfg, W, hidden)
         out["argmax"] = np.argmax(out["logits"], axis=-1).astype(np.int32)
+    if moe:
+        out["routes"] = np.concatenate(all_routes, axis=2)
     return out
 
 

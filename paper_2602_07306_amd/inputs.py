@@ -47,6 +47,7 @@ KIND_WO = 6
 KIND_WG = 7
 KIND_WU = 8
 KIND_WD = 9
+KIND_WR = 10
 KIND_TOKENS = 16
 KIND_HIDDEN = 17
 
@@ -74,6 +75,8 @@ class PTConfig:
     rms_eps: float = 1e-5
     rope_theta: float = 10000.0
     init_std: float = 0.02
+    n_experts: int = 0      # PT-MoE: experts per (track, layer); 0 = dense feed-forward network
+    top_k: int = 0          # PT-MoE: experts every token is routed to
 
     @property
     def n_merges(self) -> int:
@@ -85,6 +88,11 @@ def _mix64_int(z: int) -> int:
     z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & MASK64
     z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & MASK64
     return z ^ (z >> 31)
+
+
+def expert_layer(layer: int, expert: int) -> int:
+    """The `layer` field of the stream of expert `expert`'s tensors in layer `layer` (layer < 4096)."""
+    return layer | ((expert + 1) << 12)
 
 
 def stream_key(seed: int, kind: int, track: int = 0, layer: int = 0) -> int:
@@ -215,22 +223,32 @@ def make_weights(cfg: PTConfig, seed: int, tracks: Optional[range] = None) -> Di
     Logical layouts (``x @ W`` convention): ``wq [T,L,d,H*hd]``, ``wk, wv [T,L,d,Hkv*hd]``,
     ``wo [T,L,H*hd,d]``, ``wg, wu [T,L,d,f]``, ``wd [T,L,f,d]``, norm gains
     ``g1, g2 [T,L,d]`` and ``gf [d]`` (all ones), ``embed [V,d]``, ``head [d,V]``
-    (the last two only when ``cfg.vocab > 0``).
+    (the last two only when ``cfg.vocab > 0``).  A PT-MoE model (``cfg.n_experts = E > 0``) has
+    ``wg, wu [T,L,E,d,f]``, ``wd [T,L,E,f,d]`` and the router ``wr [T,L,d,E]``.
     """
     T, L, d = cfg.n_tracks, cfg.n_layers, cfg.d_model
     hq, hk, f = cfg.n_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim, cfg.d_ffn
+    E = cfg.n_experts
     shapes = {
         "wq": (KIND_WQ, (d, hq)), "wk": (KIND_WK, (d, hk)), "wv": (KIND_WV, (d, hk)),
         "wo": (KIND_WO, (hq, d)), "wg": (KIND_WG, (d, f)), "wu": (KIND_WU, (d, f)),
         "wd": (KIND_WD, (f, d)),
     }
+    if E > 0:
+        shapes["wr"] = (KIND_WR, (d, E))
     W: Dict[str, np.ndarray] = {}
     for name, (kind, shp) in shapes.items():
-        arr = np.empty((T, L) + shp, dtype=np.float32)
+        per_expert = E > 0 and name in ("wg", "wu", "wd")
+        arr = np.empty((T, L) + ((E,) if per_expert else ()) + shp, dtype=np.float32)
         for i in range(T):
             for l in range(L):
-                arr[i, l] = round_to_dtype(
-                    normal_tensor(stream_key(seed, kind, i, l), shp, cfg.init_std), cfg.dtype)
+                if per_expert:
+                    for e in range(E):
+                        arr[i, l, e] = round_to_dtype(normal_tensor(
+                            stream_key(seed, kind, i, expert_layer(l, e)), shp, cfg.init_std), cfg.dtype)
+                else:
+                    arr[i, l] = round_to_dtype(
+                        normal_tensor(stream_key(seed, kind, i, l), shp, cfg.init_std), cfg.dtype)
         W[name] = arr
     W["g1"] = np.ones((T, L, d), dtype=np.float32)
     W["g2"] = np.ones((T, L, d), dtype=np.float32)
