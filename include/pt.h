@@ -55,11 +55,15 @@ enum { PT_LOGITS_NONE = 0, PT_LOGITS_LAST = 1, PT_LOGITS_ALL = 2 };
  *   WQ [d, H*hd]  WK, WV [d, Hkv*hd]  WO [H*hd, d]  WG, WU [d, f]  WD [f, d]
  *   G1, G2 [d] (RMSNorm gains before attention / before the FFN)
  *   EMBED [vocab, d]  HEAD [d, vocab]  GF [d] (final RMSNorm gain)
- * The numbering of the random tensors equals the stream kinds of the seeded generator. */
+ *   ROUTER [d, n_experts] (PT-MoE models only)
+ * The numbering of the random tensors equals the stream kinds of the seeded generator.
+ * PT-MoE models hold WG, WU, WD once per expert: expert e of layer l is addressed with
+ * layer = PT_EXPERT_LAYER(l, e) (also the layer field of that tensor's random stream). */
 enum {
   PT_W_EMBED = 1, PT_W_HEAD = 2, PT_W_Q = 3, PT_W_K = 4, PT_W_V = 5, PT_W_O = 6,
-  PT_W_G = 7, PT_W_U = 8, PT_W_D = 9, PT_W_G1 = 10, PT_W_G2 = 11, PT_W_GF = 12
+  PT_W_G = 7, PT_W_U = 8, PT_W_D = 9, PT_W_G1 = 10, PT_W_G2 = 11, PT_W_GF = 12, PT_W_ROUTER = 13
 };
+#define PT_EXPERT_LAYER(layer, expert) ((layer) | (((expert) + 1) << 12))
 
 /* Shape of a PT model.  Algorithm 1's n, L, D are n_tracks, n_layers, block_depth; the
  * remaining fields give the per-track layer (Section 3.1: heads and KV heads are per track). */
@@ -81,6 +85,14 @@ typedef struct pt_config {
   float rms_eps;
   float rope_theta;
   float init_std;      /* standard deviation used by pt_init_weights */
+  /* PT-MoE (Section 2.2 and the Conclusion: MoE sparsity applied inside every track, tracks and merges
+   * unchanged).  n_experts = 0: dense SwiGLU feed-forward network.  n_experts = E in 1..64: the network of
+   * every (track, layer) is a mixture of E SwiGLU experts of width d_ffn each; a token's router logits are
+   * r = RMSNorm(h) W_router, its top_k experts are the largest logits (lowest index on exact ties), their
+   * gates the softmax over those top_k logits, and the layer adds sum_e gate_e * expert_e(RMSNorm(h)).
+   * No shared expert, no capacity limit (no token is dropped).  n_layers < 4096 for such models. */
+  int32_t n_experts;
+  int32_t top_k;       /* 1..min(8, n_experts) when n_experts > 0, else 0 */
 } pt_config;
 
 typedef struct pt_handle pt_handle;
@@ -184,6 +196,16 @@ int pt_argmax(const float* dev_logits, int32_t rows, int32_t vocab, int32_t* dev
  * [n_layers / block_depth, n_tracks, rows, d]. */
 int pt_set_taps(pt_handle* h, float* dev_taps, float* dev_track_taps);
 
+/* PT-MoE observation / forcing point for the expert selection (both may be NULL = off), int32
+ * [n_layers, n_tracks, rows, top_k] with rows as for pt_set_taps, experts in decreasing order of logit:
+ * dev_routes_out receives the selection every forward call makes; dev_routes_in prescribes it (the gates
+ * stay the softmax of the router's own logits at the prescribed experts; entries must be distinct and in
+ * [0, n_experts), else bit 1 of the status word checked by pt_sync_status is raised and expert 0.. are used).
+ * The selection is an integer decided by floating point, so a caller that compares two implementations
+ * forces one's selection on the other.  Not available with pt_prefill_ragged (BAD_STATE from that call).
+ * Errors: NULL_POINTER (handle), BAD_STATE (dense model). */
+int pt_set_moe_routes(pt_handle* h, int32_t* dev_routes_out, const int32_t* dev_routes_in);
+
 /* Kernel selection.  PT_PATH_AUTO (default) uses the MFMA / bandwidth-tuned kernels wherever the
  * shape allows and the shape-generic kernels elsewhere; PT_PATH_GENERIC forces the shape-generic
  * kernels everywhere (slow; used to cross-check the tuned kernels). */
@@ -214,7 +236,10 @@ int pt_seq_lens(const pt_handle* h, int32_t* host_out);
 enum {
   PT_K_EMBED = 0, PT_K_RMSNORM = 1, PT_K_GEMM_QKV = 2, PT_K_ATTN_PREFILL = 3, PT_K_ATTN_DECODE = 4,
   PT_K_GEMM_OUT = 5, PT_K_GEMM_GATEUP = 6, PT_K_GEMM_DOWN = 7, PT_K_MERGE = 8, PT_K_GEMM_HEAD = 9,
-  PT_K_OTHER = 10, PT_K_COUNT = 11
+  PT_K_OTHER = 10,
+  PT_K_GEMM_ROUTER = 11, /* PT-MoE: router logits */
+  PT_K_MOE = 12,         /* PT-MoE: expert selection, grouping of tokens by expert, weighted combine */
+  PT_K_COUNT = 13
 };
 /* class_mask: bit k set = bracket every launch of class k in later forward calls with a pair of
  * events (0 switches timing off).  Each bracketed launch costs two event records on the stream. */

@@ -135,7 +135,12 @@ def moe_ffn(cfg, W, i: int, l: int, a: np.ndarray, routes: Optional[list], force
         ids = np.asarray(forced, dtype=np.int64)
         gates = softmax_rows(np.take_along_axis(r, ids, axis=1))
     if routes is not None:
-        routes.append(ids.copy())
+        # also how decided the (unforced) selection was: the gap between the last logit taken and the first one
+        # left out, relative to the largest |logit| of the row (infinite when every expert is taken)
+        srt = -np.sort(-r, axis=1)
+        gap = (srt[:, cfg.top_k - 1] - srt[:, cfg.top_k] if cfg.top_k < cfg.n_experts
+               else np.full(r.shape[0], np.inf))
+        routes.append((ids.copy(), gap / np.maximum(np.max(np.abs(r), axis=1), 1e-300)))
     out = np.zeros_like(a)
     for e in range(cfg.n_experts):
         rows, slot = np.nonzero(ids == e)
@@ -237,7 +242,8 @@ def pt_prefill(cfg, W, state: PTState, tokens: Optional[np.ndarray] = None,
     NaN, taps hold lengths[b] rows, and decoding continues at position lengths[b].
 
     PT-MoE models also return ``routes``: per sequence an int array [L, T, S, k] with the experts every token
-    was sent to; ``forced_routes`` (same shape per sequence) prescribes the selection instead.
+    was sent to, and ``route_margins`` [L, T, S]: the relative gap between the last logit taken and the first left
+    out; ``forced_routes`` (same shape as routes, per sequence) prescribes the selection instead.
     """
     T, d = cfg.n_tracks, cfg.d_model
     if tokens is not None:
@@ -247,7 +253,7 @@ def pt_prefill(cfg, W, state: PTState, tokens: Optional[np.ndarray] = None,
         hidden_in = np.asarray(hidden_in, dtype=F64)
         B, S = hidden_in.shape[-3], hidden_in.shape[-2]
     hidden = np.full((B, S, d), np.nan, dtype=F64)
-    all_taps, all_track_taps, all_routes = [], [], []
+    all_taps, all_track_taps, all_routes, all_margins = [], [], [], []
     for b in range(B):
         n = S if lengths is None else int(lengths[b])
         pos = np.arange(n)
@@ -268,7 +274,8 @@ def pt_prefill(cfg, W, state: PTState, tokens: Optional[np.ndarray] = None,
         all_taps.append(taps)
         all_track_taps.append(ttaps)
         if moe:
-            all_routes.append(np.stack(routes).reshape(cfg.n_layers, T, n, cfg.top_k))
+            all_routes.append(np.stack([ids for ids, _ in routes]).reshape(cfg.n_layers, T, n, cfg.top_k))
+            all_margins.append(np.stack([m for _, m in routes]).reshape(cfg.n_layers, T, n))
     state.merge_count += cfg.n_layers // cfg.block_depth
     out = {"hidden": hidden}
     if cfg.vocab > 0:
@@ -278,6 +285,7 @@ def pt_prefill(cfg, W, state: PTState, tokens: Optional[np.ndarray] = None,
         out["track_taps"] = all_track_taps
     if all_routes:
         out["routes"] = all_routes
+        out["route_margins"] = all_margins
     return out
 
 
@@ -306,7 +314,7 @@ def pt_decode_step(cfg, W, state: PTState, tokens: Optional[np.ndarray] = None,
         hidden[b] = _run_rows(cfg, W, state, xs, b, pos, None, None, routes, forced)[0]
         state.length[b] += 1
         if moe:
-            all_routes.append(np.stack(routes).reshape(cfg.n_layers, T, 1, cfg.top_k))
+            all_routes.append(np.stack([ids for ids, _ in routes]).reshape(cfg.n_layers, T, 1, cfg.top_k))
     state.merge_count += cfg.n_layers // cfg.block_depth
     out = {"hidden": hidden}
     if cfg.vocab > 0:

@@ -20,10 +20,15 @@ PT_LOGITS_NONE, PT_LOGITS_LAST, PT_LOGITS_ALL = 0, 1, 2
 PT_FAMILY_GENERIC, PT_FAMILY_COUNT = 0, 4
 PT_TUNE_GEMM_TILE_CONFIG, PT_TUNE_SKINNY_PLAN, PT_TUNE_FOLD_RMSNORM, PT_TUNE_ATTN_PREFILL = 0, 1, 2, 3
 PT_PATH_AUTO, PT_PATH_GENERIC = 0, 1
-PT_W_EMBED, PT_W_HEAD, PT_W_Q, PT_W_K, PT_W_V, PT_W_O, PT_W_G, PT_W_U, PT_W_D, PT_W_G1, PT_W_G2, PT_W_GF = range(1, 13)
+PT_W_EMBED, PT_W_HEAD, PT_W_Q, PT_W_K, PT_W_V, PT_W_O, PT_W_G, PT_W_U, PT_W_D, PT_W_G1, PT_W_G2, PT_W_GF, PT_W_ROUTER = range(1, 14)
 WEIGHT_IDS = {"embed": PT_W_EMBED, "head": PT_W_HEAD, "wq": PT_W_Q, "wk": PT_W_K, "wv": PT_W_V,
               "wo": PT_W_O, "wg": PT_W_G, "wu": PT_W_U, "wd": PT_W_D, "g1": PT_W_G1, "g2": PT_W_G2,
-              "gf": PT_W_GF}
+              "gf": PT_W_GF, "wr": PT_W_ROUTER}
+
+
+def pt_expert_layer(layer: int, expert: int) -> int:
+    """PT_EXPERT_LAYER of include/pt.h: the `layer` argument that addresses expert `expert`'s WG / WU / WD."""
+    return layer | ((expert + 1) << 12)
 
 PT_OK = 0
 PT_ERR_INVALID_CONFIG, PT_ERR_NULL_POINTER, PT_ERR_ARENA_TOO_SMALL, PT_ERR_CAPACITY = -1, -2, -3, -4
@@ -34,17 +39,19 @@ EXPORTS = [
     "pt_prefill", "pt_decode_step", "pt_track_merge", "pt_set_taps", "pt_set_kernel_path", "pt_reset",
     "pt_merge_count", "pt_seq_len", "pt_last_error", "pt_profile_enable", "pt_profile_read",
     "pt_profile_reset", "pt_profile_paths", "pt_sync_status", "pt_set_tuning", "pt_argmax", "pt_decode_step_static", "pt_prefill_ragged", "pt_seq_lens",
+    "pt_set_moe_routes",
 ]
 
 KERNEL_CLASSES = ["embed", "rmsnorm", "gemm_qkv", "attn_prefill", "attn_decode", "gemm_out",
-                  "gemm_gateup", "gemm_down", "merge", "gemm_head", "other"]
+                  "gemm_gateup", "gemm_down", "merge", "gemm_head", "other", "gemm_router", "moe"]
 
 
 class pt_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_tracks", "n_layers", "block_depth", "d_model", "n_heads", "n_kv_heads", "head_dim",
         "d_ffn", "vocab", "max_batch", "max_seq", "dtype")] + [
-        (n, C.c_float) for n in ("merge_scale", "rms_eps", "rope_theta", "init_std")]
+        (n, C.c_float) for n in ("merge_scale", "rms_eps", "rope_theta", "init_std")] + [
+        (n, C.c_int32) for n in ("n_experts", "top_k")]
 
 
 class PTError(RuntimeError):
@@ -80,6 +87,7 @@ def lib() -> C.CDLL:
     L.pt_seq_lens.argtypes = [vp, C.POINTER(i32)]
     L.pt_track_merge.argtypes = [C.POINTER(vp), i32, i64, i32, i32, C.c_float, vp, vp]
     L.pt_set_taps.argtypes = [vp, vp, vp]
+    L.pt_set_moe_routes.argtypes = [vp, vp, vp]
     L.pt_set_kernel_path.argtypes = [vp, i32]
     L.pt_reset.argtypes = [vp]
     L.pt_merge_count.argtypes = [vp]
@@ -110,7 +118,8 @@ def _check(rc: int) -> None:
 def to_c_config(cfg: PTConfig) -> pt_config:
     return pt_config(cfg.n_tracks, cfg.n_layers, cfg.block_depth, cfg.d_model, cfg.n_heads,
                      cfg.n_kv_heads, cfg.head_dim, cfg.d_ffn, cfg.vocab, cfg.max_batch, cfg.max_seq,
-                     cfg.dtype, cfg.merge_scale, cfg.rms_eps, cfg.rope_theta, cfg.init_std)
+                     cfg.dtype, cfg.merge_scale, cfg.rms_eps, cfg.rope_theta, cfg.init_std, cfg.n_experts,
+                     cfg.top_k)
 
 
 def pt_last_error() -> str:
@@ -210,10 +219,15 @@ class PTModel:
     def load_weights(self, W):
         """Uploads a dict of logical weights (layouts of inputs.make_weights)."""
         cfg = self.cfg
-        for name in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2"):
+        E = cfg.n_experts
+        for name in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2") + (("wr",) if E > 0 else ()):
             for i in range(cfg.n_tracks):
                 for l in range(cfg.n_layers):
-                    self.pt_set_weight(name, i, l, W[name][i, l])
+                    if E > 0 and name in ("wg", "wu", "wd"):
+                        for e in range(E):
+                            self.pt_set_weight(name, i, pt_expert_layer(l, e), W[name][i, l, e])
+                    else:
+                        self.pt_set_weight(name, i, l, W[name][i, l])
         self.pt_set_weight("gf", 0, 0, W["gf"])
         if cfg.vocab > 0:
             self.pt_set_weight("embed", 0, 0, W["embed"])
@@ -232,6 +246,25 @@ class PTModel:
     def pt_clear_taps(self):
         _check(lib().pt_set_taps(self.h, None, None))
         self._taps = None
+
+    def pt_set_moe_routes(self, rows: int, forced=None, observe: bool = True):
+        """PT-MoE: observe and / or prescribe the expert selection of later forward calls over `rows` rows.
+        forced: int array [n_layers, n_tracks, rows, top_k].  Returns the int32 device tensor that receives the
+        selection (or None)."""
+        cfg, torch = self.cfg, self.torch
+        shape = (cfg.n_layers, cfg.n_tracks, rows, cfg.top_k)
+        out = torch.full(shape, -1, dtype=torch.int32, device=self.device) if observe else None
+        fin = None
+        if forced is not None:
+            fin = torch.as_tensor(np.ascontiguousarray(forced, dtype=np.int32)).to(self.device)
+            assert tuple(fin.shape) == shape
+        _check(lib().pt_set_moe_routes(self.h, _ptr(out), _ptr(fin)))
+        self._routes = (out, fin)
+        return out
+
+    def pt_clear_moe_routes(self):
+        _check(lib().pt_set_moe_routes(self.h, None, None))
+        self._routes = None
 
     def pt_set_kernel_path(self, path: int):
         _check(lib().pt_set_kernel_path(self.h, path))

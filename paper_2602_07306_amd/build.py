@@ -37,6 +37,7 @@ SOURCES = [
     "kernels_attn_generic.hip",
     "kernels_attn_prefill_mfma.hip",
     "kernels_attn_decode.hip",
+    "kernels_moe.hip",
 ]
 
 COMMON = [

@@ -471,6 +471,12 @@ gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
   const int wm = wave / WN, wn = wave % WN;
   const tile_coord tc = map_tile(blockIdx.x, gridDim.x, tiles_m, tiles_n);
   const int m0 = tc.tm * BM, n0 = tc.tn * BN, b = tc.b;
+  // grouped GEMM: the weight matrix of this tile's rows; tiles that start in a block without rows have nothing to do
+  int group = 0;
+  if (g.blk_group) {
+    group = g.blk_group[b * g.grp_bstride + (m0 >> 6)];
+    if (group < 0) return;
+  }
 
   // folded RMSNorm, consumer side: one factor per tile row (1/rms of the row, from pt_launch_row_inv_rms).  The
   // load is issued here and parked in LDS only after the K loop, so nothing waits for it.
@@ -493,16 +499,18 @@ gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
   uint32_t a_voff[A_CH], w_voff[B_CH];   // byte offsets from the tile's first row
 #pragma unroll
   for (int i = 0; i < A_CH; ++i) {
-    const int gr = min(m0 + ld_row + i * (NT / CPR), g.M - 1) - m0;
-    a_voff[i] = (uint32_t)((gr * g.lda + ld_ch * 8) * 2);
+    const int m = min(m0 + ld_row + i * (NT / CPR), g.M - 1);
+    // gathered rows (grouped GEMM) are addressed from the track's first row: the host checks rows * lda * 2 < 2^32
+    const uint32_t gr = g.a_rows ? (uint32_t)g.a_rows[b * g.a_rows_bstride + m] : (uint32_t)(m - m0);
+    a_voff[i] = (gr * (uint32_t)g.lda + ld_ch * 8) * 2;
   }
 #pragma unroll
   for (int i = 0; i < B_CH; ++i) {
     const int gr = min(n0 + ld_row + i * (NT / CPR), g.N - 1) - n0;
     w_voff[i] = (uint32_t)((gr * g.ldb + ld_ch * 8) * 2);
   }
-  const char* a_base = (const char*)((const bf16_t*)g.A + b * g.a_bstride + (int64_t)m0 * g.lda);   // wave-uniform
-  const char* w_base = (const char*)((const bf16_t*)g.W + b * g.w_bstride + (int64_t)n0 * g.ldb);
+  const char* a_base = (const char*)((const bf16_t*)g.A + b * g.a_bstride + (g.a_rows ? 0 : (int64_t)m0 * g.lda));   // wave-uniform
+  const char* w_base = (const char*)((const bf16_t*)g.W + b * g.w_bstride + group * g.w_gstride + (int64_t)n0 * g.ldb);
   auto load_a = [&](int set, int i, int kstep) { a_reg[set][i] = *(const u32x4_t*)(a_base + (size_t)kstep * (BK * 2) + a_voff[i]); };
   auto load_w = [&](int set, int i, int kstep) { w_reg[set][i] = *(const u32x4_t*)(w_base + (size_t)kstep * (BK * 2) + w_voff[i]); };
 
@@ -652,6 +660,11 @@ gemm_dl_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
   const tile_coord tc = map_tile(blockIdx.x, gridDim.x, tiles_m, tiles_n);
   const int m0 = tc.tm * BM, n0 = tc.tn * BN, b = tc.b;
   const int KT = g.K / BK;   // multiple of 4
+  int group = 0;             // grouped GEMM, as in gemm_mfma_kernel
+  if (g.blk_group) {
+    group = g.blk_group[b * g.grp_bstride + (m0 >> 6)];
+    if (group < 0) return;
+  }
 
   // folded RMSNorm, consumer side: one factor per tile row (1/rms of the row, from pt_launch_row_inv_rms).  The
   // load is issued here and parked in LDS only after the K loop, so nothing waits for it.
@@ -667,8 +680,9 @@ gemm_dl_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
 #pragma unroll
   for (int i = 0; i < LA; ++i) {
     const int row = (wave * LA + i) * 16 + rr;
-    const int gr = min(m0 + row, g.M - 1) - m0;
-    a_voff[i] = (uint32_t)((gr * g.lda + (pc ^ SWZ(row)) * 8) * 2);
+    const int m = min(m0 + row, g.M - 1);
+    const uint32_t gr = g.a_rows ? (uint32_t)g.a_rows[b * g.a_rows_bstride + m] : (uint32_t)(m - m0);
+    a_voff[i] = (gr * (uint32_t)g.lda + (pc ^ SWZ(row)) * 8) * 2;
   }
 #pragma unroll
   for (int i = 0; i < LB; ++i) {
@@ -676,8 +690,8 @@ gemm_dl_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
     const int gr = min(n0 + row, g.N - 1) - n0;
     w_voff[i] = (uint32_t)((gr * g.ldb + (pc ^ SWZ(row)) * 8) * 2);
   }
-  const char* a_base = (const char*)((const bf16_t*)g.A + b * g.a_bstride + (int64_t)m0 * g.lda);
-  const char* w_base = (const char*)((const bf16_t*)g.W + b * g.w_bstride + (int64_t)n0 * g.ldb);
+  const char* a_base = (const char*)((const bf16_t*)g.A + b * g.a_bstride + (g.a_rows ? 0 : (int64_t)m0 * g.lda));
+  const char* w_base = (const char*)((const bf16_t*)g.W + b * g.w_bstride + group * g.w_gstride + (int64_t)n0 * g.ldb);
   typedef const __attribute__((address_space(1))) void* gptr_t;
   typedef __attribute__((address_space(3))) void* lptr_t;
   auto issue_load = [&](int i, int kstep, int stage) {   // i < LA: A group, else W group

@@ -36,6 +36,13 @@ __global__ void __launch_bounds__(256) gemm_generic_kernel(pt_gemm_args g) {
   const int npairs = g.N >> 1;
   const T* A = (const T*)g.A + b * g.a_bstride;
   const T* W = (const T*)g.W + b * g.w_bstride;
+  if (g.blk_group) {   // grouped GEMM: weight matrix by 64-row block; blocks without rows are skipped
+    const int group = g.blk_group[b * g.grp_bstride + (m0 >> 6)];
+    if (group < 0) return;
+    W += group * g.w_gstride;
+  }
+  // row of A behind tile row ty (a gather when a_rows is given)
+  const int64_t arow = m0 + ty < g.M ? (g.a_rows ? g.a_rows[b * g.a_rows_bstride + m0 + ty] : m0 + ty) : 0;
 
   // the W rows this block needs, one pair per tile row
   int ln0 = 0, ln1 = 0;
@@ -48,7 +55,7 @@ __global__ void __launch_bounds__(256) gemm_generic_kernel(pt_gemm_args g) {
     for (int e = tx; e < GG_BK; e += 16) {
       const int k = k0 + e;
       const bool kin = k < g.K;
-      As[ty][e] = (kin && m0 + ty < g.M) ? elem<T>::ld(A + (int64_t)(m0 + ty) * g.lda + k) : 0.f;
+      As[ty][e] = (kin && m0 + ty < g.M) ? elem<T>::ld(A + arow * g.lda + k) : 0.f;
       const bool pin = kin && (p0 + ty) < npairs;
       W0s[ty][e] = pin ? elem<T>::ld(W + (int64_t)ln0 * g.ldb + k) : 0.f;
       W1s[ty][e] = pin ? elem<T>::ld(W + (int64_t)ln1 * g.ldb + k) : 0.f;

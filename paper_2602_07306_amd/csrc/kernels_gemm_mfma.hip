@@ -49,6 +49,8 @@ static int choose_cfg(const pt_gemm_args& g) {
   if (g.K < 2 * GM_BK || g.K % (2 * GM_BK)) return -1;
   if ((g.lda & 7) || (g.ldb & 7) || (g.a_bstride & 7) || (g.w_bstride & 7)) return -1;
   if (((uintptr_t)g.A | (uintptr_t)g.W) & 15) return -1;
+  if (g.blk_group && ((g.w_gstride & 7) || (g.M & 255))) return -1;   // expert segments are whole 256-row tiles
+  if (g.a_rows && (g.a_bstride ? g.a_bstride : (int64_t)g.M * g.lda) * 2 >= ((int64_t)1 << 32)) return -1;   // 32-bit gather offsets
   if ((g.epi == EPI_STORE_F32 || g.epi == EPI_RESIDUAL) &&
       ((g.ldo & 3) || (g.N & 3) || (g.out_bstride & 3) || (g.res_bstride & 3) || (((uintptr_t)g.out | (uintptr_t)g.res) & 15))) return -1;
   if (g.epi == EPI_SWIGLU && ((g.olp_bstride & 7) || ((uintptr_t)g.olp & 15))) return -1;

@@ -130,6 +130,17 @@ __global__ void __launch_bounds__(256) init_normal_kernel(wmap m, uint64_t key, 
   store_w(m, phys_index(m, r, 2 * cp + 1), (float)(n1 * std_dev));
 }
 
+// one thread per logical element (any column count): element e takes normal e & 1 of counter e >> 1
+__global__ void __launch_bounds__(256) init_normal_elem_kernel(wmap m, uint64_t key, double std_dev) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= m.rows * m.cols) return;
+  const int64_t r = idx % m.rows, c = idx / m.rows;
+  const int64_t e = r * m.cols + c;
+  double n0, n1;
+  normal_pair(key, (uint64_t)(e >> 1), &n0, &n1);
+  store_w(m, phys_index(m, r, c), (float)(((e & 1) ? n1 : n0) * std_dev));
+}
+
 __global__ void __launch_bounds__(256) weight_copy_kernel(wmap m, float* logical, int to_storage) {
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= m.rows * m.cols) return;
@@ -145,7 +156,15 @@ static int make_map(const pt_handle* h, int32_t tensor, int32_t track, int32_t l
   const pt_config& c = h->cfg;
   const pt_layout& l = h->lay;
   const int64_t es = l.elem_size, d = c.d_model, f = c.d_ffn;
+  // PT-MoE: the feed-forward tensors exist once per expert, addressed with layer = PT_EXPERT_LAYER(layer, expert)
+  int64_t expert = 0;
+  if (c.n_experts > 0 && (tensor == PT_W_G || tensor == PT_W_U || tensor == PT_W_D)) {
+    expert = (layer >> 12) - 1;
+    layer &= 0xfff;
+    if (expert < 0 || expert >= c.n_experts) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "expert %d out of range", (int)expert);
+  }
   char* lw = h->w + l.off_layers + (size_t)(((int64_t)track * c.n_layers + layer) * l.layer_w_elems * es);
+  char* le = lw + (l.off_exp_elems + expert * l.expert_elems) * es;   // this expert's gate/up block, then its down block
   memset(m, 0, sizeof(*m));
   m->dtype = c.dtype;
   m->transposed = 1;
@@ -154,9 +173,10 @@ static int make_map(const pt_handle* h, int32_t tensor, int32_t track, int32_t l
     case PT_W_K: m->base = lw; m->rows = d; m->cols = l.hk; m->ld = d; m->row_off = l.hq; break;
     case PT_W_V: m->base = lw; m->rows = d; m->cols = l.hk; m->ld = d; m->row_off = l.hq + l.hk; break;
     case PT_W_O: m->base = lw + l.wqkv_elems * es; m->rows = l.hq; m->cols = d; m->ld = l.hq; break;
-    case PT_W_G: m->base = lw + (l.wqkv_elems + l.wo_elems) * es; m->rows = d; m->cols = f; m->ld = d; m->interleave = 1; break;
-    case PT_W_U: m->base = lw + (l.wqkv_elems + l.wo_elems) * es; m->rows = d; m->cols = f; m->ld = d; m->interleave = 2; break;
-    case PT_W_D: m->base = lw + (l.wqkv_elems + l.wo_elems + l.wgu_elems) * es; m->rows = f; m->cols = d; m->ld = f; break;
+    case PT_W_G: m->base = le; m->rows = d; m->cols = f; m->ld = d; m->interleave = 1; break;
+    case PT_W_U: m->base = le; m->rows = d; m->cols = f; m->ld = d; m->interleave = 2; break;
+    case PT_W_D: m->base = le + l.wgu_elems * es; m->rows = f; m->cols = d; m->ld = f; break;
+    case PT_W_ROUTER: m->base = lw + l.off_wr_elems * es; m->rows = d; m->cols = c.n_experts; m->ld = d; break;
     case PT_W_EMBED: m->base = h->w + l.off_embed; m->rows = c.vocab; m->cols = d; m->ld = d; m->transposed = 0; break;
     case PT_W_HEAD: m->base = h->w + l.off_headT; m->rows = d; m->cols = c.vocab; m->ld = d; break;
     case PT_W_G1:
@@ -186,14 +206,26 @@ int pt_launch_weight_init(pt_handle* h, uint64_t seed) {
   static const int32_t per_layer[7] = {PT_W_Q, PT_W_K, PT_W_V, PT_W_O, PT_W_G, PT_W_U, PT_W_D};
   wmap m;
   for (int t = 0; t < c.n_tracks; ++t)
-    for (int layer = 0; layer < c.n_layers; ++layer)
+    for (int layer = 0; layer < c.n_layers; ++layer) {
       for (int k = 0; k < 7; ++k) {
-        int rc = make_map(h, per_layer[k], t, layer, &m);
-        if (rc) return rc;
-        const int64_t n = m.rows * (m.cols / 2);
-        hipLaunchKernelGGL(init_normal_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, h->stream, m,
-                           stream_key(seed, (uint32_t)per_layer[k], (uint32_t)t, (uint32_t)layer), sd);
+        const bool per_expert = c.n_experts > 0 && k >= 4;
+        for (int e = 0; e < (per_expert ? c.n_experts : 1); ++e) {
+          const int32_t lay = per_expert ? PT_EXPERT_LAYER(layer, e) : layer;   // also the stream's layer field
+          int rc = make_map(h, per_layer[k], t, lay, &m);
+          if (rc) return rc;
+          const int64_t n = m.rows * (m.cols / 2);
+          hipLaunchKernelGGL(init_normal_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, h->stream, m,
+                             stream_key(seed, (uint32_t)per_layer[k], (uint32_t)t, (uint32_t)lay), sd);
+        }
       }
+      if (c.n_experts > 0) {
+        int rc = make_map(h, PT_W_ROUTER, t, layer, &m);
+        if (rc) return rc;
+        const int64_t n = m.rows * m.cols;
+        hipLaunchKernelGGL(init_normal_elem_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, h->stream, m,
+                           stream_key(seed, PT_W_ROUTER, (uint32_t)t, (uint32_t)layer), sd);
+      }
+    }
   if (c.vocab > 0) {
     for (int32_t tensor : {PT_W_EMBED, PT_W_HEAD}) {
       int rc = make_map(h, tensor, 0, 0, &m);

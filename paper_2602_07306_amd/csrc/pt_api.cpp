@@ -45,6 +45,11 @@ int pt_validate_config(const pt_config* c) {
   if ((int64_t)c->max_batch * c->max_seq > (int64_t)1 << 30)
     return pt_set_error(PT_ERR_INVALID_CONFIG, "max_batch * max_seq too large");
   if (c->dtype != PT_F32 && c->dtype != PT_BF16) return pt_set_error(PT_ERR_INVALID_CONFIG, "dtype must be PT_F32 or PT_BF16");
+  if (c->n_experts < 0 || c->n_experts > 64) return pt_set_error(PT_ERR_INVALID_CONFIG, "n_experts = %d, need 0 (dense) or 1..64", c->n_experts);
+  if (c->n_experts == 0 && c->top_k != 0) return pt_set_error(PT_ERR_INVALID_CONFIG, "top_k must be 0 for a dense model");
+  if (c->n_experts > 0 && (c->top_k < 1 || c->top_k > 8 || c->top_k > c->n_experts))
+    return pt_set_error(PT_ERR_INVALID_CONFIG, "top_k = %d, need 1..min(8, n_experts)", c->top_k);
+  if (c->n_experts > 0 && c->n_layers >= 4096) return pt_set_error(PT_ERR_INVALID_CONFIG, "a PT-MoE model needs n_layers < 4096");
   if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f) || !(c->init_std >= 0.f) || !(c->merge_scale == c->merge_scale))
     return pt_set_error(PT_ERR_INVALID_CONFIG, "rms_eps, rope_theta, init_std or merge_scale out of range");
   return PT_OK;
@@ -63,7 +68,12 @@ int pt_compute_layout(const pt_config* c, pt_layout* l) {
   l->wo_elems = up(d * l->hq);
   l->wgu_elems = up(2 * f * d);
   l->wd_elems = up(d * f);
-  l->layer_w_elems = l->wqkv_elems + l->wo_elems + l->wgu_elems + l->wd_elems;
+  l->e_pad = (c->n_experts + 3) / 4 * 4;
+  l->wr_elems = up(l->e_pad * d);
+  l->expert_elems = l->wgu_elems + l->wd_elems;
+  l->off_wr_elems = l->wqkv_elems + l->wo_elems;
+  l->off_exp_elems = l->off_wr_elems + l->wr_elems;
+  l->layer_w_elems = l->off_exp_elems + (c->n_experts > 0 ? c->n_experts : 1) * l->expert_elems;
   size_t off = 0;
   l->off_layers = off; off = align_up(off + (size_t)(T * L * l->layer_w_elems * es), 256);
   l->off_gains = off;  off = align_up(off + (size_t)(T * L * 2 * d * 4), 256);
@@ -100,12 +110,25 @@ void pt_layout_workspace(const pt_config* c, const pt_layout* l, int64_t rows, i
   w->off_a = off;    off = align_up(off + (size_t)(T * rows * d * es), 256);
   w->off_q = off;    off = align_up(off + (size_t)(T * rows * l->hq * es), 256);
   w->off_o = off;    off = align_up(off + (size_t)(T * rows * l->hq * es), 256);
-  w->off_m = off;    off = align_up(off + (size_t)(T * rows * f * es), 256);
+  const int64_t E = c->n_experts, k = c->top_k;
+  w->slots = E > 0 ? (rows * k + E * 255 + 255) / 256 * 256 : 0;
+  w->off_m = off;    off = align_up(off + (size_t)(T * (E > 0 ? w->slots : rows) * f * es), 256);
   w->off_part = off; off = align_up(off + (size_t)(T * batch * c->n_heads * max_splits * (hd + 2) * 4), 256);
   w->off_ss = off;   off = align_up(off + (size_t)(T * rows * ((d + 63) / 64) * 4), 256);
   w->off_rinv = off; off = align_up(off + (size_t)(T * rows * 4), 256);
   w->off_rowmap = off; off = align_up(off + (size_t)(rows * 8), 256);
   w->off_rowidx = off; off = align_up(off + (size_t)((batch + rows) * 4), 256);
+  w->off_rlogit = w->off_route = w->off_gate = w->off_slot = w->off_perm = w->off_blk = w->off_cnt = w->off_y = 0;
+  if (E > 0) {
+    w->off_rlogit = off; off = align_up(off + (size_t)(T * rows * l->e_pad * 4), 256);
+    w->off_route = off;  off = align_up(off + (size_t)(T * rows * k * 4), 256);
+    w->off_gate = off;   off = align_up(off + (size_t)(T * rows * k * 4), 256);
+    w->off_slot = off;   off = align_up(off + (size_t)(T * rows * k * 4), 256);
+    w->off_perm = off;   off = align_up(off + (size_t)(T * w->slots * 4), 256);
+    w->off_blk = off;    off = align_up(off + (size_t)(T * (w->slots / 64) * 4), 256);
+    w->off_cnt = off;    off = align_up(off + (size_t)(T * ((rows + 255) / 256 + 2) * 64 * 4), 256);
+    w->off_y = off;      off = align_up(off + (size_t)(T * w->slots * d * 4), 256);
+  }
   w->off_skp = off;  off = align_up(off + (size_t)skp_floats * 4, 256);
   w->bytes = off;
   w->skp_floats = skp_floats;
@@ -160,6 +183,8 @@ extern "C" int pt_create(const pt_config* cfg, void* dev_weights, size_t weight_
   h->rope_ready = false;
   h->taps = nullptr;
   h->track_taps = nullptr;
+  h->routes_out = nullptr;
+  h->routes_in = nullptr;
   h->path = PT_PATH_AUTO;
   *out = h;
   return PT_OK;
@@ -192,6 +217,14 @@ extern "C" int pt_set_taps(pt_handle* h, float* dev_taps, float* dev_track_taps)
   return PT_OK;
 }
 
+extern "C" int pt_set_moe_routes(pt_handle* h, int32_t* dev_routes_out, const int32_t* dev_routes_in) {
+  if (!h) return pt_set_error(PT_ERR_NULL_POINTER, "handle is NULL");
+  if (h->cfg.n_experts == 0) return pt_set_error(PT_ERR_BAD_STATE, "the model has no experts");
+  h->routes_out = dev_routes_out;
+  h->routes_in = dev_routes_in;
+  return PT_OK;
+}
+
 extern "C" int pt_set_kernel_path(pt_handle* h, int32_t path) {
   if (!h) return pt_set_error(PT_ERR_NULL_POINTER, "handle is NULL");
   if (path != PT_PATH_AUTO && path != PT_PATH_GENERIC)
@@ -209,8 +242,16 @@ extern "C" int pt_init_weights(pt_handle* h, uint64_t seed) {
 }
 
 static int check_tensor(const pt_handle* h, int32_t tensor, int32_t track, int32_t layer) {
-  if (tensor < PT_W_EMBED || tensor > PT_W_GF) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "unknown tensor id %d", tensor);
+  if (tensor < PT_W_EMBED || tensor > PT_W_ROUTER) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "unknown tensor id %d", tensor);
   const bool global = tensor == PT_W_EMBED || tensor == PT_W_HEAD || tensor == PT_W_GF;
+  if (tensor == PT_W_ROUTER && h->cfg.n_experts == 0) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "the model has no router");
+  if (h->cfg.n_experts > 0 && (tensor == PT_W_G || tensor == PT_W_U || tensor == PT_W_D)) {
+    // per-expert tensors: layer = PT_EXPERT_LAYER(layer, expert)
+    const int32_t expert = (layer >> 12) - 1;
+    if (expert < 0 || expert >= h->cfg.n_experts)
+      return pt_set_error(PT_ERR_INVALID_ARGUMENT, "expert tensors are addressed with layer = PT_EXPERT_LAYER(layer, expert); expert %d out of range", expert);
+    layer &= 0xfff;
+  }
   if ((tensor == PT_W_EMBED || tensor == PT_W_HEAD) && h->cfg.vocab == 0)
     return pt_set_error(PT_ERR_INVALID_ARGUMENT, "model has no vocabulary");
   if (!global && (track < 0 || track >= h->cfg.n_tracks || layer < 0 || layer >= h->cfg.n_layers))
@@ -363,6 +404,7 @@ extern "C" int pt_sync_status(pt_handle* h) {
     int rc = pt_launch_fill_f32((float*)dev_flag, 1, 0.0f, h->stream);   // all-zero bits
     if (rc) return rc;
     if (flag & 1) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "a token id outside [0, vocab) was given to a forward call");
+    if (flag & 2) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "a prescribed expert selection held an expert out of range or twice");
   }
   return PT_OK;
 }
@@ -381,7 +423,7 @@ static int run_gemm(pt_handle* h, const pt_gemm_args& g_in, int cls) {
   g.sk_part = (float*)(h->active->base + h->active->off_skp);
   g.sk_part_floats = h->active->skp_floats;
   if (h->path == PT_PATH_AUTO) {
-    int r = g.M <= 64 ? pt_launch_gemm_skinny(g, false, h->stream) : 0;
+    int r = g.M <= 64 && !g.blk_group && !g.a_rows ? pt_launch_gemm_skinny(g, false, h->stream) : 0;
     if (r < 0) return r;
     if (r > 0) { count_family(h, cls, r); return PT_OK; }
     if (g.norm_src) return pt_set_error(PT_ERR_HIP, "a GEMM that was to form its own normalised operand was not taken by that kernel");
@@ -551,8 +593,26 @@ static int forward(pt_handle* h, const pt_workspace& w, const int32_t* dev_token
     fuse_qkv_norm = pt_gemm_fuses_norm(p);
     qkv_proto = p;
     p.N = (int32_t)(2 * f); p.epi = EPI_SWIGLU; p.olp = mbuf; p.olp_bstride = rows * f;
-    fuse_ffn_norm = pt_gemm_fuses_norm(p);
+    fuse_ffn_norm = pt_gemm_fuses_norm(p) && c.n_experts == 0;
     gu_proto = p;
+  }
+  // PT-MoE: the feed-forward half of every layer is a routed mixture of experts (moe_ffn below); the RMSNorm in
+  // front of it is always materialised, because the router and the gathered expert GEMMs both read it
+  const bool moe = c.n_experts > 0;
+  pt_moe_args ma;
+  memset(&ma, 0, sizeof(ma));
+  if (moe) {
+    ma.T = (int32_t)T; ma.E = c.n_experts; ma.e_pad = (int32_t)l.e_pad; ma.k = c.top_k;
+    ma.rows = rows; ma.slots = w.slots;
+    ma.logits = (const float*)(w.base + w.off_rlogit);
+    ma.route = (int32_t*)(w.base + w.off_route);
+    ma.gate = (float*)(w.base + w.off_gate);
+    ma.slot = (int32_t*)(w.base + w.off_slot);
+    ma.perm = (int32_t*)(w.base + w.off_perm);
+    ma.blk = (int32_t*)(w.base + w.off_blk);
+    ma.cnt = (int32_t*)(w.base + w.off_cnt);
+    ma.obs_bstride = rows * c.top_k;
+    ma.flag = (int32_t*)(h->w + l.off_flag);
   }
   for (int64_t layer = 0; layer < L; ++layer) {
     const bool first = (layer % c.block_depth) == 0;
@@ -621,9 +681,62 @@ static int forward(pt_handle* h, const pt_workspace& w, const int32_t* dev_token
     // ... and the RMSNorm that opens the feed-forward half
     int gu_rs_parts = 0;
     rc = run_residual_gemm_norm(h, g, PT_K_GEMM_OUT, fuse_ffn_norm ? nullptr : gains + (layer * 2 + 1) * d, L * 2 * d, abuf,
-                                &gu_proto, &gu_rs_parts);
+                                moe ? nullptr : &gu_proto, &gu_rs_parts);
     if (rc) return rc;
 
+    // inside a block the next layer's first RMSNorm follows directly; at a block end the merge comes first
+    const bool block_end = (layer + 1) % c.block_depth == 0;
+    const bool norm_next = !block_end && !fuse_qkv_norm;
+
+    if (moe) {
+      // feed-forward half, PT-MoE: router logits -> expert selection and grouping -> gate/up and down GEMMs over the
+      // slots of every expert -> gate-weighted sum into the residual stream (and the next RMSNorm)
+      const char* wexp = wl + (size_t)(l.off_exp_elems * es);
+      memset(&g, 0, sizeof(g));
+      g.A = abuf; g.a_bstride = rows * d; g.lda = (int32_t)d;
+      g.W = wl + (size_t)(l.off_wr_elems * es); g.w_bstride = w_bstride; g.ldb = (int32_t)d;
+      g.M = (int32_t)rows; g.N = (int32_t)l.e_pad; g.K = (int32_t)d; g.batch = (int32_t)T;
+      g.dtype = c.dtype; g.epi = EPI_STORE_F32;
+      g.out = (float*)(w.base + w.off_rlogit); g.out_bstride = rows * l.e_pad; g.ldo = (int32_t)l.e_pad;
+      rc = run_gemm(h, g, PT_K_GEMM_ROUTER);
+      if (rc) return rc;
+      {
+        prof_scope ps(h, PT_K_MOE);
+        const int64_t obs = layer * T * rows * c.top_k;
+        ma.forced = h->routes_in ? h->routes_in + obs : nullptr;
+        ma.chosen_out = h->routes_out ? h->routes_out + obs : nullptr;
+        rc = pt_launch_moe_route(ma, st);
+      }
+      if (rc) return rc;
+      memset(&g, 0, sizeof(g));
+      g.A = abuf; g.a_bstride = rows * d; g.lda = (int32_t)d;
+      g.a_rows = ma.perm; g.a_rows_bstride = w.slots;
+      g.blk_group = ma.blk; g.grp_bstride = w.slots / 64; g.w_gstride = l.expert_elems;
+      g.W = wexp; g.w_bstride = w_bstride; g.ldb = (int32_t)d;
+      g.M = (int32_t)w.slots; g.N = (int32_t)(2 * f); g.K = (int32_t)d; g.batch = (int32_t)T;
+      g.dtype = c.dtype; g.epi = EPI_SWIGLU;
+      g.olp = mbuf; g.olp_bstride = w.slots * f;
+      rc = run_gemm(h, g, PT_K_GEMM_GATEUP);
+      if (rc) return rc;
+      float* ybuf = (float*)(w.base + w.off_y);
+      memset(&g, 0, sizeof(g));
+      g.A = mbuf; g.a_bstride = w.slots * f; g.lda = (int32_t)f;
+      g.blk_group = ma.blk; g.grp_bstride = w.slots / 64; g.w_gstride = l.expert_elems;
+      g.W = wexp + (size_t)(l.wgu_elems * es); g.w_bstride = w_bstride; g.ldb = (int32_t)f;
+      g.M = (int32_t)w.slots; g.N = (int32_t)d; g.K = (int32_t)f; g.batch = (int32_t)T;
+      g.dtype = c.dtype; g.epi = EPI_STORE_F32;
+      g.out = ybuf; g.out_bstride = w.slots * d; g.ldo = (int32_t)d;
+      rc = run_gemm(h, g, PT_K_GEMM_DOWN);
+      if (rc) return rc;
+      {
+        prof_scope ps(h, PT_K_MOE);
+        rc = pt_launch_moe_combine(ma, ybuf, hres, rows * d, hres, (int32_t)d,
+                                   norm_next ? gains + ((layer + 1) * 2 + 0) * d : nullptr, L * 2 * d,
+                                   norm_next ? abuf : nullptr, c.dtype, c.rms_eps, st);
+      }
+      if (rc) return rc;
+      qkv_rs_parts = 0;
+    } else {
     // feed-forward half
     memset(&g, 0, sizeof(g));
     g.A = abuf; g.a_bstride = rows * d; g.lda = (int32_t)d;
@@ -647,12 +760,10 @@ static int forward(pt_handle* h, const pt_workspace& w, const int32_t* dev_token
     g.dtype = c.dtype; g.epi = EPI_RESIDUAL;
     g.out = hres; g.out_bstride = rows * d; g.ldo = (int32_t)d;
     g.res = hres; g.res_bstride = rows * d;
-    // inside a block the next layer's first RMSNorm follows directly; at a block end the merge comes first
-    const bool block_end = (layer + 1) % c.block_depth == 0;
-    const bool norm_next = !block_end && !fuse_qkv_norm;
     rc = run_residual_gemm_norm(h, g, PT_K_GEMM_DOWN, norm_next ? gains + ((layer + 1) * 2 + 0) * d : nullptr,
                                 L * 2 * d, abuf, &qkv_proto, &qkv_rs_parts);
     if (rc) return rc;
+    }
     normed = norm_next;
 
     // Algorithm 1: after every D-th layer, all-reduce the track activations; every track
@@ -780,6 +891,8 @@ extern "C" int pt_prefill_ragged(pt_handle* h, const int32_t* dev_tokens, const 
     if (h->cfg.vocab == 0) return pt_set_error(PT_ERR_INVALID_ARGUMENT, "model has no vocabulary: no logits");
     if (!dev_logits) return pt_set_error(PT_ERR_NULL_POINTER, "logits requested but dev_logits is NULL");
   }
+  if (h->routes_out || h->routes_in)
+    return pt_set_error(PT_ERR_BAD_STATE, "the expert-selection observation points (pt_set_moe_routes) are not available for a ragged prefill");
   int rc = check_inputs(h, dev_tokens, dev_hidden_in, hidden_tracks);
   if (rc) return rc;
   // padded-packed layout: every sequence starts on a multiple of 64 rows

@@ -37,8 +37,12 @@ struct pt_layout {
   int64_t n_qkv;        // (H + 2*Hkv) * hd
   int64_t hq;           // H * hd
   int64_t hk;           // Hkv * hd
-  int64_t wqkv_elems, wo_elems, wgu_elems, wd_elems;  // per (track, layer)
-  int64_t layer_w_elems;                               // sum of the four
+  int64_t wqkv_elems, wo_elems, wgu_elems, wd_elems;  // per (track, layer); gate/up and down once per expert
+  int64_t wr_elems;                                    // PT-MoE router [e_pad, d] (0 for a dense model)
+  int64_t e_pad;                                       // experts rounded up to 4: pitch of the router logits
+  int64_t expert_elems;                                // wgu_elems + wd_elems: distance between two experts
+  int64_t off_wr_elems, off_exp_elems;                 // element offsets of the router / first expert in a layer block
+  int64_t layer_w_elems;                               // everything of one (track, layer)
   int64_t s_pad;                                       // Vt row pitch (elements)
   // byte offsets inside the weight arena
   size_t off_layers;    // [T][L] blocks of layer_w_elems elements
@@ -74,6 +78,17 @@ struct pt_workspace {
   size_t off_rinv;    // fp32 [T, rows] 1/rms of every row, from those sums
   size_t off_rowmap;  // int2 [rows] (sequence, position) of every row of a ragged batch
   size_t off_rowidx;  // int32 [rows] packed row of every valid token, then [max_batch] last rows (ragged prefill)
+  // PT-MoE (all absent for a dense model).  An assignment is one (row, chosen expert) pair; assignments are
+  // grouped by expert into `slots`: expert e of a track owns a segment of slots that starts at a multiple of 256.
+  int64_t slots;      // slot capacity per track: rows * top_k plus up to 255 padding slots per expert, a multiple of 256
+  size_t off_rlogit;  // fp32 [T, rows, e_pad] router logits
+  size_t off_route;   // int32 [T, rows, k] chosen experts
+  size_t off_gate;    // fp32 [T, rows, k] their gates
+  size_t off_slot;    // int32 [T, rows, k] slot of every assignment
+  size_t off_perm;    // int32 [T, slots] row of every slot (0 in padding slots)
+  size_t off_blk;     // int32 [T, slots / 64] expert of every 64-slot block, -1 where the block holds no assignment
+  size_t off_cnt;     // int32 [T, rows / 256 + 2, 64] per 256-row block: assignments per expert in earlier blocks; then totals, segment bases
+  size_t off_y;       // fp32 [T, slots, d] expert outputs per slot
   size_t bytes;
   int64_t skp_floats; // capacity behind off_skp
   int32_t max_splits; // capacity behind off_part, in splits per (track, sequence, head)
@@ -118,6 +133,8 @@ struct pt_handle {
   bool rope_ready;    // the rotary table and the device status word have been written
   float* taps;
   float* track_taps;
+  int32_t* routes_out;          // PT-MoE observation / forcing points (pt_set_moe_routes)
+  const int32_t* routes_in;
   int32_t path;
   pt_prof prof;
 };
@@ -190,6 +207,14 @@ struct pt_gemm_args {
   int32_t nf_parts;
   const float* rs_inv;
   int64_t rs_bstride;
+  // Grouped GEMM (PT-MoE experts): rows are slots grouped by expert in 256-aligned segments.
+  //   a_rows    : when given, GEMM row m of track b reads A row a_rows[b * a_rows_bstride + m] (a gather)
+  //   blk_group : per 64-row block of track b, the weight group (expert) of its rows, or -1: the block holds no
+  //               row and tiles that start in it do nothing; W of group e starts w_gstride elements after e-1's
+  const int32_t* a_rows;
+  int64_t a_rows_bstride;
+  const int32_t* blk_group;
+  int64_t grp_bstride, w_gstride;
 };
 
 enum { PT_SK_PART_FLOATS = 16 << 20 };   // K-slice scratch inside the caller's workspace arena
@@ -293,6 +318,34 @@ int pt_launch_resnorm(const float* part, int32_t slices, const float* res, int64
 int pt_launch_fill_f32(float* dst, int64_t n, float v, hipStream_t s);
 // out[r] = 1 / sqrt(sum_p ss[r][p] / d + eps) for r < rows (rows of all tracks back to back)
 int pt_launch_row_inv_rms(const float* ss, int32_t parts, int64_t rows, int32_t d, float eps, float* out, hipStream_t s);
+// ---------------------------------------------------------------------------------------------
+// PT-MoE: expert selection, grouping, weighted combine (kernels_moe.hip).  Shapes: T tracks, rows per track, E
+// experts (logit pitch e_pad), k experts per row.
+// ---------------------------------------------------------------------------------------------
+struct pt_moe_args {
+  int32_t T, E, e_pad, k;
+  int64_t rows, slots;
+  const float* logits;   // [T, rows, e_pad]
+  int32_t* route;        // [T, rows, k]
+  float* gate;           // [T, rows, k]
+  int32_t* slot;         // [T, rows, k]
+  int32_t* perm;         // [T, slots]
+  int32_t* blk;          // [T, slots / 64]
+  int32_t* cnt;          // [T, rows / 256 + 2, 64]
+  const int32_t* forced; // [T, rows, k] or null; track stride forced_bstride
+  int32_t* chosen_out;   // [T, rows, k] or null; same stride
+  int64_t obs_bstride;
+  int32_t* flag;         // device status word (bit 1: a forced selection was invalid)
+};
+// Top-k of the router logits and the gates (softmax over the chosen logits), then the grouping: slot of every
+// assignment, row of every slot, expert of every 64-slot block.
+int pt_launch_moe_route(const pt_moe_args& a, hipStream_t s);
+// h[t][r][:] = res[t][r][:] + sum_j gate[t][r][j] * y[t][slot[t][r][j]][:] (j in order), then, when out is given,
+// out[t][r][:] = RMSNorm(h[t][r][:]) * gains[t][:] in `dtype`.  res may alias h.
+int pt_launch_moe_combine(const pt_moe_args& a, const float* y, const float* res, int64_t res_bstride, float* h,
+                          int32_t d, const float* gains, int64_t g_bstride, void* out, int32_t dtype, float eps,
+                          hipStream_t s);
+
 // Sets attribute hipFuncAttributeMaxDynamicSharedMemorySize once per kernel (thread-safe: the result is the
 // initialiser of a function-local static at the call site).
 #define PT_SET_MAX_LDS_ONCE(kern, bytes)                                                                   \

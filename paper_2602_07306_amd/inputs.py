@@ -47,7 +47,7 @@ KIND_WO = 6
 KIND_WG = 7
 KIND_WU = 8
 KIND_WD = 9
-KIND_WR = 10
+KIND_WR = 13
 KIND_TOKENS = 16
 KIND_HIDDEN = 17
 

@@ -1,0 +1,180 @@
+"""GPU parity of PT-MoE models (a routed mixture of SwiGLU experts inside every track) against the CPU oracle.
+
+The expert selection is an integer that floating point decides, so the comparison has two legs: with the oracle's
+selection prescribed to the library (pt_set_moe_routes) every output must agree to the usual tolerance, and the
+library's own selection must equal the oracle's wherever the oracle's routing margin is wider than that
+tolerance."""
+import numpy as np
+import pytest
+
+from oracle import pt_oracle as O
+from paper_2602_07306_amd import inputs as I
+from tests.helpers import BF16_TOL, FP32_TOL, assert_close, oracle_prefill, small_bf16_config
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+MOE_GEMMS = ("gemm_router", "gemm_gateup", "gemm_down")
+
+
+def stack_routes(routes, B, S):
+    """Per-sequence [L, T, S, k] arrays -> the library's [L, T, B*S, k]."""
+    return np.concatenate(routes, axis=2)
+
+
+def run_moe_case(cfg, seed, B, S, steps, tol, paths):
+    from paper_2602_07306_amd import binding as PB
+    W = I.make_weights(cfg, seed)
+    tokens = I.make_tokens(seed, B, S, cfg.vocab)
+    ref, st = oracle_prefill(cfg, W, tokens)
+    ref_routes = stack_routes(ref["routes"], B, S)
+    ref_margin = np.concatenate(ref["route_margins"], axis=2)          # [L, T, B*S]
+    nxt = np.argmax(ref["logits"][:, -1], -1).astype(np.int32)
+    dec_refs = []
+    for _ in range(steps):
+        r = O.pt_decode_step(cfg, W, st, tokens=nxt)
+        dec_refs.append((nxt.copy(), r))
+        nxt = r["argmax"]
+    model = PB.PTModel(cfg)
+    model.pt_init_weights(seed)
+    # the device generator reproduces the router and one expert of the host generator bit for bit
+    got = model.pt_get_weight("wr", cfg.n_tracks - 1, 1, (cfg.d_model, cfg.n_experts))
+    assert np.array_equal(got, W["wr"][cfg.n_tracks - 1, 1])
+    e = cfg.n_experts - 1
+    got = model.pt_get_weight("wu", 0, PB.pt_expert_layer(1, e), (cfg.d_model, cfg.d_ffn))
+    assert np.array_equal(got, W["wu"][0, 1, e])
+    got = model.pt_get_weight("wd", 0, PB.pt_expert_layer(0, 0), (cfg.d_ffn, cfg.d_model))
+    assert np.array_equal(got, W["wd"][0, 0, 0])
+    tok_dev = torch.from_numpy(tokens).cuda()
+    for path in paths:
+        model.pt_set_kernel_path(path)
+        # leg 1: the library routes by itself
+        model.pt_reset()
+        own = model.pt_set_moe_routes(B * S)
+        model.pt_prefill(tok_dev, logits_mode=PB.PT_LOGITS_NONE)
+        torch.cuda.synchronize()
+        own = own.cpu().numpy()
+        assert own.min() >= 0 and own.max() < cfg.n_experts
+        assert all(len(set(sel)) == cfg.top_k for sel in own.reshape(-1, cfg.top_k)[:4096])
+        same = np.all(np.sort(own, -1) == np.sort(ref_routes, -1), axis=-1)      # [L, T, B*S], as sets
+        decided0 = ref_margin[0] > tol
+        # layer 0 sees inputs that differ by rounding only: every decided selection must agree
+        assert np.all(same[0][decided0]), "layer-0 selection differs on %d decided rows" % np.sum(~same[0][decided0])
+        assert decided0.mean() > 0.5
+        assert same.mean() > 0.9, "only %.3f of all selections agree with the oracle" % same.mean()
+        # leg 2: the oracle's selection prescribed
+        model.pt_reset()
+        model.pt_profile_reset()
+        seen = model.pt_set_moe_routes(B * S, forced=ref_routes)
+        taps, _ = model.pt_set_taps(B * S)
+        lg, hid = model.pt_prefill(tok_dev, logits_mode=PB.PT_LOGITS_ALL, want_hidden=True)
+        torch.cuda.synchronize()
+        assert np.array_equal(seen.cpu().numpy(), ref_routes)
+        assert_close(hid.cpu().numpy(), ref["hidden"], tol, "prefill hidden")
+        assert_close(lg.cpu().numpy().reshape(B, S, -1), ref["logits"], tol, "prefill logits")
+        for b in range(B):
+            for k in range(cfg.n_merges):
+                assert_close(taps[k].cpu().numpy().reshape(B, S, -1)[b], ref["taps"][b][k], tol, "tap %d" % k)
+        model.pt_clear_taps()
+        pre = {c: model.pt_profile_paths(c) for c in MOE_GEMMS}
+        model.pt_profile_reset()
+        for i, (tok, r) in enumerate(dec_refs):
+            seen = model.pt_set_moe_routes(B, forced=r["routes"])
+            lg, _, _ = model.pt_decode_step(torch.from_numpy(tok).cuda())
+            torch.cuda.synchronize()
+            assert np.array_equal(seen.cpu().numpy(), r["routes"])
+            assert_close(lg.cpu().numpy(), r["logits"], tol, "decode step %d" % i)
+        dec = {c: model.pt_profile_paths(c) for c in MOE_GEMMS}
+        model.pt_clear_moe_routes()
+        model.pt_sync_status()
+        L = cfg.n_layers
+        for c in MOE_GEMMS:
+            assert sum(pre[c]) == L and sum(dec[c]) == L * steps, (c, pre[c], dec[c])
+            if path == PB.PT_PATH_GENERIC:
+                assert pre[c][0] == L and dec[c][0] == L * steps
+            elif cfg.dtype == I.PT_BF16 and cfg.d_model % 128 == 0 and cfg.d_ffn % 128 == 0:
+                assert pre[c][0] == 0 and dec[c][0] == 0, ("fell back to the generic GEMM", c, pre[c], dec[c])
+    model.close()
+
+
+CASES = {
+    # name: (config overrides, B, S, decode steps)
+    "four_experts_top2": (dict(n_experts=4, top_k=2), 2, 128, 2),
+    "eight_experts_top2_gqa": (dict(n_experts=8, top_k=2, n_kv_heads=2, d_ffn=256), 2, 96, 2),
+    "top1": (dict(n_experts=4, top_k=1, n_tracks=3, n_layers=3, block_depth=1, merge_scale=1.0 / 3), 1, 64, 2),
+    "all_experts_taken": (dict(n_experts=3, top_k=3, n_layers=2, block_depth=2), 1, 160, 1),
+    "one_expert": (dict(n_experts=1, top_k=1, n_layers=2, block_depth=1), 2, 64, 1),
+    # far more experts than a decode step has assignments: most expert segments are empty
+    "sixteen_experts_mostly_empty": (dict(n_experts=16, top_k=2, n_layers=2, block_depth=2, d_model=512, n_heads=8,
+                                          n_kv_heads=2, d_ffn=256), 1, 32, 3),
+    # several 256-row counting blocks and GEMM tiles per expert, ragged last block
+    "many_rows": (dict(n_experts=4, top_k=2, n_layers=2, block_depth=2, max_batch=3, max_seq=320), 3, 300, 1),
+}
+
+
+@pytest.mark.parametrize("name", sorted(CASES))
+def test_small_bf16_moe_models_match_the_oracle(name):
+    from paper_2602_07306_amd import binding as PB
+    over, B, S, steps = CASES[name]
+    cfg = small_bf16_config(**over)
+    run_moe_case(cfg, 11 + len(name), B, S, steps, BF16_TOL, (PB.PT_PATH_AUTO, PB.PT_PATH_GENERIC))
+
+
+def test_fp32_moe_model_matches_the_oracle():
+    from paper_2602_07306_amd import binding as PB
+    cfg = I.PTConfig(n_tracks=2, n_layers=4, block_depth=2, d_model=128, n_heads=4, n_kv_heads=2, head_dim=32,
+                     d_ffn=96, vocab=512, max_batch=2, max_seq=96, dtype=I.PT_F32, n_experts=5, top_k=2)
+    run_moe_case(cfg, 3, 2, 70, 2, FP32_TOL, (PB.PT_PATH_AUTO,))
+
+
+def test_invalid_prescribed_selection_is_reported():
+    from paper_2602_07306_amd import binding as PB
+    cfg = small_bf16_config(n_experts=4, top_k=2, n_layers=2, block_depth=2)
+    model = PB.PTModel(cfg)
+    model.pt_init_weights(1)
+    tokens = torch.from_numpy(I.make_tokens(1, 1, 32, cfg.vocab)).cuda()
+    forced = np.zeros((cfg.n_layers, cfg.n_tracks, 32, 2), dtype=np.int32)     # expert 0 twice
+    model.pt_set_moe_routes(32, forced=forced)
+    model.pt_prefill(tokens)
+    with pytest.raises(PB.PTError) as err:
+        model.pt_sync_status()
+    assert err.value.code == PB.PT_ERR_INVALID_ARGUMENT and "expert" in str(err.value)
+    model.pt_sync_status()   # the flag was cleared
+    model.pt_clear_moe_routes()
+    # the observation points address rows of an evenly shaped batch; a ragged prefill refuses them
+    model.pt_set_moe_routes(30)
+    with pytest.raises(PB.PTError) as err:
+        model.pt_prefill_ragged([10, 20], tokens=tokens[0, :30].contiguous())
+    assert err.value.code == PB.PT_ERR_BAD_STATE
+    model.close()
+
+
+def test_ragged_fp32_moe_batch_matches_the_oracle():
+    """Sequences of different lengths through the padded-packed layout: the padding rows are routed like any row
+    and must not disturb the real ones.  fp32, so the library's own selection equals the oracle's."""
+    from paper_2602_07306_amd import binding as PB
+    cfg = I.PTConfig(n_tracks=2, n_layers=2, block_depth=1, d_model=128, n_heads=4, n_kv_heads=4, head_dim=32,
+                     d_ffn=64, vocab=512, max_batch=3, max_seq=128, dtype=I.PT_F32, n_experts=4, top_k=2)
+    W = I.make_weights(cfg, 5)
+    lens = [70, 5, 33]
+    S = max(lens)
+    tokens = I.make_tokens(5, 3, S, cfg.vocab)
+    st = O.PTState(cfg, 3, cfg.max_seq)
+    ref = O.pt_prefill(cfg, W, st, tokens=tokens, lengths=np.array(lens))
+    assert min(float(m.min()) for m in ref["route_margins"]) > 1e-4, "choose another seed: a selection is undecided"
+    packed = np.concatenate([tokens[b, :n] for b, n in enumerate(lens)])
+    model = PB.PTModel(cfg)
+    model.pt_init_weights(5)
+    lg, hid = model.pt_prefill_ragged(lens, tokens=torch.from_numpy(packed).cuda(), logits_mode=PB.PT_LOGITS_LAST,
+                                      want_hidden=True)
+    torch.cuda.synchronize()
+    want = np.concatenate([ref["hidden"][b, :n] for b, n in enumerate(lens)])
+    assert_close(hid.cpu().numpy(), want, FP32_TOL, "ragged hidden")
+    last = np.stack([ref["logits"][b, n - 1] for b, n in enumerate(lens)])
+    assert_close(lg.cpu().numpy(), last, FP32_TOL, "ragged last logits")
+    nxt = np.argmax(last, -1).astype(np.int32)
+    r = O.pt_decode_step(cfg, W, st, tokens=nxt)
+    lg, _, _ = model.pt_decode_step(torch.from_numpy(nxt).cuda())
+    assert_close(lg.cpu().numpy(), r["logits"], FP32_TOL, "ragged decode")
+    model.pt_sync_status()
+    model.close()
