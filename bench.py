@@ -22,7 +22,7 @@ resident in HBM before the timed region.  One JSON line is printed on stdout:
                 mixed lengths: ragged prefill and decode)
   cpu_baseline  the CPU oracle (numpy float64) on a stated, bounded sample of the headline workload
 
---legs selects a subset (comma list of large-prefill, large-decode-gqa, large-decode-mha, share-prefill,
+--legs selects a subset (comma list of moe-prefill, moe-decode, large-prefill, large-decode-gqa, large-decode-mha, share-prefill,
 share-decode, mid-prefill, mid-decode, throughput, cpu; default all), which is how the per-kernel profiles under
 profiles/ are taken.  Other modes: --paper-sweep (batch-1 latency over input lengths), --ceilings (sustained
 MFMA and HBM-read rates of two bare loops).
@@ -41,11 +41,11 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
 
 ALL_LEGS = ["large-prefill", "large-decode-gqa", "large-decode-mha", "share-prefill", "share-decode",
-            "mid-prefill", "mid-decode", "throughput", "cpu"]
-PREFILL_CLASSES = ["embed", "rmsnorm", "gemm_qkv", "attn_prefill", "gemm_out", "gemm_gateup", "gemm_down",
-                   "merge", "gemm_head"]
-DECODE_CLASSES = ["embed", "rmsnorm", "gemm_qkv", "attn_decode", "gemm_out", "gemm_gateup", "gemm_down",
-                  "merge", "gemm_head"]
+            "mid-prefill", "mid-decode", "throughput", "moe-prefill", "moe-decode", "cpu"]
+PREFILL_CLASSES = ["embed", "rmsnorm", "gemm_qkv", "attn_prefill", "gemm_out", "gemm_router", "moe", "gemm_gateup",
+                   "gemm_down", "merge", "gemm_head"]
+DECODE_CLASSES = ["embed", "rmsnorm", "gemm_qkv", "attn_decode", "gemm_out", "gemm_router", "moe", "gemm_gateup",
+                  "gemm_down", "merge", "gemm_head"]
 FAMILY_NAMES = {
     "gemm": ["shape-generic", "MFMA tile kernel", "weight-streaming kernel", "matrix-vector kernel"],
     "attn_prefill": ["shape-generic", "flash kernel, LDS key/value tiles", "flash kernel, register operands", ""],
@@ -63,13 +63,16 @@ def prefill_flops(cfg, B, S, head_rows):
     T, L, d, f = cfg.n_tracks, cfg.n_layers, cfg.d_model, cfg.d_ffn
     hq, hk = cfg.n_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
     rows = B * S
+    k = cfg.top_k if cfg.n_experts else 1     # PT-MoE: every token runs top_k experts of width d_ffn
     per_class = {
         "gemm_qkv": 2.0 * rows * d * (hq + 2 * hk) * T,
         "gemm_out": 2.0 * rows * hq * d * T,
-        "gemm_gateup": 2.0 * rows * d * 2 * f * T,
-        "gemm_down": 2.0 * rows * f * d * T,
+        "gemm_gateup": 2.0 * rows * k * d * 2 * f * T,
+        "gemm_down": 2.0 * rows * k * f * d * T,
         "attn_prefill": 2.0 * S * S * hq * B * T,
     }
+    if cfg.n_experts:
+        per_class["gemm_router"] = 2.0 * rows * d * cfg.n_experts * T
     total = L * sum(per_class.values()) + 2.0 * head_rows * d * cfg.vocab
     return total, per_class
 
@@ -78,7 +81,14 @@ def decode_bytes(cfg, B, ctx):
     """Algorithmic HBM bytes of one decode step: every weight once, the KV cache once."""
     T, L, d, f = cfg.n_tracks, cfg.n_layers, cfg.d_model, cfg.d_ffn
     hq, hk = cfg.n_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
-    weights = T * L * (d * (hq + 2 * hk) + hq * d + 3 * d * f) * 2.0
+    if cfg.n_experts:
+        # expected number of distinct experts the B * top_k assignments of a (track, layer) touch, uniform routing
+        E = cfg.n_experts
+        touched = E * (1.0 - (1.0 - cfg.top_k / E) ** B)
+        ffn = touched * 3 * d * f + d * E
+    else:
+        ffn = 3 * d * f
+    weights = T * L * (d * (hq + 2 * hk) + hq * d + ffn) * 2.0
     kv_per_launch = T * B * ctx * 2 * hk * 2.0
     return weights, kv_per_launch * L, kv_per_launch
 
@@ -559,6 +569,14 @@ def main():
             args.mid_decode_steps, 2, token_seed=2, traffic_file="mid_decode_attn_traffic.json")
     if "throughput" in legs:
         other["throughput_mode"] = run_throughput_leg(torch, PB, I, 16)
+    if "moe-prefill" in legs:
+        other["moe_prefill"] = run_prefill_leg(
+            torch, PB, I, "Large PT-MoE prefill 8 x 4096 (8 experts of width 4096 per track and layer, top-2)",
+            I.config_large_moe(max_batch=8, max_seq=4096), 8, 4096, 3, max(args.steps // 2, 3), 1)
+    if "moe-decode" in legs:
+        decode["large_moe"] = run_decode_leg(
+            torch, PB, I, "Large PT-MoE decode, 2 KV heads per track, batch 64, context 4096",
+            I.config_large_moe(max_batch=64, max_seq=4096 + 64, n_kv_heads=2), 64, 4096, 3, args.decode_steps, 2)
     cpu = run_cpu_baseline(I) if "cpu" in legs else None
 
     cfg = I.config_large()

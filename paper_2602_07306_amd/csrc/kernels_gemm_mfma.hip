@@ -57,9 +57,11 @@ static int choose_cfg(const pt_gemm_args& g) {
   // measured: the direct-to-LDS variant (10) wins for the QKV epilogue and, at short K, for SwiGLU
   static const int big[] = {0, 4, 2, -1}, big_qkv[] = {10, 8, 0, 4, 2, -1}, big_dl[] = {10, 0, 4, 2, -1}, mid[] = {4, 2, -1}, m64[] = {3, 6, -1}, m32[] = {5, 7, -1};
   const int* cand;
-  if (g.M <= 32) cand = m32;
-  else if (g.M <= 64) cand = m64;
-  else if (g.M <= 128 || (int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256) * g.batch < 200) cand = mid;
+  // grouped GEMM: the tile height follows the rows of an average group, not the padded total
+  const int m_sel = g.blk_group && g.grp_rows > 0 && g.grp_rows < g.M ? g.grp_rows : g.M;
+  if (m_sel <= 32) cand = m32;
+  else if (m_sel <= 64) cand = m64;
+  else if (m_sel <= 128 || (int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256) * g.batch < 200) cand = mid;
   else cand = g.epi == EPI_QKV ? big_qkv : (g.epi == EPI_SWIGLU && g.K <= 1024) ? big_dl : big;
   if (pt_tune_gemm_cfg >= 0 && pt_tune_gemm_cfg < GM_NCFG) return cfg_fits(g, pt_tune_gemm_cfg) ? pt_tune_gemm_cfg : -1;
   for (; *cand >= 0; ++cand)

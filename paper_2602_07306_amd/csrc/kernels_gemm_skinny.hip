@@ -173,7 +173,9 @@ __device__ __forceinline__ void skinny_body(const pt_gemm_args& g, int b, int fi
 #pragma unroll
   for (int j = 0; j < 4 * MI; ++j) {
     const int row = j * 8 + (lane >> 3);
-    a_src[j] = (const bf16_t*)g.A + b * g.a_bstride + (int64_t)min(row, g.M - 1) * g.lda + k_first + (lane & 7) * 8;
+    const int mrow = min(row, g.M - 1);
+    const int64_t arow = g.a_rows ? g.a_rows[b * g.a_rows_bstride + mrow] : mrow;   // grouped GEMM: gathered rows
+    a_src[j] = (const bf16_t*)g.A + b * g.a_bstride + arow * g.lda + k_first + (lane & 7) * 8;
   }
   u32x4_t areg[4 * MI], wreg[2][RB][4];
   auto load_a = [&](int step) {
@@ -447,6 +449,33 @@ static int launch_gemv_m(const pt_gemm_args& g, int tiles, hipStream_t s) {
   return launch_gemv<4, EPI>(g, tiles, s);
 }
 
+// Grouped GEMM (rows grouped by weight matrix, e.g. the experts of a PT-MoE layer): the batch index of the grid runs
+// over (track, group); a workgroup works on the rows of its group only, through a view of the arguments whose
+// pointers start at the group's first row.  Groups without rows are skipped, their weights never read.
+template <int MI, int RB, int EPI>
+__device__ __forceinline__ void skinny_group(const pt_gemm_args& g, int bg, int first_tile, int ks, int ksn) {
+  const int t = bg / g.n_groups, e = bg - t * g.n_groups;
+  const int count = g.grp_count[t * g.grp_info_bstride + e];
+  if (count <= 0) return;
+  const int base = g.grp_base[t * g.grp_info_bstride + e];
+  pt_gemm_args v = g;
+  v.M = min(count, 32 * MI);
+  v.W = (const bf16_t*)g.W + t * g.w_bstride + e * g.w_gstride;
+  v.A = (const bf16_t*)g.A + t * g.a_bstride + (g.a_rows ? 0 : (int64_t)base * g.lda);
+  v.a_rows = g.a_rows ? g.a_rows + t * g.a_rows_bstride + base : nullptr;
+  if constexpr (EPI == EPI_SWIGLU) v.olp = (bf16_t*)g.olp + t * g.olp_bstride + (int64_t)base * (g.N >> 1);
+  else v.out = g.out + t * g.out_bstride + (int64_t)base * g.ldo;
+  skinny_body<MI, RB, EPI>(v, 0, first_tile, ks, ksn);
+}
+
+template <int MI, int RB, int EPI>
+__device__ __forceinline__ void skinny_dispatch(const pt_gemm_args& g, int b, int first_tile, int ks, int ksn) {
+  if constexpr (EPI == EPI_SWIGLU || EPI == EPI_STORE_F32) {
+    if (g.n_groups > 0) { skinny_group<MI, RB, EPI>(g, b, first_tile, ks, ksn); return; }
+  }
+  skinny_body<MI, RB, EPI>(g, b, first_tile, ks, ksn);
+}
+
 // The tiles (blocks of 32 weight rows) of a track are dealt out to wgs_per_track workgroups as evenly as
 // possible: `rem` workgroups take RBHI tiles, the others RBHI - 1 (all take RBHI when rem == 0).  The grid
 // lists the larger workgroups of all tracks first, so that a second round of workgroups fills up evenly.
@@ -456,18 +485,18 @@ __global__ void __launch_bounds__(256) gemm_skinny_kernel(const pt_gemm_args g, 
   const int unit = blockIdx.x / ksn, ks = blockIdx.x - unit * ksn;
   if (rem == 0) {
     const int b = unit / wgs_per_track, wg = unit - b * wgs_per_track;
-    skinny_body<MI, RBHI, EPI>(g, b, wg * RBHI, ks, ksn);
+    skinny_dispatch<MI, RBHI, EPI>(g, b, wg * RBHI, ks, ksn);
     return;
   }
   const int n_big = rem * g.batch;
   if (unit < n_big) {
     const int b = unit / rem, wg = unit - b * rem;
-    skinny_body<MI, RBHI, EPI>(g, b, wg * RBHI, ks, ksn);
+    skinny_dispatch<MI, RBHI, EPI>(g, b, wg * RBHI, ks, ksn);
   } else {
     if constexpr (RBHI > 1) {
       const int small = wgs_per_track - rem, u2 = unit - n_big;
       const int b = u2 / small, wg = u2 - b * small;
-      skinny_body<MI, RBHI - 1, EPI>(g, b, rem * RBHI + wg * (RBHI - 1), ks, ksn);
+      skinny_dispatch<MI, RBHI - 1, EPI>(g, b, rem * RBHI + wg * (RBHI - 1), ks, ksn);
     }
   }
 }
@@ -575,7 +604,7 @@ static bool skinny_covers(const pt_gemm_args& g) {
 // slices itself (0: the kernel does not cover the shape; 1: no split).
 // one to four rows: matrix-vector kernel, if A fits its LDS budget and the grid is at least half a round
 static bool use_gemv(const pt_gemm_args& g) {
-  return g.M <= 4 && pt_tune_skinny_plan == 0 && g.K % 512 == 0 &&
+  return g.M <= 4 && g.n_groups == 0 && pt_tune_skinny_plan == 0 && g.K % 512 == 0 &&
          (int64_t)(g.M == 3 ? 4 : g.M) * g.K * 2 <= 48 * 1024 && (int64_t)(g.N / 32) * g.batch >= 128;
 }
 
@@ -591,7 +620,16 @@ int pt_gemm_skinny_ksplit(const pt_gemm_args& g) {
 
 // Returns the kernel family launched (2, or 3 for the matrix-vector form), 0 if the shape is not covered.  With allow_split the K slices chosen by
 // pt_gemm_skinny_ksplit are left in g.sk_part instead of the finished residual stream.
-int pt_launch_gemm_skinny(const pt_gemm_args& g, bool allow_split, hipStream_t s) {
+int pt_launch_gemm_skinny(const pt_gemm_args& g_in, bool allow_split, hipStream_t s) {
+  pt_gemm_args g = g_in;
+  if (g.n_groups > 0) {
+    // grouped: one batch entry per (track, group), each with at most grp_max_rows rows
+    if (g.grp_max_rows > 64 || !g.grp_count || !g.grp_base || (g.w_gstride & 7)) return 0;
+    if (g.epi != EPI_SWIGLU && g.epi != EPI_STORE_F32) return 0;
+    g.M = g.grp_max_rows;
+    g.batch = g_in.batch * g.n_groups;
+    allow_split = false;
+  }
   if (!skinny_covers(g)) return 0;
   const int tiles = g.N / 32;
   const int ks_max = allow_split && g.epi == EPI_RESIDUAL && g.sk_part && !(g.N & 3) ? 16 : 1;

@@ -7,7 +7,7 @@
 // tile height), in row order inside an expert.  The order is fixed by counting, not by atomics: per 256-row block
 // the assignments per expert are counted (ballots), an exclusive scan over the blocks gives every block its first
 // slot per expert, and the block's rows take consecutive slots in row order.  Slots between the end of an
-// expert's assignments and the next multiple of 256 are padding: their row index is 0 (any valid row: the GEMMs
+// expert's assignments and the next multiple of 256 are padding: their row index is some valid row (the GEMMs
 // compute them and nobody reads the result), and 64-slot blocks made of padding only are marked -1 so that GEMM
 // tiles starting there return at once.
 #include "pt_device.h"
@@ -79,11 +79,14 @@ __device__ __forceinline__ int find_expert(uint64_t packed, int k, int e) {
   return -1;
 }
 
-// Assignments per expert in each block of 256 rows; also clears the row-of-slot table.
+// Assignments per expert in each block of 256 rows; also presets the row-of-slot table for the padding slots.
 __global__ void __launch_bounds__(MOE_ROWS) moe_count_kernel(pt_moe_args a, int nblk) {
   __shared__ int s_cnt[4][64];
   const int blk = blockIdx.x, t = blockIdx.y, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  for (int64_t i = (int64_t)blk * MOE_ROWS + tid; i < a.slots; i += (int64_t)nblk * MOE_ROWS) a.perm[t * a.slots + i] = 0;
+  // padding slots read some valid row; spread them over the rows, since thousands of loads of one row would all
+  // queue on one memory channel
+  for (int64_t i = (int64_t)blk * MOE_ROWS + tid; i < a.slots; i += (int64_t)nblk * MOE_ROWS)
+    a.perm[t * a.slots + i] = (int32_t)(i % a.rows);
   const uint64_t packed = load_packed_route(a, t, (int64_t)blk * MOE_ROWS + tid);
   for (int e = 0; e < a.E; ++e) {
     const uint64_t bal = __ballot(find_expert(packed, a.k, e) >= 0);

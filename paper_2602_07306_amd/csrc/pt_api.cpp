@@ -4,6 +4,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
 #include <mutex>
 #include <new>
 
@@ -423,7 +424,7 @@ static int run_gemm(pt_handle* h, const pt_gemm_args& g_in, int cls) {
   g.sk_part = (float*)(h->active->base + h->active->off_skp);
   g.sk_part_floats = h->active->skp_floats;
   if (h->path == PT_PATH_AUTO) {
-    int r = g.M <= 64 && !g.blk_group && !g.a_rows ? pt_launch_gemm_skinny(g, false, h->stream) : 0;
+    int r = g.M <= 64 || g.n_groups > 0 ? pt_launch_gemm_skinny(g, false, h->stream) : 0;
     if (r < 0) return r;
     if (r > 0) { count_family(h, cls, r); return PT_OK; }
     if (g.norm_src) return pt_set_error(PT_ERR_HIP, "a GEMM that was to form its own normalised operand was not taken by that kernel");
@@ -600,10 +601,14 @@ static int forward(pt_handle* h, const pt_workspace& w, const int32_t* dev_token
   // front of it is always materialised, because the router and the gathered expert GEMMs both read it
   const bool moe = c.n_experts > 0;
   pt_moe_args ma;
+  int64_t moe_nblk = 0;
   memset(&ma, 0, sizeof(ma));
   if (moe) {
     ma.T = (int32_t)T; ma.E = c.n_experts; ma.e_pad = (int32_t)l.e_pad; ma.k = c.top_k;
-    ma.rows = rows; ma.slots = w.slots;
+    // slots of this call's rows (the workspace was laid out for at least as many)
+    ma.rows = rows; ma.slots = (rows * c.top_k + (int64_t)c.n_experts * 255 + 255) / 256 * 256;
+    if (ma.slots > w.slots) return pt_set_error(PT_ERR_CAPACITY, "expert slots exceed the workspace");
+    moe_nblk = (rows + 255) / 256;   // counting blocks of 256 rows: the layout of ma.cnt
     ma.logits = (const float*)(w.base + w.off_rlogit);
     ma.route = (int32_t*)(w.base + w.off_route);
     ma.gate = (float*)(w.base + w.off_gate);
@@ -710,22 +715,28 @@ static int forward(pt_handle* h, const pt_workspace& w, const int32_t* dev_token
       if (rc) return rc;
       memset(&g, 0, sizeof(g));
       g.A = abuf; g.a_bstride = rows * d; g.lda = (int32_t)d;
-      g.a_rows = ma.perm; g.a_rows_bstride = w.slots;
-      g.blk_group = ma.blk; g.grp_bstride = w.slots / 64; g.w_gstride = l.expert_elems;
+      g.a_rows = ma.perm; g.a_rows_bstride = ma.slots;
+      g.blk_group = ma.blk; g.grp_bstride = ma.slots / 64; g.w_gstride = l.expert_elems;
+      g.grp_rows = (int32_t)((rows * c.top_k + c.n_experts - 1) / c.n_experts);
+      g.grp_count = ma.cnt + moe_nblk * 64; g.grp_base = ma.cnt + (moe_nblk + 1) * 64; g.grp_info_bstride = (moe_nblk + 2) * 64;
+      g.n_groups = c.n_experts; g.grp_max_rows = (int32_t)std::min<int64_t>(rows, 0x7fffffff);
       g.W = wexp; g.w_bstride = w_bstride; g.ldb = (int32_t)d;
-      g.M = (int32_t)w.slots; g.N = (int32_t)(2 * f); g.K = (int32_t)d; g.batch = (int32_t)T;
+      g.M = (int32_t)ma.slots; g.N = (int32_t)(2 * f); g.K = (int32_t)d; g.batch = (int32_t)T;
       g.dtype = c.dtype; g.epi = EPI_SWIGLU;
-      g.olp = mbuf; g.olp_bstride = w.slots * f;
+      g.olp = mbuf; g.olp_bstride = ma.slots * f;
       rc = run_gemm(h, g, PT_K_GEMM_GATEUP);
       if (rc) return rc;
       float* ybuf = (float*)(w.base + w.off_y);
       memset(&g, 0, sizeof(g));
-      g.A = mbuf; g.a_bstride = w.slots * f; g.lda = (int32_t)f;
-      g.blk_group = ma.blk; g.grp_bstride = w.slots / 64; g.w_gstride = l.expert_elems;
+      g.A = mbuf; g.a_bstride = ma.slots * f; g.lda = (int32_t)f;
+      g.blk_group = ma.blk; g.grp_bstride = ma.slots / 64; g.w_gstride = l.expert_elems;
+      g.grp_rows = (int32_t)((rows * c.top_k + c.n_experts - 1) / c.n_experts);
+      g.grp_count = ma.cnt + moe_nblk * 64; g.grp_base = ma.cnt + (moe_nblk + 1) * 64; g.grp_info_bstride = (moe_nblk + 2) * 64;
+      g.n_groups = c.n_experts; g.grp_max_rows = (int32_t)std::min<int64_t>(rows, 0x7fffffff);
       g.W = wexp + (size_t)(l.wgu_elems * es); g.w_bstride = w_bstride; g.ldb = (int32_t)f;
-      g.M = (int32_t)w.slots; g.N = (int32_t)d; g.K = (int32_t)f; g.batch = (int32_t)T;
+      g.M = (int32_t)ma.slots; g.N = (int32_t)d; g.K = (int32_t)f; g.batch = (int32_t)T;
       g.dtype = c.dtype; g.epi = EPI_STORE_F32;
-      g.out = ybuf; g.out_bstride = w.slots * d; g.ldo = (int32_t)d;
+      g.out = ybuf; g.out_bstride = ma.slots * d; g.ldo = (int32_t)d;
       rc = run_gemm(h, g, PT_K_GEMM_DOWN);
       if (rc) return rc;
       {

@@ -85,7 +85,7 @@ struct pt_workspace {
   size_t off_route;   // int32 [T, rows, k] chosen experts
   size_t off_gate;    // fp32 [T, rows, k] their gates
   size_t off_slot;    // int32 [T, rows, k] slot of every assignment
-  size_t off_perm;    // int32 [T, slots] row of every slot (0 in padding slots)
+  size_t off_perm;    // int32 [T, slots] row of every slot (some valid row in padding slots)
   size_t off_blk;     // int32 [T, slots / 64] expert of every 64-slot block, -1 where the block holds no assignment
   size_t off_cnt;     // int32 [T, rows / 256 + 2, 64] per 256-row block: assignments per expert in earlier blocks; then totals, segment bases
   size_t off_y;       // fp32 [T, slots, d] expert outputs per slot
@@ -215,6 +215,14 @@ struct pt_gemm_args {
   int64_t a_rows_bstride;
   const int32_t* blk_group;
   int64_t grp_bstride, w_gstride;
+  int32_t grp_rows;   // rows an average group holds (a hint for the tile height; 0 = unknown)
+  // The same groups as (first row, row count) per group, for the weight-streaming kernel, which takes a whole
+  // group per workgroup when no group can hold more than 64 rows (grp_max_rows): group e of track b has
+  // grp_count[b * grp_info_bstride + e] rows starting at row grp_base[b * grp_info_bstride + e].
+  const int32_t* grp_count;
+  const int32_t* grp_base;
+  int64_t grp_info_bstride;
+  int32_t n_groups, grp_max_rows;
 };
 
 enum { PT_SK_PART_FLOATS = 16 << 20 };   // K-slice scratch inside the caller's workspace arena

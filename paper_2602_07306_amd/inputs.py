@@ -293,6 +293,14 @@ def config_large(max_batch: int = 8, max_seq: int = 4096, n_kv_heads: int = 16) 
                     max_batch=max_batch, max_seq=max_seq, dtype=PT_BF16)
 
 
+def config_large_moe(max_batch: int = 8, max_seq: int = 4096, n_kv_heads: int = 16) -> PTConfig:
+    """PT-MoE variant of the Large PT workload (Section 2.2 and the Conclusion: MoE sparsity inside every track).  The
+    paper gives no PT-MoE shapes: here every track's feed-forward network becomes 8 experts of width 4096 with 2
+    experts per token, so a token activates the same 8192 hidden units as in the dense Large model while the
+    feed-forward parameters grow fourfold (about 56 B parameters, 112 GB in bf16)."""
+    return dataclasses.replace(config_large(max_batch, max_seq, n_kv_heads), d_ffn=4096, n_experts=8, top_k=2)
+
+
 def config_paper30b(block_depth: int = 8, max_batch: int = 1, max_seq: int = 4096) -> PTConfig:
     """Shape of the paper's 30B PT model (Section 3.1, Table 1): 8 tracks, 48 layers, 8 query heads and 1 KV
     head per track, track block depth 2, 4 or 8.  The paper prints no widths: per-track d_model 3072,

@@ -178,3 +178,13 @@ def test_ragged_fp32_moe_batch_matches_the_oracle():
     assert_close(lg.cpu().numpy(), r["logits"], FP32_TOL, "ragged decode")
     model.pt_sync_status()
     model.close()
+
+
+def test_large_moe_widths_at_reduced_depth():
+    """Layer shape of the Large PT-MoE benchmark workload (d = 2048, 16 heads x 128, 8 experts of width 4096, 2 per
+    token, vocab 32000) with 2 tracks, 2 layers and a merge after each, 2 x 192 tokens and one decode step."""
+    import dataclasses
+    from paper_2602_07306_amd import binding as PB
+    cfg = dataclasses.replace(I.config_large_moe(max_batch=2, max_seq=256), n_tracks=2, n_layers=2, block_depth=1,
+                              merge_scale=0.5)
+    run_moe_case(cfg, 3, 2, 192, 1, BF16_TOL, (PB.PT_PATH_AUTO,))
