@@ -6,6 +6,11 @@
         --write <dir of the WRITE_SIZE pass> --kernel <substring of the kernel name> --algorithmic-bytes N
         --command "<command of the FETCH_SIZE pass>" --command "<command of the WRITE_SIZE pass>" [--note TEXT]
         > profiles/<kernel>_<workload>_traffic.json
+    python -m paper_2602_07306_amd.profile_summary mfma <dir of the counter pass> --command "<full command>"
+        [--kernel SUBSTRING ...] > profiles/<workload>_mfma_counters.json
+
+`mfma` reads a pass over SQ_INSTS_VALU_MFMA_MOPS_BF16, SQ_VALU_MFMA_BUSY_CYCLES and GRBM_GUI_ACTIVE and reports, per
+kernel, the matrix FLOPs executed and the share of the matrix pipes' cycles that were busy.
 
 `traffic` scales both counters (KiB per dispatch) by what the same counter reads for the plain copy kernel of known
 size that `bench.py --copy-calibration` runs in the same process (hbm_copy_kernel over 1 GiB: 1 GiB read, 1 GiB
@@ -88,6 +93,27 @@ def traffic(args):
     print(json.dumps(rec, indent=1))
 
 
+def mfma(args):
+    mops = counter_means(args.dir, "SQ_INSTS_VALU_MFMA_MOPS_BF16")
+    busy = counter_means(args.dir, "SQ_VALU_MFMA_BUSY_CYCLES")
+    active = counter_means(args.dir, "GRBM_GUI_ACTIVE")
+    rec = {"command": args.command,
+           "reading": "Per launch, mean over launches. SQ_INSTS_VALU_MFMA_MOPS_BF16 counts 512 FLOPs per unit; "
+                      "SQ_VALU_MFMA_BUSY_CYCLES sums the busy cycles of the 1024 MFMA pipes (4 SIMDs x 256 CUs); "
+                      "GRBM_GUI_ACTIVE sums the active cycles of the 8 XCDs, so one eighth of it is the kernel's duration "
+                      "in shader clocks. mfma_pipe_busy = busy / (1024 x duration). Counter runs serialise kernels; "
+                      "durations are a few per cent longer than in the timed run.",
+           "kernels": {}}
+    names = [k for k in mops if mops[k][1] > 0 and (not args.kernel or any(n in k for n in args.kernel))]
+    names.sort(key=lambda k: -mops[k][0] * mops[k][1])
+    for k in names[:args.top]:
+        clocks = active[k][1] / 8.0
+        rec["kernels"][k[:120]] = {"launches": mops[k][0], "mfma_flops_executed": mops[k][1] * 512.0,
+                                   "mfma_busy_cycles": busy[k][1], "duration_shader_clocks": clocks,
+                                   "mfma_pipe_busy": busy[k][1] / (1024.0 * clocks)}
+    print(json.dumps(rec, indent=1))
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     sub = ap.add_subparsers(dest="mode", required=True)
@@ -103,8 +129,13 @@ def main():
     t.add_argument("--algorithmic-bytes", type=float, required=True)
     t.add_argument("--command", action="append", required=True)
     t.add_argument("--note")
+    m = sub.add_parser("mfma")
+    m.add_argument("dir")
+    m.add_argument("--command", required=True)
+    m.add_argument("--kernel", action="append")
+    m.add_argument("--top", type=int, default=6)
     args = ap.parse_args()
-    (kernels if args.mode == "kernels" else traffic)(args)
+    {"kernels": kernels, "traffic": traffic, "mfma": mfma}[args.mode](args)
 
 
 if __name__ == "__main__":
