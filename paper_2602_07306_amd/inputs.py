@@ -261,6 +261,51 @@ def make_weights(cfg: PTConfig, seed: int, tracks: Optional[range] = None) -> Di
     return W
 
 
+class LazyWeights:
+    """The weights of make_weights(cfg, seed), generated tensor by tensor on demand: ``W["wq"][i, l]`` (or
+    ``W["wg"][i, l, e]`` for a PT-MoE model) builds that one tensor from its stream.  For models whose weights do not
+    fit host memory at once; a consumer that walks layers in order holds one tensor at a time."""
+
+    class _Indexer:
+        def __init__(self, make):
+            self._make = make
+
+        def __getitem__(self, idx):
+            return self._make(*idx) if isinstance(idx, tuple) else self._make(idx)
+
+    def __init__(self, cfg: PTConfig, seed: int):
+        self.cfg, self.seed = cfg, seed
+        d = cfg.d_model
+        hq, hk, f = cfg.n_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim, cfg.d_ffn
+        self._shapes = {"wq": (KIND_WQ, (d, hq)), "wk": (KIND_WK, (d, hk)), "wv": (KIND_WV, (d, hk)),
+                        "wo": (KIND_WO, (hq, d)), "wg": (KIND_WG, (d, f)), "wu": (KIND_WU, (d, f)),
+                        "wd": (KIND_WD, (f, d)), "wr": (KIND_WR, (d, cfg.n_experts))}
+        self._global = {}
+
+    def _tensor(self, name, track, layer, expert=None):
+        kind, shp = self._shapes[name]
+        lay = layer if expert is None else expert_layer(layer, expert)
+        return round_to_dtype(normal_tensor(stream_key(self.seed, kind, track, lay), shp, self.cfg.init_std), self.cfg.dtype)
+
+    def __getitem__(self, name):
+        cfg = self.cfg
+        if name in ("g1", "g2"):
+            return LazyWeights._Indexer(lambda i, l: np.ones((cfg.d_model,), dtype=np.float32))
+        if name in ("gf", "embed", "head"):
+            if name not in self._global:
+                if name == "gf":
+                    self._global[name] = np.ones((cfg.d_model,), dtype=np.float32)
+                else:
+                    kind, shp = ((KIND_EMBED, (cfg.vocab, cfg.d_model)) if name == "embed"
+                                 else (KIND_HEAD, (cfg.d_model, cfg.vocab)))
+                    self._global[name] = round_to_dtype(normal_tensor(stream_key(self.seed, kind), shp, cfg.init_std),
+                                                        cfg.dtype)
+            return self._global[name]
+        if name not in self._shapes or (name == "wr" and cfg.n_experts == 0):
+            raise KeyError(name)
+        return LazyWeights._Indexer(lambda i, l, e=None: self._tensor(name, i, l, e))
+
+
 def make_tokens(seed: int, batch: int, seq: int, vocab: int, stream: int = 0) -> np.ndarray:
     """int32 ``[batch, seq]`` token ids, uniform over the vocabulary."""
     key = stream_key(seed, KIND_TOKENS, stream, 0)
