@@ -273,8 +273,10 @@ class LazyWeights:
         def __getitem__(self, idx):
             return self._make(*idx) if isinstance(idx, tuple) else self._make(idx)
 
-    def __init__(self, cfg: PTConfig, seed: int):
-        self.cfg, self.seed = cfg, seed
+    def __init__(self, cfg: PTConfig, seed: int, on_tensor=None):
+        """on_tensor(name, track, layer), when given, is called before a per-layer tensor is generated (a long
+        consumer reports its progress through it)."""
+        self.cfg, self.seed, self.on_tensor = cfg, seed, on_tensor
         d = cfg.d_model
         hq, hk, f = cfg.n_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim, cfg.d_ffn
         self._shapes = {"wq": (KIND_WQ, (d, hq)), "wk": (KIND_WK, (d, hk)), "wv": (KIND_WV, (d, hk)),
@@ -284,6 +286,8 @@ class LazyWeights:
 
     def _tensor(self, name, track, layer, expert=None):
         kind, shp = self._shapes[name]
+        if self.on_tensor is not None:
+            self.on_tensor(name, track, layer)
         lay = layer if expert is None else expert_layer(layer, expert)
         return round_to_dtype(normal_tensor(stream_key(self.seed, kind, track, lay), shp, self.cfg.init_std), self.cfg.dtype)
 

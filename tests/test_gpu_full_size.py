@@ -9,6 +9,7 @@ block tap of the full-depth GPU run).  PT_LONG_TESTS=1 follows all 32 layers and
 (about five minutes of host time, nearly all of it weight generation)."""
 import dataclasses
 import os
+import sys
 
 import numpy as np
 import pytest
@@ -21,7 +22,7 @@ torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
 
 
-def test_large_prefill_at_full_size_matches_the_oracle_on_sampled_positions():
+def test_large_prefill_at_full_size_matches_the_oracle_on_sampled_positions(capsys):
     from paper_2602_07306_amd import binding as PB
     full = os.environ.get("PT_LONG_TESTS") == "1"
     B, S, P, picks = 8, 4096, 64, (5,)
@@ -46,7 +47,13 @@ def test_large_prefill_at_full_size_matches_the_oracle_on_sampled_positions():
     torch.cuda.empty_cache()
 
     ocfg = cfg if full else dataclasses.replace(cfg, n_layers=cfg.block_depth)
-    W = I.LazyWeights(ocfg, 3)
+
+    def progress(name, track, layer):   # one line per layer, past pytest's capture: the oracle works for minutes
+        if name == "wq" and track == 0:
+            with capsys.disabled():
+                print("oracle: layer %d of %d" % (layer + 1, ocfg.n_layers), file=sys.stderr, flush=True)
+
+    W = I.LazyWeights(ocfg, 3, on_tensor=progress)
     for j, b in enumerate(picks):
         st = O.PTState(ocfg, 1, P)
         ref = O.pt_prefill(ocfg, W, st, tokens=tokens[b:b + 1, :P], collect_taps=True)
