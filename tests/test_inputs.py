@@ -61,3 +61,29 @@ def test_make_weights_shapes_and_rounding():
     Wb = I.make_weights(dataclasses.replace(cfg, dtype=I.PT_BF16, n_layers=1, block_depth=1), 0)
     assert np.array_equal(Wb["wq"][0, 0], I.round_to_dtype(W["wq"][0, 0], I.PT_BF16))
     assert np.all((Wb["wq"].view(np.uint32) & 0xFFFF) == 0)
+
+
+def test_expert_streams_and_lazy_weights():
+    """PT-MoE weights: one stream per (tensor, track, layer, expert), distinct from each other and from the dense
+    streams; LazyWeights generates exactly the tensors of make_weights, one at a time."""
+    cfg = I.PTConfig(n_tracks=2, n_layers=2, block_depth=1, d_model=32, n_heads=2, n_kv_heads=1, head_dim=16,
+                     d_ffn=32, vocab=64, max_batch=1, max_seq=8, dtype=I.PT_BF16, n_experts=3, top_k=2)
+    W = I.make_weights(cfg, 9)
+    assert W["wg"].shape == (2, 2, 3, 32, 32) and W["wd"].shape == (2, 2, 3, 32, 32) and W["wr"].shape == (2, 2, 32, 3)
+    flat = [W["wu"][i, l, e].tobytes() for i in range(2) for l in range(2) for e in range(3)]
+    assert len(set(flat)) == len(flat)
+    dense = I.make_weights(I.PTConfig(**{**cfg.__dict__, "n_experts": 0, "top_k": 0}), 9)
+    assert not np.array_equal(dense["wu"][0, 0], W["wu"][0, 0, 0])          # expert 0 is not the dense stream
+    assert np.array_equal(dense["wq"], W["wq"])                              # the attention half is unchanged
+    assert I.stream_key(9, I.KIND_WU, 1, I.expert_layer(1, 2)) != I.stream_key(9, I.KIND_WU, 1, 1)
+    seen = []
+    L = I.LazyWeights(cfg, 9, on_tensor=lambda name, i, l: seen.append((name, i, l)))
+    for name in ("wq", "wk", "wv", "wo"):
+        assert np.array_equal(L[name][1, 0], W[name][1, 0])
+    for name in ("wg", "wu", "wd"):
+        assert np.array_equal(L[name][0, 1, 2], W[name][0, 1, 2])
+    assert np.array_equal(L["wr"][1, 1], W["wr"][1, 1])
+    for name in ("embed", "head", "gf"):
+        assert np.array_equal(L[name], W[name])
+    assert np.array_equal(L["g2"][0, 0], W["g2"][0, 0])
+    assert ("wq", 1, 0) in seen and ("wd", 0, 1) in seen
