@@ -118,6 +118,10 @@ CASES = {
     # one track that merges after every layer (the dense twin of a PT model): the merge is the identity and is
     # skipped over several blocks once no tap is requested (the decode steps here)
     "dense_one_track_three_blocks": (dict(n_tracks=1, n_layers=3, block_depth=1), 2, 64, 3),
+    # the largest track count the library takes; decoding up to the last row of the KV cache (max_seq is not a
+    # multiple of the cache's 64-row granularity)
+    "sixteen_tracks": (dict(n_tracks=16, n_layers=2, block_depth=1, merge_scale=1.0 / 16), 1, 64, 2),
+    "cache_filled_to_the_last_row": (dict(max_batch=2, max_seq=99), 2, 96, 3),
     # per-track shape of the paper's 30B model (Table 1: 8 tracks, 8 query heads and 1 KV head per track), batch 1
     "paper30b_track_shape": (dict(n_tracks=8, n_layers=2, block_depth=2, d_model=512, n_heads=8, n_kv_heads=1,
                                   head_dim=128, d_ffn=1024, max_batch=1, max_seq=512), 1, 192, 3),
