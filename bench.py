@@ -17,13 +17,14 @@ resident in HBM before the timed region.  One JSON line is printed on stdout:
                 for the decode-attention kernel from in-run events): Large PT at batch 64, context 4096 with
                 2 KV heads per track (as written, with 16 KV heads, the cache would need 550 GB), Large PT as
                 written at batch 16, and one GPU's share of the wide model at batch 64, context 8192
-  legs          the other workloads on the same kernels: share prefill 2 x 4096, Mid PT prefill 4 x 1024, Mid PT
+  legs          the other workloads on the same kernels: share prefill 2 x 4096, the share-shape block-end merge
+                (8 x [8192, 8192] bf16 through pt_track_merge), Mid PT prefill 4 x 1024, Mid PT
                 decode (batch 32, 2048-token prompts, 128 steps) and the throughput mode (Mid PT, batch 256 of
                 mixed lengths: ragged prefill and decode)
   cpu_baseline  the CPU oracle (numpy float64) on a stated, bounded sample of the headline workload
 
 --legs selects a subset (comma list of moe-prefill, moe-decode, large-prefill, large-decode-gqa, large-decode-mha, share-prefill,
-share-decode, mid-prefill, mid-decode, throughput, cpu; default all), which is how the per-kernel profiles under
+share-decode, share-merge, mid-prefill, mid-decode, throughput, cpu; default all), which is how the per-kernel profiles under
 profiles/ are taken.  Other modes: --paper-sweep (batch-1 latency over input lengths), --ceilings (sustained
 MFMA and HBM-read rates of two bare loops).
 """
@@ -40,7 +41,7 @@ sys.path.insert(0, ROOT)
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
 
-ALL_LEGS = ["large-prefill", "large-decode-gqa", "large-decode-mha", "share-prefill", "share-decode",
+ALL_LEGS = ["large-prefill", "large-decode-gqa", "large-decode-mha", "share-prefill", "share-decode", "share-merge",
             "mid-prefill", "mid-decode", "throughput", "moe-prefill", "moe-decode", "cpu"]
 PREFILL_CLASSES = ["embed", "rmsnorm", "gemm_qkv", "attn_prefill", "gemm_out", "gemm_router", "moe", "gemm_gateup",
                    "gemm_down", "merge", "gemm_head"]
@@ -338,6 +339,32 @@ def run_throughput_leg(torch, PB, I, steps):
     return rec
 
 
+def run_merge_leg(torch, PB, I, reps=50):
+    """The block-end merge at the one-GPU share shape: own hidden state plus 7 peers', seeded N(0,1) bf16 tensors of
+    [8192 tokens, 8192], through pt_track_merge (T reads and one write of 134 MB each)."""
+    tokens, d, n = 8192, 8192, 8
+    tracks = [torch.from_numpy(I.make_hidden(4, i, tokens, d)).cuda().to(torch.bfloat16) for i in range(n)]
+    out = torch.empty_like(tracks[0])
+    for _ in range(5):
+        PB.pt_track_merge(tracks, 1.0, out=out)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+    ev[0].record()
+    for i in range(reps):
+        PB.pt_track_merge(tracks, 1.0, out=out)
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    per = [ev[i].elapsed_time(ev[i + 1]) for i in range(reps)]
+    nbytes = (n + 1) * tokens * d * 2.0
+    med = median(per)
+    rec = {"workload": "track merge of 8 x [8192, 8192] bf16 (one-GPU share, block end)", "reps": reps,
+           "ms_median": med, "ms_min": min(per), "bytes": nbytes, "GBs": nbytes / (med * 1e-3) / 1e9,
+           "frac_of_hbm_peak": nbytes / (med * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    log("share merge 8 x [8192, 8192] bf16: %.3f ms, %.0f GB/s (%.1f%% of HBM peak)" % (med, rec["GBs"], 100 * rec["frac_of_hbm_peak"]))
+    del tracks, out
+    torch.cuda.empty_cache()
+    return rec
+
+
 def run_cpu_baseline(I):
     """The oracle, as it stands, on a bounded sample of the headline workload: sequence 0 of the 8 x 4096 batch
     through the first layer of each of the 8 tracks and the merge that follows (1/32 of the model's depth; all
@@ -558,6 +585,8 @@ def main():
             torch, PB, I, "one-GPU share decode, batch 64, context 8192",
             I.config_share(max_batch=64, max_seq=8192 + 64), 64, 8192, 4, args.decode_steps, 2,
             traffic_file="share_decode_traffic.json")
+    if "share-merge" in legs:
+        other["share_merge"] = run_merge_leg(torch, PB, I)
     if "mid-prefill" in legs:
         other["mid_prefill"] = run_prefill_leg(
             torch, PB, I, "Mid PT prefill 4 x 1024", I.config_mid(max_batch=4, max_seq=1024), 4, 1024, 1,
