@@ -118,16 +118,48 @@ __device__ __forceinline__ tile_coord map_tile(int id, int total, int tiles_m, i
 // ------------------------------------------------------------------------------------------------
 // `rs`, when given, holds one factor per row of the wavefront's tile (LDS, index = row - wave_m): the folded
 // RMSNorm scale that the QKV and SwiGLU epilogues apply to the accumulators of that row.
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+// Element v of an accumulator tile.  Kernels whose accumulators fill the accumulation registers (more than 128 per
+// lane) read them with an explicit v_accvgpr_read at the point of use: left to itself, the register allocator moves
+// all of them to vector registers at once when the K loop ends, spills what does not fit to scratch memory, and the
+// reloads, each waited for on its own, dominate the epilogue.
+template <bool FROM_ACC_REGS>
+__device__ __forceinline__ float acc_elem(const f32x16_t& tile, int v) {
+  if constexpr (FROM_ACC_REGS) {
+    float x;
+    asm("v_accvgpr_read_b32 %0, %1" : "=v"(x) : "a"(tile[v]));
+    return x;
+  } else {
+    return tile[v];
+  }
+}
+
 template <int MI, int NI, int EPI, bool STAGED, int STAGE_ELEMS>
 __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&acc)[MI][NI], bf16_t* stage, int b,
                                               int wave_m, int wave_n, int lane, const float* rs) {
   constexpr int TN = NI * 32;
+  constexpr bool AR = MI * NI * 16 > 128;   // accumulators live in the accumulation registers
   const int col_l = lane & 31;
   const int row_l = 4 * (lane >> 5);
   (void)stage;
   // factor of the row that register v of block mi holds
   auto row_scale = [&](int mi, int v) { return rs ? rs[mi * 32 + 8 * (v >> 2) + row_l + (v & 3)] : 1.0f; };
   (void)row_scale;
+  // the factors of all 16 registers of block mi at once (four 16-byte LDS reads, issued before the arithmetic
+  // that uses them: a read per register, each waited for on the spot, serialises the epilogue)
+  auto row_scales = [&](int mi, float (&rsv)[16]) {
+#pragma unroll
+    for (int vg = 0; vg < 4; ++vg) {
+      f32x4_t t = {1.f, 1.f, 1.f, 1.f};
+      if (rs) t = *(const f32x4_t*)(rs + mi * 32 + 8 * vg + row_l);
+      rsv[4 * vg + 0] = t.x;
+      rsv[4 * vg + 1] = t.y;
+      rsv[4 * vg + 2] = t.z;
+      rsv[4 * vg + 3] = t.w;
+    }
+  };
+  (void)row_scales;
   if constexpr (EPI == EPI_STORE_F32 || EPI == EPI_RESIDUAL) {
     float* out = g.out + b * g.out_bstride;
     const float* res = EPI == EPI_RESIDUAL ? g.res + b * g.res_bstride : nullptr;
@@ -138,35 +170,47 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
       // column) becomes row pieces of 4 floats, so the residual read-modify-write moves 16 bytes per
       // lane and whole 128-byte lines per row
       float* fst = (float*)stage;
-      constexpr int LPR = TN / 4, RPI = 64 / LPR, ITS = RCH / RPI;
-      typedef float f32x4_t __attribute__((ext_vector_type(4)));
-      static_for<MI * (32 / RCH)>([&](auto C_) {
-        constexpr int mi = decltype(C_)::value / (32 / RCH), rc = decltype(C_)::value % (32 / RCH);
+      constexpr int LPR = TN / 4, RPI = 64 / LPR, ITS = RCH / RPI, NCH = MI * (32 / RCH);
+      const int c4 = (lane % LPR) * 4, n = wave_n + c4;
+      // folded RMSNorm, producer side: bf16(h * gain) and the row's sum of squares over this wavefront's columns
+      const bool fold = EPI == EPI_RESIDUAL && g.nf_out != nullptr;
+      f32x4_t gain4 = {1.f, 1.f, 1.f, 1.f};
+      if (fold && n < g.N) gain4 = *(const f32x4_t*)(g.nf_gain + b * g.nf_gain_bstride + n);
+      // The residual rows of a chunk are loaded one whole chunk ahead of their use (a load from the residual
+      // stream takes thousands of clocks under load and nothing else in the workgroup can cover it), where the
+      // registers are there: kernels whose accumulators sit in the accumulation registers have the vector
+      // registers of the K loop's staging free by now.  The others load in batches of 8 rows.
+      constexpr bool PIPE = EPI == EPI_RESIDUAL && (AR || MI * NI * 16 + 8 * ITS <= 160);
+      constexpr int BATCH = PIPE ? ITS : (ITS < 8 ? ITS : 8);
+      f32x4_t rbuf[PIPE ? 2 : 1][BATCH];
+      (void)rbuf;
+      auto load_res = [&](auto C_, auto IT0_, f32x4_t (&dst)[BATCH]) {
+        constexpr int mi = decltype(C_)::value / (32 / RCH), row0 = (decltype(C_)::value % (32 / RCH)) * RCH;
+        constexpr int it0 = decltype(IT0_)::value;
+        static_for<BATCH>([&](auto I_) {
+          constexpr int i = decltype(I_)::value;
+          const int m = wave_m + mi * 32 + row0 + (it0 + i) * RPI + lane / LPR;
+          dst[i] = (m < g.M && n < g.N) ? *(const f32x4_t*)(res + (int64_t)m * g.ldo + n) : f32x4_t{0.f, 0.f, 0.f, 0.f};
+        });
+      };
+      if constexpr (PIPE) load_res(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, rbuf[0]);
+      static_for<NCH>([&](auto C_) {
+        constexpr int c = decltype(C_)::value;
+        constexpr int mi = c / (32 / RCH), rc = c % (32 / RCH);
         constexpr int row0 = rc * RCH;                 // first row of the chunk inside the 32-row block
+        if constexpr (PIPE && c + 1 < NCH) load_res(std::integral_constant<int, c + 1>{}, std::integral_constant<int, 0>{}, rbuf[(c + 1) & 1]);
         static_for<RCH / 2>([&](auto V_) {
           constexpr int v = (row0 / 8) * 4 + decltype(V_)::value;     // registers whose rows lie in the chunk
           const int row_in = 8 * (v >> 2) + row_l + (v & 3) - row0;
           static_for<NI>([&](auto NI_) {
             constexpr int ni = decltype(NI_)::value;
-            fst[row_in * FPITCH + ni * 32 + col_l] = acc[mi][ni][v];
+            fst[row_in * FPITCH + ni * 32 + col_l] = acc_elem<AR>(acc[mi][ni], v);
           });
         });
-        const int c4 = (lane % LPR) * 4, n = wave_n + c4;
-        constexpr int BATCH = ITS < 8 ? ITS : 8;
-        // folded RMSNorm, producer side: bf16(h * gain) and the row's sum of squares over this wavefront's columns
-        const bool fold = EPI == EPI_RESIDUAL && g.nf_out != nullptr;
-        f32x4_t gain4 = {1.f, 1.f, 1.f, 1.f};
-        if (fold && n < g.N) gain4 = *(const f32x4_t*)(g.nf_gain + b * g.nf_gain_bstride + n);
         static_for<ITS / BATCH>([&](auto B_) {
           constexpr int it0 = decltype(B_)::value * BATCH;
-          f32x4_t r4[BATCH];
-          if constexpr (EPI == EPI_RESIDUAL) {
-            static_for<BATCH>([&](auto I_) {
-              constexpr int i = decltype(I_)::value;
-              const int m = wave_m + mi * 32 + row0 + (it0 + i) * RPI + lane / LPR;
-              r4[i] = (m < g.M && n < g.N) ? *(const f32x4_t*)(res + (int64_t)m * g.ldo + n) : f32x4_t{0.f, 0.f, 0.f, 0.f};
-            });
-          }
+          f32x4_t (&r4)[BATCH] = rbuf[PIPE ? (c & 1) : 0];
+          if constexpr (EPI == EPI_RESIDUAL && !PIPE) load_res(C_, std::integral_constant<int, it0>{}, r4);
           static_for<BATCH>([&](auto I_) {
             constexpr int i = decltype(I_)::value;
             const int row_in = (it0 + i) * RPI + lane / LPR;
@@ -204,7 +248,7 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
               const int n = wave_n + ni * 32 + col_l;
               if (n < g.N) {
                 const int64_t idx = (int64_t)m * g.ldo + n;
-                float x = acc[mi][ni][v];
+                float x = acc_elem<AR>(acc[mi][ni], v);
                 if constexpr (EPI == EPI_RESIDUAL) x += res[idx];
                 out[idx] = x;
               }
@@ -222,13 +266,15 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
       static_assert(32 * PITCH <= STAGE_ELEMS, "staging patch too small");
       static_for<MI>([&](auto MI_) {
         constexpr int mi = decltype(MI_)::value;
+        float rsv[16];
+        row_scales(mi, rsv);
         static_for<16>([&](auto V_) {
           constexpr int v = decltype(V_)::value;
           const int row_in = 8 * (v >> 2) + row_l + (v & 3);
-          const float rsc = row_scale(mi, v);
+          const float rsc = rsv[v];
           static_for<NI / 2>([&](auto P_) {
             constexpr int pp = decltype(P_)::value;
-            stage[row_in * PITCH + 32 * pp + col_l] = f32_to_bf16(silu_fast(rsc * acc[mi][2 * pp][v]) * (rsc * acc[mi][2 * pp + 1][v]));
+            stage[row_in * PITCH + 32 * pp + col_l] = f32_to_bf16(silu_fast(rsc * acc_elem<AR>(acc[mi][2 * pp], v)) * (rsc * acc_elem<AR>(acc[mi][2 * pp + 1], v)));
           });
           if constexpr ((v & 3) == 3) __builtin_amdgcn_sched_barrier(0);   // bounds the scheduler's window (register pressure)
         });
@@ -252,7 +298,7 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
             for (int ni = 0; ni < NI; ni += 2) {
               const int j = ((wave_n + ni * 32) >> 1) + col_l;   // (phys/64)*32 + lane column
               const float rsc = row_scale(mi, v);
-              if (2 * j < g.N) o[(int64_t)m * ldo + j] = f32_to_bf16(silu_fast(rsc * acc[mi][ni][v]) * (rsc * acc[mi][ni + 1][v]));
+              if (2 * j < g.N) o[(int64_t)m * ldo + j] = f32_to_bf16(silu_fast(rsc * acc_elem<AR>(acc[mi][ni], v)) * (rsc * acc_elem<AR>(acc[mi][ni + 1], v)));
             }
           }
         }
@@ -275,101 +321,114 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
       if ((g.row_map ? g.row_blocks != 0 : (g.S & 31) == 0) && (g.pos0 & 7) == 0 && wave_n < g.N) {
         staged_done = true;
         const bool is_qk = wave_n < hq + hk, is_q = wave_n < hq;
-        // cos/sin of (position, column): the table is read once per 32-row block, for the lane's first row;
-        // the lane's other rows follow by rotating with the table's entries for 1 and 5 positions (its rows
-        // are r, r+1, r+2, r+3, r+8, ...).  All loads are issued before the first staging store: a load after
-        // a store through the staging pointer would wait for it, and the registers to keep one table entry
-        // per accumulator element in flight are not there.  With hd = 64 every low-half tile uses column
-        // col_l, with hd = 128 the two low-half tiles use col_l and col_l + 32.
-        float2 cs_base[MI][2], rot1[2], rot5[2];
-        if (is_qk) {
-          const float2* tab = (const float2*)g.rope + col_l;
-          rot1[0] = tab[half];
-          rot5[0] = tab[5 * half];
-          if (wide) { rot1[1] = tab[half + 32]; rot5[1] = tab[5 * half + 32]; }
+        // The head width as a constant: a wavefront owns whole heads (wave_n is a multiple of hd), so which
+        // 32-column tiles hold the low halves, and where their partners are, is then known at compile time.
+        auto staged_part = [&](auto WIDE_) {
+          constexpr bool W = decltype(WIDE_)::value;
+          constexpr int HD = W ? 128 : 64, HALF = HD / 2, NW = HALF / 32;   // NW low-half tiles per head
+          // cos/sin of (position, column): the table is read once per 32-row block, for the lane's first row;
+          // the lane's other rows follow by rotating with the table's entries for 1 and 5 positions (its rows
+          // are r, r+1, r+2, r+3, r+8, ...).  All loads are issued before the first staging store: a load after
+          // a store through the staging pointer would wait for it, and the registers to keep one table entry
+          // per accumulator element in flight are not there.  Low-half tile w of a head uses column col_l + 32 w.
+          float2 cs_base[MI][NW], rot1[NW], rot5[NW];
+          if (is_qk) {
+            const float2* tab = (const float2*)g.rope + col_l;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+              rot1[w] = tab[HALF + 32 * w];
+              rot5[w] = tab[5 * HALF + 32 * w];
+            }
+            static_for<MI>([&](auto MI_) {
+              constexpr int mi = decltype(MI_)::value;
+              const int mrow0 = min(wave_m + mi * 32, g.M - 32);
+              const int pos0b = gemm_row_pos(g, mrow0).pos;
+              const float2* rp = tab + (int64_t)(pos0b + row_l) * HALF;
+#pragma unroll
+              for (int w = 0; w < NW; ++w) cs_base[mi][w] = rp[32 * w];
+            });
+          }
           static_for<MI>([&](auto MI_) {
             constexpr int mi = decltype(MI_)::value;
-            const int mrow0 = min(wave_m + mi * 32, g.M - 32);
-            const int pos0b = gemm_row_pos(g, mrow0).pos;
-            const float2* rp = tab + (int64_t)(pos0b + row_l) * half;
-            cs_base[mi][0] = rp[0];
-            if (wide) cs_base[mi][1] = rp[32];
-          });
-        }
-        static_for<MI>([&](auto MI_) {
-          constexpr int mi = decltype(MI_)::value;
-          const int mrow0 = wave_m + mi * 32;           // first row of the block
-          if (mrow0 < g.M) {
-            const pt_rowpos rp0 = gemm_row_pos(g, mrow0);
-            const int seq = rp0.seq, pos0b = rp0.pos;
-            if (is_qk) {
-              float2 cs_cur[2] = {cs_base[mi][0], wide ? cs_base[mi][1] : cs_base[mi][0]};
-              static_for<16>([&](auto V_) {
-                constexpr int v = decltype(V_)::value;
-                const int row_in = 8 * (v >> 2) + row_l + (v & 3);
-                const float rsc = row_scale(mi, v);
-                if constexpr (v > 0) {
+            const int mrow0 = wave_m + mi * 32;           // first row of the block
+            if (mrow0 < g.M) {
+              const pt_rowpos rp0 = gemm_row_pos(g, mrow0);
+              const int seq = rp0.seq, pos0b = rp0.pos;
+              float rsv[16];
+              row_scales(mi, rsv);
+              if (is_qk) {
+                float2 cs_cur[NW];
 #pragma unroll
-                  for (int w = 0; w < 2; ++w) {
-                    if (w == 1 && !wide) break;
-                    const float2 r = (v & 3) == 0 ? rot5[w] : rot1[w];
-                    const float2 c = cs_cur[w];
-                    cs_cur[w].x = c.x * r.x - c.y * r.y;
-                    cs_cur[w].y = c.y * r.x + c.x * r.y;
+                for (int w = 0; w < NW; ++w) cs_cur[w] = cs_base[mi][w];
+                bf16_t* st = stage + row_l * QPITCH + col_l;
+                static_for<16>([&](auto V_) {
+                  constexpr int v = decltype(V_)::value;
+                  constexpr int row_c = 8 * (v >> 2) + (v & 3);   // row inside the block, less row_l
+                  const float rsc = rsv[v];
+                  if constexpr (v > 0) {
+#pragma unroll
+                    for (int w = 0; w < NW; ++w) {
+                      const float2 r = (v & 3) == 0 ? rot5[w] : rot1[w];
+                      const float2 c = cs_cur[w];
+                      cs_cur[w].x = c.x * r.x - c.y * r.y;
+                      cs_cur[w].y = c.y * r.x + c.x * r.y;
+                    }
                   }
-                }
-                static_for<NI>([&](auto NI_) {
-                  constexpr int ni = decltype(NI_)::value;
-                  constexpr int p1 = ni + 1 < NI ? ni + 1 : ni, p2 = ni + 2 < NI ? ni + 2 : ni;
-                  const int jb = (wave_n + ni * 32) & (hd - 1);   // wave-uniform
-                  if (jb < half) {
-                    const float2 cs = jb == 0 ? cs_cur[0] : cs_cur[1];
-                    const float lo = rsc * acc[mi][ni][v];
-                    const float hi = rsc * (wide ? acc[mi][p2][v] : acc[mi][p1][v]);
-                    stage[row_in * QPITCH + ni * 32 + col_l] = f32_to_bf16(lo * cs.x - hi * cs.y);
-                    stage[row_in * QPITCH + ni * 32 + col_l + half] = f32_to_bf16(hi * cs.x + lo * cs.y);
-                  }
+                  static_for<NI>([&](auto NI_) {
+                    constexpr int ni = decltype(NI_)::value;
+                    constexpr int jb = (ni * 32) & (HD - 1);
+                    constexpr int pn = ni + NW < NI ? ni + NW : ni;   // the tile with the partner columns
+                    if constexpr (jb < HALF) {
+                      const float2 cs = cs_cur[jb / 32];
+                      const float lo = rsc * acc_elem<AR>(acc[mi][ni], v);
+                      const float hi = rsc * acc_elem<AR>(acc[mi][pn], v);
+                      st[row_c * QPITCH + ni * 32] = f32_to_bf16(lo * cs.x - hi * cs.y);
+                      st[row_c * QPITCH + ni * 32 + HALF] = f32_to_bf16(hi * cs.x + lo * cs.y);
+                    }
+                  });
                 });
-              });
-              constexpr int LPR = TN / 8, RPI = 64 / LPR;
-              const int c8 = (lane % LPR) * 8;
-              const int c = (is_q ? wave_n : wave_n - hq) + c8;       // column inside the q or k section
-              const int head = c >> hd_sh, j = c & (hd - 1);
-              static_for<32 / RPI>([&](auto IT_) {
-                constexpr int it = decltype(IT_)::value;
-                const int row_in = it * RPI + lane / LPR;
-                const u32x4_t val = *(const u32x4_t*)(stage + row_in * QPITCH + c8);
-                if (is_q) {
-                  *(u32x4_t*)((bf16_t*)g.olp + b * g.olp_bstride + (int64_t)(mrow0 + row_in) * hq + c) = val;
-                } else {
-                  const int64_t hidx = b * g.kv_bstride + seq * g.kv_seq_stride + head;
-                  *(u32x4_t*)((bf16_t*)g.kc + hidx * g.kv_head_elems + (int64_t)(pos0b + row_in) * hd + j) = val;
-                }
-              });
-            } else {
-              static_for<4>([&](auto VG_) {
-                constexpr int vg = decltype(VG_)::value;
-                static_for<NI>([&](auto NI_) {
-                  constexpr int ni = decltype(NI_)::value;
-                  uint2 pk;
-                  pk.x = pack_bf16x2(row_scale(mi, vg * 4 + 0) * acc[mi][ni][vg * 4 + 0], row_scale(mi, vg * 4 + 1) * acc[mi][ni][vg * 4 + 1]);
-                  pk.y = pack_bf16x2(row_scale(mi, vg * 4 + 2) * acc[mi][ni][vg * 4 + 2], row_scale(mi, vg * 4 + 3) * acc[mi][ni][vg * 4 + 3]);
-                  *(uint2*)(stage + (ni * 32 + col_l) * VPITCH + 8 * vg + row_l) = pk;
+                constexpr int LPR = TN / 8, RPI = 64 / LPR;
+                const int c8 = (lane % LPR) * 8;
+                const int c = (is_q ? wave_n : wave_n - hq) + c8;       // column inside the q or k section
+                const int head = c / HD, j = c % HD;
+                bf16_t* dst = is_q ? (bf16_t*)g.olp + b * g.olp_bstride + (int64_t)(mrow0 + lane / LPR) * hq + c
+                                   : (bf16_t*)g.kc + (b * g.kv_bstride + seq * g.kv_seq_stride + head) * g.kv_head_elems +
+                                         (int64_t)(pos0b + lane / LPR) * HD + j;
+                const int64_t dpitch = is_q ? hq : HD;                  // elements per row at the destination
+                const bf16_t* src = stage + (lane / LPR) * QPITCH + c8;
+                static_for<32 / RPI>([&](auto IT_) {
+                  constexpr int it = decltype(IT_)::value;
+                  *(u32x4_t*)(dst + it * RPI * dpitch) = *(const u32x4_t*)(src + it * RPI * QPITCH);
                 });
-              });
-              const int p8 = (lane & 3) * 8;
-              static_for<TN / 16>([&](auto IT_) {
-                constexpr int it = decltype(IT_)::value;
-                const int col = it * 16 + (lane >> 2);
-                const u32x4_t val = *(const u32x4_t*)(stage + col * VPITCH + p8);
-                const int c = wave_n - hq - hk + col;
-                const int head = c >> hd_sh, j = c & (hd - 1);
-                const int64_t hidx = b * g.kv_bstride + seq * g.kv_seq_stride + head;
-                *(u32x4_t*)((bf16_t*)g.vc + hidx * ((int64_t)hd * g.s_pad) + (int64_t)j * g.s_pad + pos0b + p8) = val;
-              });
+              } else {
+                static_for<4>([&](auto VG_) {
+                  constexpr int vg = decltype(VG_)::value;
+                  static_for<NI>([&](auto NI_) {
+                    constexpr int ni = decltype(NI_)::value;
+                    uint2 pk;
+                    pk.x = pack_bf16x2(rsv[vg * 4 + 0] * acc_elem<AR>(acc[mi][ni], vg * 4 + 0), rsv[vg * 4 + 1] * acc_elem<AR>(acc[mi][ni], vg * 4 + 1));
+                    pk.y = pack_bf16x2(rsv[vg * 4 + 2] * acc_elem<AR>(acc[mi][ni], vg * 4 + 2), rsv[vg * 4 + 3] * acc_elem<AR>(acc[mi][ni], vg * 4 + 3));
+                    *(uint2*)(stage + (ni * 32 + col_l) * VPITCH + 8 * vg + row_l) = pk;
+                  });
+                });
+                const int p8 = (lane & 3) * 8;
+                // a wavefront's columns lie in whole heads: head and head-dim index of column (lane >> 2)
+                const int c0 = wave_n - hq - hk + (lane >> 2);
+                const int head0 = c0 / HD, j0 = c0 % HD;
+                bf16_t* dst = (bf16_t*)g.vc + (b * g.kv_bstride + seq * g.kv_seq_stride + head0) * ((int64_t)HD * g.s_pad) +
+                              (int64_t)j0 * g.s_pad + pos0b + p8;
+                const bf16_t* src = stage + (lane >> 2) * VPITCH + p8;
+                static_for<TN / 16>([&](auto IT_) {
+                  constexpr int it = decltype(IT_)::value;
+                  // column it*16 further on: the head-dim rows of V^T are s_pad apart and heads follow one another
+                  *(u32x4_t*)(dst + (int64_t)(it * 16) * g.s_pad) = *(const u32x4_t*)(src + it * 16 * VPITCH);
+                });
+              }
             }
-          }
-        });
+          });
+        };
+        if (wide) staged_part(std::true_type{});
+        else staged_part(std::false_type{});
       }
     }
     if (!staged_done)
@@ -404,8 +463,8 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
                   else { const pt_rowpos rpm = gemm_row_pos(g, m); seq = rpm.seq; pos = rpm.pos; }
                   const float2 cs = ((const float2*)g.rope)[(int64_t)pos * half + j];
                   const float rsc = row_scale(mi, vg * 4 + r);
-                  const float lo = rsc * acc[mi][ni][vg * 4 + r];
-                  const float hi = rsc * (wide ? acc[mi][p2][vg * 4 + r] : acc[mi][p1][vg * 4 + r]);
+                  const float lo = rsc * acc_elem<AR>(acc[mi][ni], vg * 4 + r);
+                  const float hi = rsc * (wide ? acc_elem<AR>(acc[mi][p2], vg * 4 + r) : acc_elem<AR>(acc[mi][p1], vg * 4 + r));
                   const bf16_t rlo = f32_to_bf16(lo * cs.x - hi * cs.y);
                   const bf16_t rhi = f32_to_bf16(hi * cs.x + lo * cs.y);
                   if (is_q) {
@@ -429,8 +488,8 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
               const int64_t hidx = b * g.kv_bstride + seq4 * g.kv_seq_stride + head;
               bf16_t* v = (bf16_t*)g.vc + hidx * ((int64_t)hd * g.s_pad) + (int64_t)j * g.s_pad + pos4;
               uint2 pk;
-              pk.x = pack_bf16x2(row_scale(mi, vg * 4 + 0) * acc[mi][ni][vg * 4 + 0], row_scale(mi, vg * 4 + 1) * acc[mi][ni][vg * 4 + 1]);
-              pk.y = pack_bf16x2(row_scale(mi, vg * 4 + 2) * acc[mi][ni][vg * 4 + 2], row_scale(mi, vg * 4 + 3) * acc[mi][ni][vg * 4 + 3]);
+              pk.x = pack_bf16x2(row_scale(mi, vg * 4 + 0) * acc_elem<AR>(acc[mi][ni], vg * 4 + 0), row_scale(mi, vg * 4 + 1) * acc_elem<AR>(acc[mi][ni], vg * 4 + 1));
+              pk.y = pack_bf16x2(row_scale(mi, vg * 4 + 2) * acc_elem<AR>(acc[mi][ni], vg * 4 + 2), row_scale(mi, vg * 4 + 3) * acc_elem<AR>(acc[mi][ni], vg * 4 + 3));
               *(uint2*)v = pk;
             } else {
               static_for<4>([&](auto R_) {
@@ -440,7 +499,7 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
                   const pt_rowpos rpm = gemm_row_pos(g, m);
                   const int seq = rpm.seq, pos = rpm.pos;
                   const int64_t hidx = b * g.kv_bstride + seq * g.kv_seq_stride + head;
-                  ((bf16_t*)g.vc)[hidx * ((int64_t)hd * g.s_pad) + (int64_t)j * g.s_pad + pos] = f32_to_bf16(row_scale(mi, vg * 4 + r) * acc[mi][ni][vg * 4 + r]);
+                  ((bf16_t*)g.vc)[hidx * ((int64_t)hd * g.s_pad) + (int64_t)j * g.s_pad + pos] = f32_to_bf16(row_scale(mi, vg * 4 + r) * acc_elem<AR>(acc[mi][ni], vg * 4 + r));
                 }
               });
             }
@@ -470,7 +529,10 @@ gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
   const tile_coord tc = map_tile(blockIdx.x, gridDim.x, tiles_m, tiles_n);
-  const int m0 = tc.tm * BM, n0 = tc.tn * BN, b = tc.b;
+  // the tile's coordinates are the same for every lane: kept in scalar registers (the divisions of the tile walk
+  // leave them in vector registers, where their 64-bit products crowd the K loop and get spilled around it)
+  const int m0 = __builtin_amdgcn_readfirstlane(tc.tm) * BM, n0 = __builtin_amdgcn_readfirstlane(tc.tn) * BN,
+            b = __builtin_amdgcn_readfirstlane(tc.b);
   // grouped GEMM: the weight matrix of this tile's rows; tiles that start in a block without rows have nothing to do
   int group = 0;
   if (g.blk_group) {
@@ -480,11 +542,11 @@ gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
 
   // folded RMSNorm, consumer side: one factor per tile row (1/rms of the row, from pt_launch_row_inv_rms).  The
   // load is issued here and parked in LDS only after the K loop, so nothing waits for it.
-  __shared__ float rs_inv[BM];
+  __shared__ __attribute__((aligned(16))) float rs_inv[BM];
   const bool has_rs = (EPI == EPI_QKV || EPI == EPI_SWIGLU) && g.rs_inv != nullptr;
   static_assert(BM <= NT, "one factor per thread");
   float rs_mine = 1.0f;
-  if (has_rs && tid < BM) rs_mine = g.rs_inv[b * g.rs_bstride + min(m0 + tid, g.M - 1)];
+  if (has_rs) rs_mine = g.rs_inv[b * g.rs_bstride + min(m0 + min(tid, BM - 1), g.M - 1)];   // wave-uniform branch
 
   // global -> register staging: chunk id = tid + i*NT; row = id/CPR, 16-byte chunk = id%CPR.
   // Rows of one thread are NT/CPR apart, a multiple of 16, so they share the swizzle and the LDS
@@ -546,10 +608,14 @@ gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
   for (int i = 0; i < A_CH; ++i) *(u32x4_t*)(As + st_dst + i * ST_STRIDE) = a_reg[0][i];
 #pragma unroll
   for (int i = 0; i < B_CH; ++i) *(u32x4_t*)(Bs + st_dst + i * ST_STRIDE) = w_reg[0][i];
+  // The largest tile leaves the loads of K step 2 to its first iteration, between the MFMAs.
+  constexpr bool LATE2 = BM * BN >= 256 * 256;
+  if constexpr (!LATE2) {
 #pragma unroll
-  for (int i = 0; i < A_CH; ++i) load_a(0, i, min(2, KT - 1));
+    for (int i = 0; i < A_CH; ++i) load_a(0, i, min(2, KT - 1));
 #pragma unroll
-  for (int i = 0; i < B_CH; ++i) load_w(0, i, min(2, KT - 1));
+    for (int i = 0; i < B_CH; ++i) load_w(0, i, min(2, KT - 1));
+  }
   __syncthreads();
   bf16x8_t af[2][MI], bfr[2][NI];
 #pragma unroll
@@ -565,8 +631,13 @@ gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
 
   f32x16_t acc[MI][NI];
 
-  auto iteration = [&](auto PAR, int kt) {
+  // FIRST: the iteration of K step 0, which also loads K step 2 into the staging set that the pipeline fill has
+  // just parked (a wavefront can keep 63 loads in flight: issued in front of the loop, those loads would hold
+  // the first MFMA back until the loads of K step 1 have returned).
+  auto iteration = [&](auto PAR, auto FIRST_, int kt) {
     constexpr int cur = decltype(PAR)::value;          // LDS buffer being multiplied
+    constexpr bool FIRST = decltype(FIRST_)::value;
+    constexpr int PER = FIRST ? 3 : 2;                  // memory instructions per staging chunk
     constexpr int wset = cur ^ 1;                       // staging set stored, then reloaded
     const bf16_t* Ac = As + cur * BM * BK;
     const bf16_t* Bc = Bs + cur * BN * BK;
@@ -576,7 +647,7 @@ gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
     static_for<SS>([&](auto KK) {
       constexpr int kk = decltype(KK)::value;
       constexpr int fb = (kk + 1) & 1;                  // fragment buffer being filled
-      constexpr int R = kk < NS ? FR + 2 * EXS : FR;   // memory instructions of this sub-step
+      constexpr int R = kk < NS ? FR + PER * EXS : FR;   // memory instructions of this sub-step
       if constexpr (kk == SS - 1) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
       static_for<NM>([&](auto J) {
         constexpr int j = decltype(J)::value;
@@ -592,9 +663,13 @@ gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
             const bf16_t* src = kk == SS - 1 ? Bn + b_fr[0] : Bc + b_fr[(kk + 1) % SS];
             bfr[fb][r - MI] = *(const bf16x8_t*)(src + (r - MI) * 32 * BK);
           } else {
-            constexpr int e = kk * EXS + (r - FR) / 2;   // staging chunk: parked, then refilled right away
+            constexpr int e = kk * EXS + (r - FR) / PER;   // staging chunk: parked, then refilled right away
+            constexpr int what = (r - FR) % PER + (FIRST ? 0 : 1);   // 0: load of K step 2, 1: park, 2: refill
             if constexpr (e < EX && kk < NS) {
-              if constexpr ((r - FR) % 2 == 0) {
+              if constexpr (what == 0) {
+                if constexpr (e < A_CH) load_a(cur, e, min(2, KT - 1));
+                else load_w(cur, e - A_CH, min(2, KT - 1));
+              } else if constexpr (what == 1) {
                 if constexpr (e < A_CH) *(u32x4_t*)(An + st_dst + e * ST_STRIDE) = a_reg[wset][e];
                 else *(u32x4_t*)(Bn + st_dst + (e - A_CH) * ST_STRIDE) = w_reg[wset][e - A_CH];
               } else {
@@ -615,9 +690,13 @@ gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
     for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
-  for (int kt = 0; kt < KT; kt += 2) {
-    iteration(std::integral_constant<int, 0>{}, kt);
-    iteration(std::integral_constant<int, 1>{}, kt + 1);
+  if constexpr (LATE2) {
+    iteration(std::integral_constant<int, 0>{}, std::true_type{}, 0);
+    iteration(std::integral_constant<int, 1>{}, std::false_type{}, 1);
+  }
+  for (int kt = LATE2 ? 2 : 0; kt < KT; kt += 2) {
+    iteration(std::integral_constant<int, 0>{}, std::false_type{}, kt);
+    iteration(std::integral_constant<int, 1>{}, std::false_type{}, kt + 1);
   }
   if (has_rs && tid < BM) rs_inv[tid] = rs_mine;
   __syncthreads();   // LDS is free for the staged epilogues
@@ -658,7 +737,10 @@ gemm_dl_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
   const tile_coord tc = map_tile(blockIdx.x, gridDim.x, tiles_m, tiles_n);
-  const int m0 = tc.tm * BM, n0 = tc.tn * BN, b = tc.b;
+  // the tile's coordinates are the same for every lane: kept in scalar registers (the divisions of the tile walk
+  // leave them in vector registers, where their 64-bit products crowd the K loop and get spilled around it)
+  const int m0 = __builtin_amdgcn_readfirstlane(tc.tm) * BM, n0 = __builtin_amdgcn_readfirstlane(tc.tn) * BN,
+            b = __builtin_amdgcn_readfirstlane(tc.b);
   const int KT = g.K / BK;   // multiple of 4
   int group = 0;             // grouped GEMM, as in gemm_mfma_kernel
   if (g.blk_group) {
@@ -668,11 +750,11 @@ gemm_dl_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
 
   // folded RMSNorm, consumer side: one factor per tile row (1/rms of the row, from pt_launch_row_inv_rms).  The
   // load is issued here and parked in LDS only after the K loop, so nothing waits for it.
-  __shared__ float rs_inv[BM];
+  __shared__ __attribute__((aligned(16))) float rs_inv[BM];
   const bool has_rs = (EPI == EPI_QKV || EPI == EPI_SWIGLU) && g.rs_inv != nullptr;
   static_assert(BM <= (NW * 64), "one factor per thread");
   float rs_mine = 1.0f;
-  if (has_rs && tid < BM) rs_mine = g.rs_inv[b * g.rs_bstride + min(m0 + tid, g.M - 1)];
+  if (has_rs) rs_mine = g.rs_inv[b * g.rs_bstride + min(m0 + min(tid, BM - 1), g.M - 1)];   // wave-uniform branch
 
   // direct loads: group grp covers tile rows grp*16 .. +15; this lane fetches row L/4, logical chunk (L%4)^swz
   const int rr = lane >> 2, pc = lane & 3;

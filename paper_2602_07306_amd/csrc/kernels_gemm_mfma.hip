@@ -54,15 +54,16 @@ static int choose_cfg(const pt_gemm_args& g) {
   if ((g.epi == EPI_STORE_F32 || g.epi == EPI_RESIDUAL) &&
       ((g.ldo & 3) || (g.N & 3) || (g.out_bstride & 3) || (g.res_bstride & 3) || (((uintptr_t)g.out | (uintptr_t)g.res) & 15))) return -1;
   if (g.epi == EPI_SWIGLU && ((g.olp_bstride & 7) || ((uintptr_t)g.olp & 15))) return -1;
-  // measured: the direct-to-LDS variant (10) wins for the QKV epilogue and, at short K, for SwiGLU
-  static const int big[] = {0, 4, 2, -1}, big_qkv[] = {10, 8, 0, 4, 2, -1}, big_dl[] = {10, 0, 4, 2, -1}, mid[] = {4, 2, -1}, m64[] = {3, 6, -1}, m32[] = {5, 7, -1};
+  // measured at the Large, one-GPU-share and Mid shapes: the register-staged 256 x 256 tile (0) is the fastest for
+  // every epilogue; the direct-to-LDS variants (10, 11) stay reachable through the tuning override
+  static const int big[] = {0, 4, 2, -1}, big_qkv[] = {0, 10, 8, 4, 2, -1}, mid[] = {4, 2, -1}, m64[] = {3, 6, -1}, m32[] = {5, 7, -1};
   const int* cand;
   // grouped GEMM: the tile height follows the rows of an average group, not the padded total
   const int m_sel = g.blk_group && g.grp_rows > 0 && g.grp_rows < g.M ? g.grp_rows : g.M;
   if (m_sel <= 32) cand = m32;
   else if (m_sel <= 64) cand = m64;
   else if (m_sel <= 128 || (int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256) * g.batch < 200) cand = mid;
-  else cand = g.epi == EPI_QKV ? big_qkv : (g.epi == EPI_SWIGLU && g.K <= 1024) ? big_dl : big;
+  else cand = g.epi == EPI_QKV ? big_qkv : big;
   if (pt_tune_gemm_cfg >= 0 && pt_tune_gemm_cfg < GM_NCFG) return cfg_fits(g, pt_tune_gemm_cfg) ? pt_tune_gemm_cfg : -1;
   for (; *cand >= 0; ++cand)
     if (cfg_fits(g, *cand)) return *cand;
