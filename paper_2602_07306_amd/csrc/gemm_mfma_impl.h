@@ -182,60 +182,88 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
       // registers of the K loop's staging free by now.  The others load in batches of 8 rows.
       constexpr bool PIPE = EPI == EPI_RESIDUAL && (AR || MI * NI * 16 + 8 * ITS <= 160);
       constexpr int BATCH = PIPE ? ITS : (ITS < 8 ? ITS : 8);
-      f32x4_t rbuf[PIPE ? 2 : 1][BATCH];
-      (void)rbuf;
-      auto load_res = [&](auto C_, auto IT0_, f32x4_t (&dst)[BATCH]) {
-        constexpr int mi = decltype(C_)::value / (32 / RCH), row0 = (decltype(C_)::value % (32 / RCH)) * RCH;
-        constexpr int it0 = decltype(IT0_)::value;
-        static_for<BATCH>([&](auto I_) {
-          constexpr int i = decltype(I_)::value;
-          const int m = wave_m + mi * 32 + row0 + (it0 + i) * RPI + lane / LPR;
-          dst[i] = (m < g.M && n < g.N) ? *(const f32x4_t*)(res + (int64_t)m * g.ldo + n) : f32x4_t{0.f, 0.f, 0.f, 0.f};
-        });
-      };
-      if constexpr (PIPE) load_res(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, rbuf[0]);
-      static_for<NCH>([&](auto C_) {
-        constexpr int c = decltype(C_)::value;
-        constexpr int mi = c / (32 / RCH), rc = c % (32 / RCH);
-        constexpr int row0 = rc * RCH;                 // first row of the chunk inside the 32-row block
-        if constexpr (PIPE && c + 1 < NCH) load_res(std::integral_constant<int, c + 1>{}, std::integral_constant<int, 0>{}, rbuf[(c + 1) & 1]);
-        static_for<RCH / 2>([&](auto V_) {
-          constexpr int v = (row0 / 8) * 4 + decltype(V_)::value;     // registers whose rows lie in the chunk
-          const int row_in = 8 * (v >> 2) + row_l + (v & 3) - row0;
-          static_for<NI>([&](auto NI_) {
-            constexpr int ni = decltype(NI_)::value;
-            fst[row_in * FPITCH + ni * 32 + col_l] = acc_elem<AR>(acc[mi][ni], v);
-          });
-        });
-        static_for<ITS / BATCH>([&](auto B_) {
-          constexpr int it0 = decltype(B_)::value * BATCH;
-          f32x4_t (&r4)[BATCH] = rbuf[PIPE ? (c & 1) : 0];
-          if constexpr (EPI == EPI_RESIDUAL && !PIPE) load_res(C_, std::integral_constant<int, it0>{}, r4);
+      // A wavefront whose tile lies inside the matrix (FULL) runs without the per-row bounds tests: they split the
+      // code into small blocks, each of which waits for its own LDS read before it stores.
+      auto run = [&](auto FULL_, auto FOLD_) {
+        constexpr bool FULL = decltype(FULL_)::value, FOLD = decltype(FOLD_)::value;
+        const int row_t = lane / LPR;                                         // the lane's row inside an iteration
+        const int64_t lane_off = (int64_t)(wave_m + row_t) * g.ldo + n;     // element offset of the lane's first piece
+        f32x4_t rbuf[PIPE ? 2 : 1][BATCH];
+        (void)rbuf;
+        auto load_res = [&](auto C_, auto IT0_, f32x4_t (&dst)[BATCH]) {
+          constexpr int mi = decltype(C_)::value / (32 / RCH), row0 = (decltype(C_)::value % (32 / RCH)) * RCH;
+          constexpr int it0 = decltype(IT0_)::value;
           static_for<BATCH>([&](auto I_) {
             constexpr int i = decltype(I_)::value;
-            const int row_in = (it0 + i) * RPI + lane / LPR;
-            const int m = wave_m + mi * 32 + row0 + row_in;
-            f32x4_t x = *(const f32x4_t*)(fst + row_in * FPITCH + c4);
-            if constexpr (EPI == EPI_RESIDUAL) x += r4[i];
-            if (m < g.M && n < g.N) *(f32x4_t*)(out + (int64_t)m * g.ldo + n) = x;
-            if constexpr (EPI == EPI_RESIDUAL) {
-              if (fold) {
-                float ss = n < g.N ? x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w : 0.f;
-                ss = group_sum_last_lane<LPR>(ss);
-                if (m < g.M) {
-                  if (n < g.N) {
-                    uint2 pk;
-                    pk.x = pack_bf16x2(x.x * gain4.x, x.y * gain4.y);
-                    pk.y = pack_bf16x2(x.z * gain4.z, x.w * gain4.w);
-                    *(uint2*)((bf16_t*)g.nf_out + b * g.nf_out_bstride + (int64_t)m * g.N + n) = pk;
-                  }
-                  if (lane % LPR == LPR - 1) g.nf_ss[b * g.nf_ss_bstride + (int64_t)m * g.nf_parts + wave_n / TN] = ss;
+            constexpr int r = mi * 32 + row0 + (it0 + i) * RPI;           // row of the iteration inside the tile
+            dst[i] = (FULL || (wave_m + r + row_t < g.M && n < g.N)) ? *(const f32x4_t*)(res + lane_off + (int64_t)r * g.ldo)
+                                                                     : f32x4_t{0.f, 0.f, 0.f, 0.f};
+          });
+        };
+        if constexpr (PIPE) load_res(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, rbuf[0]);
+        static_for<NCH>([&](auto C_) {
+          constexpr int c = decltype(C_)::value;
+          constexpr int mi = c / (32 / RCH), rc = c % (32 / RCH);
+          constexpr int row0 = rc * RCH;                 // first row of the chunk inside the 32-row block
+          if constexpr (PIPE && c + 1 < NCH) load_res(std::integral_constant<int, c + 1>{}, std::integral_constant<int, 0>{}, rbuf[(c + 1) & 1]);
+          static_for<RCH / 2>([&](auto V_) {
+            constexpr int v = (row0 / 8) * 4 + decltype(V_)::value;     // registers whose rows lie in the chunk
+            const int row_in = 8 * (v >> 2) + row_l + (v & 3) - row0;
+            static_for<NI>([&](auto NI_) {
+              constexpr int ni = decltype(NI_)::value;
+              fst[row_in * FPITCH + ni * 32 + col_l] = acc_elem<AR>(acc[mi][ni], v);
+            });
+          });
+          static_for<ITS / BATCH>([&](auto B_) {
+            constexpr int it0 = decltype(B_)::value * BATCH;
+            f32x4_t (&r4)[BATCH] = rbuf[PIPE ? (c & 1) : 0];
+            if constexpr (EPI == EPI_RESIDUAL && !PIPE) load_res(C_, std::integral_constant<int, it0>{}, r4);
+            f32x4_t x[BATCH];
+            float ssv[FOLD ? BATCH : 1];
+            (void)ssv;
+            static_for<BATCH>([&](auto I_) {
+              constexpr int i = decltype(I_)::value;
+              x[i] = *(const f32x4_t*)(fst + ((it0 + i) * RPI + row_t) * FPITCH + c4);
+            });
+            static_for<BATCH>([&](auto I_) {
+              constexpr int i = decltype(I_)::value;
+              constexpr int r = mi * 32 + row0 + (it0 + i) * RPI;
+              const int m = wave_m + r + row_t;
+              const bool ok_m = FULL || m < g.M, ok_n = FULL || n < g.N;
+              if constexpr (EPI == EPI_RESIDUAL) x[i] += r4[i];
+              if (ok_m && ok_n) *(f32x4_t*)(out + lane_off + (int64_t)r * g.ldo) = x[i];
+              if constexpr (FOLD) {
+                const float ss = ok_n ? x[i].x * x[i].x + x[i].y * x[i].y + x[i].z * x[i].z + x[i].w * x[i].w : 0.f;
+                ssv[i] = group_sum_last_lane<LPR>(ss);
+                if (ok_m && ok_n) {
+                  uint2 pk;
+                  pk.x = pack_bf16x2(x[i].x * gain4.x, x[i].y * gain4.y);
+                  pk.y = pack_bf16x2(x[i].z * gain4.z, x[i].w * gain4.w);
+                  *(uint2*)((bf16_t*)g.nf_out + b * g.nf_out_bstride + (int64_t)m * g.N + n) = pk;
                 }
+              }
+            });
+            // the rows' sums of squares, from the last lane of every row group: one divergent branch per batch
+            if constexpr (FOLD) {
+              if (lane % LPR == LPR - 1) {
+                float* ssp = g.nf_ss + b * g.nf_ss_bstride + (int64_t)(wave_m + row_t) * g.nf_parts + wave_n / TN;
+                static_for<BATCH>([&](auto I_) {
+                  constexpr int i = decltype(I_)::value;
+                  constexpr int r = mi * 32 + row0 + (it0 + i) * RPI;
+                  if (FULL || wave_m + r + row_t < g.M) ssp[(int64_t)r * g.nf_parts] = ssv[i];
+                });
               }
             }
           });
         });
-      });
+      };
+      const bool full = wave_m + MI * 32 <= g.M && wave_n + TN <= g.N;
+      if constexpr (EPI == EPI_RESIDUAL) {
+        if (fold) { if (full) run(std::true_type{}, std::true_type{}); else run(std::false_type{}, std::true_type{}); }
+        else { if (full) run(std::true_type{}, std::false_type{}); else run(std::false_type{}, std::false_type{}); }
+      } else {
+        if (full) run(std::true_type{}, std::false_type{}); else run(std::false_type{}, std::false_type{});
+      }
     } else {
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi)
@@ -264,6 +292,7 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
       // row pieces and leave as full 128-byte lines
       constexpr int OC = TN / 2, PITCH = OC + 8, LPR = OC / 8, RPI = 64 / LPR;
       static_assert(32 * PITCH <= STAGE_ELEMS, "staging patch too small");
+      const bool full = wave_m + MI * 32 <= g.M && wave_n + TN <= g.N;
       static_for<MI>([&](auto MI_) {
         constexpr int mi = decltype(MI_)::value;
         float rsv[16];
@@ -278,14 +307,27 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
           });
           if constexpr ((v & 3) == 3) __builtin_amdgcn_sched_barrier(0);   // bounds the scheduler's window (register pressure)
         });
+        // a wavefront whose tile lies inside the matrix stores without bounds tests, all LDS reads first
+        const int row_t = lane / LPR, chunk = lane % LPR;
+        const int j = (wave_n >> 1) + chunk * 8;
+        const bf16_t* src = stage + row_t * PITCH + chunk * 8;
+        bf16_t* dst = o + (int64_t)(wave_m + mi * 32 + row_t) * ldo + j;
+        u32x4_t val[32 / RPI];
         static_for<32 / RPI>([&](auto IT_) {
           constexpr int it = decltype(IT_)::value;
-          const int row_in = it * RPI + lane / LPR, chunk = lane % LPR;
-          const u32x4_t val = *(const u32x4_t*)(stage + row_in * PITCH + chunk * 8);
-          const int m = wave_m + mi * 32 + row_in;
-          const int j = (wave_n >> 1) + chunk * 8;
-          if (m < g.M && 2 * j < g.N) *(u32x4_t*)(o + (int64_t)m * ldo + j) = val;
+          val[it] = *(const u32x4_t*)(src + it * RPI * PITCH);
         });
+        if (full) {
+          static_for<32 / RPI>([&](auto IT_) {
+            constexpr int it = decltype(IT_)::value;
+            *(u32x4_t*)(dst + (int64_t)(it * RPI) * ldo) = val[it];
+          });
+        } else {
+          static_for<32 / RPI>([&](auto IT_) {
+            constexpr int it = decltype(IT_)::value;
+            if (wave_m + mi * 32 + it * RPI + row_t < g.M && 2 * j < g.N) *(u32x4_t*)(dst + (int64_t)(it * RPI) * ldo) = val[it];
+          });
+        }
       });
     } else {
 #pragma unroll
