@@ -135,8 +135,12 @@ __device__ __forceinline__ void sk_finish(const pt_gemm_args& g, int b, int tile
 // block holds its 16-byte chunk c at position c ^ swizzle(r): writes and fragment reads are conflict-free.
 // Weight rows use two rotating register sets, refilled with step s+2 as soon as step s is parked, so two
 // steps of weights are in flight per wavefront; A uses one register set and one LDS slot.
+// `items` > 1: the workgroup works through that many consecutive groups of RB tiles of its track, and the first
+// loads of the next group are in flight while the partial tiles of the current one are reduced and stored.  All
+// workgroups of a launch start together; with one group each they would all wait for their first loads, stream,
+// and reduce at the same moments, and HBM would idle in between.
 template <int MI, int RB, int EPI>
-__device__ __forceinline__ void skinny_body(const pt_gemm_args& g, int b, int first_tile, int ks, int ksn) {
+__device__ __forceinline__ void skinny_body(const pt_gemm_args& g, int b, int first_tile, int ks, int ksn, int items = 1) {
   constexpr int A_STEP = MI * 32 * 128;                 // bytes of A per K step
   constexpr int W_STEP = RB * 32 * 128;                 // bytes of W per K step
   constexpr int RING = A_STEP + W_STEP;                 // per wavefront
@@ -159,16 +163,19 @@ __device__ __forceinline__ void skinny_body(const pt_gemm_args& g, int b, int fi
     dst[i] = row * 128 + (((lane & 7) ^ swz(row)) * 16);
   }
   const bf16_t* w_src[RB][4];
+  auto set_w_src = [&](int tile0) {
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    const sk_tile tl = sk_decode_tile<EPI>(g, first_tile + rb);
+    for (int rb = 0; rb < RB; ++rb) {
+      const sk_tile tl = sk_decode_tile<EPI>(g, tile0 + rb);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int r = i * 8 + (lane >> 3);
-      const int wrow = r < 16 ? tl.n_a + r : tl.n_b + (r - 16);
-      w_src[rb][i] = (const bf16_t*)g.W + b * g.w_bstride + (int64_t)wrow * g.ldb + k_first + (lane & 7) * 8;
+      for (int i = 0; i < 4; ++i) {
+        const int r = i * 8 + (lane >> 3);
+        const int wrow = r < 16 ? tl.n_a + r : tl.n_b + (r - 16);
+        w_src[rb][i] = (const bf16_t*)g.W + b * g.w_bstride + (int64_t)wrow * g.ldb + k_first + (lane & 7) * 8;
+      }
     }
-  }
+  };
+  set_w_src(first_tile);
   const bf16_t* a_src[4 * MI];
 #pragma unroll
   for (int j = 0; j < 4 * MI; ++j) {
@@ -204,12 +211,6 @@ __device__ __forceinline__ void skinny_body(const pt_gemm_args& g, int b, int fi
   const int fr_row = l32 * 128, fr_sw = swz(l32);
 
   f32x16_t acc[RB][MI];
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[rb][mi][v] = 0.f;
 
   auto mul_step = [&](int step) {
     const char* a_slot = a_ring;
@@ -232,33 +233,6 @@ __device__ __forceinline__ void skinny_body(const pt_gemm_args& g, int b, int fi
 
   // Loads past the last step re-read it (never used).  The prologue issues its loads in the order of the
   // loop body, so that the waits the compiler derives for the loop need not cover a different order on entry.
-  load_w(0, 0);
-  __builtin_amdgcn_sched_barrier(0);
-  load_a(0);
-  __builtin_amdgcn_sched_barrier(0);
-  park_a(0);
-  __builtin_amdgcn_sched_barrier(0);
-  load_w(1, min(1, nsteps - 1));
-  __builtin_amdgcn_sched_barrier(0);
-  load_a(min(1, nsteps - 1));
-  for (int s0 = 0; s0 < nsteps; s0 += 2) {   // nsteps is even
-#pragma unroll
-    for (int par = 0; par < 2; ++par) {
-      const int st = s0 + par;
-      __builtin_amdgcn_sched_barrier(0);
-      park_w(par);                                // step st; the fragments of step st-1 have been read
-      __builtin_amdgcn_sched_barrier(0);
-      load_w(par, min(st + 2, nsteps - 1));
-      __builtin_amdgcn_sched_barrier(0);
-      mul_step(st);
-      __builtin_amdgcn_sched_barrier(0);
-      park_a(st + 1);                             // the fragments of step st have been read
-      __builtin_amdgcn_sched_barrier(0);
-      load_a(min(st + 2, nsteps - 1));
-    }
-  }
-  __syncthreads();   // the rings become the reduction buffer
-
   // Register v of a lane is C^T row 8*(v/4) + 4*half + v%4, column l32.  Wavefront w finishes m-block w/2,
   // register groups (w%2) and (w%2)+2: rows 8*(w%2)+4*half+i of each segment.
   const int mi_e = wave >> 1, vg = wave & 1;
@@ -266,28 +240,70 @@ __device__ __forceinline__ void skinny_body(const pt_gemm_args& g, int b, int fi
   const int off = 8 * vg + 4 * half;   // column offset inside a segment
   const bool owner = mi_e < MI && m < g.M;
 
-  auto finish = [&](int rb, const float (&lo)[4], const float (&hi)[4]) {
-    sk_finish<EPI>(g, b, first_tile + rb, m, off, ks, ksn, lo, hi);
-  };
-
-  // per block of weight rows: the four wavefronts' partial tiles meet in LDS
+  load_w(0, 0);
+  __builtin_amdgcn_sched_barrier(0);
+  load_a(0);
+  for (int item = 0; item < items; ++item) {
+    const int tile0 = first_tile + item * RB;
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    if (rb > 0) __syncthreads();
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
+      for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) red[wave][mi][v][lane] = acc[rb][mi][v];
-    __syncthreads();
-    if (owner) {
-      float lo[4], hi[4];
+        for (int v = 0; v < 16; ++v) acc[rb][mi][v] = 0.f;
+    __builtin_amdgcn_sched_barrier(0);
+    park_a(0);
+    __builtin_amdgcn_sched_barrier(0);
+    load_w(1, min(1, nsteps - 1));
+    __builtin_amdgcn_sched_barrier(0);
+    load_a(min(1, nsteps - 1));
+    for (int s0 = 0; s0 < nsteps; s0 += 2) {   // nsteps is even
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        lo[i] = red[0][mi_e][vg * 4 + i][lane] + red[1][mi_e][vg * 4 + i][lane] + red[2][mi_e][vg * 4 + i][lane] + red[3][mi_e][vg * 4 + i][lane];
-        hi[i] = red[0][mi_e][vg * 4 + 8 + i][lane] + red[1][mi_e][vg * 4 + 8 + i][lane] + red[2][mi_e][vg * 4 + 8 + i][lane] + red[3][mi_e][vg * 4 + 8 + i][lane];
+      for (int par = 0; par < 2; ++par) {
+        const int st = s0 + par;
+        __builtin_amdgcn_sched_barrier(0);
+        park_w(par);                                // step st; the fragments of step st-1 have been read
+        __builtin_amdgcn_sched_barrier(0);
+        load_w(par, min(st + 2, nsteps - 1));
+        __builtin_amdgcn_sched_barrier(0);
+        mul_step(st);
+        __builtin_amdgcn_sched_barrier(0);
+        park_a(st + 1);                             // the fragments of step st have been read
+        __builtin_amdgcn_sched_barrier(0);
+        load_a(min(st + 2, nsteps - 1));
       }
-      finish(rb, lo, hi);
     }
+    __syncthreads();   // the rings become the reduction buffer
+    if (item + 1 < items) {
+      // the next group's first loads travel while this one is reduced and stored
+      __builtin_amdgcn_sched_barrier(0);
+      set_w_src(tile0 + RB);
+      load_w(0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      load_a(0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+
+    // per block of weight rows: the four wavefronts' partial tiles meet in LDS
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      if (rb > 0) __syncthreads();
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) red[wave][mi][v][lane] = acc[rb][mi][v];
+      __syncthreads();
+      if (owner) {
+        float lo[4], hi[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          lo[i] = red[0][mi_e][vg * 4 + i][lane] + red[1][mi_e][vg * 4 + i][lane] + red[2][mi_e][vg * 4 + i][lane] + red[3][mi_e][vg * 4 + i][lane];
+          hi[i] = red[0][mi_e][vg * 4 + 8 + i][lane] + red[1][mi_e][vg * 4 + 8 + i][lane] + red[2][mi_e][vg * 4 + 8 + i][lane] + red[3][mi_e][vg * 4 + 8 + i][lane];
+        }
+        sk_finish<EPI>(g, b, tile0 + rb, m, off, ks, ksn, lo, hi);
+      }
+    }
+    if (item + 1 < items) __syncthreads();   // the reduction buffer becomes the rings again
   }
 }
 
@@ -469,23 +485,24 @@ __device__ __forceinline__ void skinny_group(const pt_gemm_args& g, int bg, int 
 }
 
 template <int MI, int RB, int EPI>
-__device__ __forceinline__ void skinny_dispatch(const pt_gemm_args& g, int b, int first_tile, int ks, int ksn) {
+__device__ __forceinline__ void skinny_dispatch(const pt_gemm_args& g, int b, int first_tile, int ks, int ksn, int items = 1) {
   if constexpr (EPI == EPI_SWIGLU || EPI == EPI_STORE_F32) {
-    if (g.n_groups > 0) { skinny_group<MI, RB, EPI>(g, b, first_tile, ks, ksn); return; }
+    if (g.n_groups > 0) { skinny_group<MI, RB, EPI>(g, b, first_tile, ks, ksn); return; }   // one group of tiles each
   }
-  skinny_body<MI, RB, EPI>(g, b, first_tile, ks, ksn);
+  skinny_body<MI, RB, EPI>(g, b, first_tile, ks, ksn, items);
 }
 
 // The tiles (blocks of 32 weight rows) of a track are dealt out to wgs_per_track workgroups as evenly as
 // possible: `rem` workgroups take RBHI tiles, the others RBHI - 1 (all take RBHI when rem == 0).  The grid
 // lists the larger workgroups of all tracks first, so that a second round of workgroups fills up evenly.
 // Workgroups that share output tiles (one per K slice, EPI_RESIDUAL only) are neighbours in the grid.
+// items > 1 (only with rem == 0): wgs_per_track counts workgroups that take `items` consecutive groups of RBHI tiles.
 template <int MI, int RBHI, int EPI>
-__global__ void __launch_bounds__(256) gemm_skinny_kernel(const pt_gemm_args g, int wgs_per_track, int rem, int ksn) {
+__global__ void __launch_bounds__(256) gemm_skinny_kernel(const pt_gemm_args g, int wgs_per_track, int rem, int ksn, int items) {
   const int unit = blockIdx.x / ksn, ks = blockIdx.x - unit * ksn;
   if (rem == 0) {
     const int b = unit / wgs_per_track, wg = unit - b * wgs_per_track;
-    skinny_dispatch<MI, RBHI, EPI>(g, b, wg * RBHI, ks, ksn);
+    skinny_dispatch<MI, RBHI, EPI>(g, b, wg * items * RBHI, ks, ksn, items);
     return;
   }
   const int n_big = rem * g.batch;
@@ -504,17 +521,31 @@ __global__ void __launch_bounds__(256) gemm_skinny_kernel(const pt_gemm_args g, 
 // Tuning knob for benchmarks (pt_set_tuning): 0 = automatic, else 256 * workgroups per track + K slices
 // (where the shape allows).
 int pt_tune_skinny_plan = 0;
+static int pt_tune_skinny_items = 0;   // 0: automatic; 1: one group of tiles per workgroup; n: n groups where the plan allows
 
 struct sk_plan { int wpt, ks; };
 
+static int device_cus();
+
 template <int MI, int RBHI, int EPI>
 static int launch_skinny_rb(const pt_gemm_args& g, int tiles, sk_plan p, hipStream_t s) {
-  const unsigned grid = (unsigned)((int64_t)p.wpt * g.batch * p.ks);
   constexpr int RING = 4 * (MI + RBHI) * 32 * 128, RED = 4 * MI * 16 * 64 * 4;
   constexpr int LDS = RING > RED ? RING : RED;
+  // Groups of tiles per workgroup: when every workgroup takes the same number of tiles, as many consecutive groups
+  // as still leave every compute unit its resident workgroups (LDS: 160 KB per compute unit).
+  int items = 1;
+  if (tiles % p.wpt == 0 && g.n_groups == 0 && pt_tune_skinny_items != 1) {
+    const int64_t total = (int64_t)p.wpt * g.batch * p.ks;
+    const int64_t resident = (int64_t)device_cus() * ((160 * 1024) / LDS >= 3 ? 3 : (160 * 1024) / LDS >= 2 ? 2 : 1);
+    for (int d = 2; d <= 16; ++d)
+      if (p.wpt % d == 0 && total / d >= resident) items = d;
+    if (pt_tune_skinny_items > 1 && p.wpt % pt_tune_skinny_items == 0) items = pt_tune_skinny_items;
+  }
+  const int wpt = p.wpt / items;
+  const unsigned grid = (unsigned)((int64_t)wpt * g.batch * p.ks);
   auto kern = gemm_skinny_kernel<MI, RBHI, EPI>;
   PT_SET_MAX_LDS_ONCE(kern, LDS);
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), LDS, s, g, p.wpt, tiles % p.wpt, p.ks);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), LDS, s, g, wpt, tiles % p.wpt, p.ks, items);
   PT_HIP_CHECK(hipGetLastError());
   return 2;
 }
