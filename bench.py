@@ -26,7 +26,8 @@ resident in HBM before the timed region.  One JSON line is printed on stdout:
 --legs selects a subset (comma list of moe-prefill, moe-decode, large-prefill, large-decode-gqa, large-decode-mha, share-prefill,
 share-decode, share-merge, mid-prefill, mid-decode, throughput, cpu; default all), which is how the per-kernel profiles under
 profiles/ are taken.  Other modes: --paper-sweep (batch-1 latency over input lengths), --ceilings (sustained
-MFMA and HBM-read rates of two bare loops).
+MFMA and HBM-read rates of two bare loops), --tile-clocks (where the time of a prefill GEMM tile goes: the tile
+kernel built from the same source with shader-clock stamps).
 """
 import argparse
 import dataclasses
@@ -400,6 +401,60 @@ def run_cpu_baseline(I):
                       "equal layers, not a measurement of the full depth" % (t_layer, t_head, t_layer, t_head)}
 
 
+def run_tile_clocks(torch):
+    """Where the time of a 256 x 256 tile of the prefill GEMM goes at the Large shapes (libpt_ceilings.so,
+    pt_gemm_tile_clocks: the forward library's tile kernel compiled from the same source with shader-clock
+    stamps): entry to first MFMA, K loop, barrier, epilogue, per wavefront, averaged over the launch."""
+    import ctypes as C
+    path = os.path.join(ROOT, "paper_2602_07306_amd", "libpt_ceilings.so")
+    if not os.path.exists(path):
+        raise ImportError("%s is missing: build it with `python -m paper_2602_07306_amd.build`" % path)
+    L = C.CDLL(path)
+    vp, i32 = C.c_void_p, C.c_int32
+    L.pt_gemm_tile_clocks.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, C.c_size_t, vp,
+                                      C.POINTER(C.c_double)]
+    st = torch.cuda.current_stream().cuda_stream
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(11)
+    T, M = 8, 8 * 4096
+    shapes = [("gate/up (SwiGLU epilogue, folded-norm row factors)", 2, 16384, 2048),
+              ("down (residual epilogue with the folded-norm outputs)", 1, 2048, 8192),
+              ("out-projection (residual epilogue with the folded-norm outputs)", 1, 2048, 2048),
+              ("out-projection shape, fp32 store only", 0, 2048, 2048)]
+    out = []
+    for name, epi, N, K in shapes:
+        a = torch.randn((T, M, K), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        w = (0.02 * torch.randn((T, N, K), generator=gen, device="cuda", dtype=torch.float32)).to(torch.bfloat16)
+        o = torch.zeros((T, M, N), dtype=torch.float32, device="cuda")
+        tiles = T * (M // 256) * (N // 256)
+        stamps = torch.zeros(tiles * 32, dtype=torch.int64, device="cuda")
+        rf = torch.ones((T, M), dtype=torch.float32, device="cuda") if epi == 2 else None
+        ob = torch.empty((T, M, N), dtype=torch.bfloat16, device="cuda") if epi == 1 else None
+        gain = torch.ones((T, N), dtype=torch.float32, device="cuda") if epi == 1 else None
+        sums = torch.empty((T, M, N // 128), dtype=torch.float32, device="cuda") if epi == 1 else None
+        res = (C.c_double * 10)()
+        ptr = lambda t: t.data_ptr() if t is not None else None
+        rc = L.pt_gemm_tile_clocks(epi, a.data_ptr(), w.data_ptr(), o.data_ptr(), ptr(ob), ptr(rf), ptr(gain), ptr(sums),
+                                   M, N, K, T, stamps.data_ptr(), stamps.numel() * 8, st, res)
+        if rc != 0:
+            raise RuntimeError("pt_gemm_tile_clocks failed with %d" % rc)
+        r = list(res)
+        ms = r[9]
+        rec = {"gemm": name, "M": M, "N": N, "K": K, "batch": T, "ms_per_launch": ms,
+               "TFLOPs": 2.0 * M * N * K * T / (ms * 1e-3) / 1e12,
+               "clocks": {"entry_to_first_mfma": r[0], "k_loop": r[1], "barrier": r[2], "epilogue": r[3], "tile": r[4]},
+               "tile_us": r[5] / 1e3, "shader_clock_GHz": r[4] / r[5], "stamped_launch_span_ms": r[6] / 1e6,
+               "tiles": int(r[7]), "tiles_per_cu": r[7] / 256.0, "k_loop_clocks_at_mfma_rate": 2.0 * 256 * 256 * K / 4069.0}
+        out.append(rec)
+        log("%s: %.2f ms/launch (%.0f TFLOP/s); per tile %.1f k clocks = first MFMA after %.1f k + K loop %.1f k "
+            "(%.1f k at the MFMA rate) + barrier %.1f k + epilogue %.1f k; clock %.2f GHz"
+            % (name, ms, rec["TFLOPs"], r[4] / 1e3, r[0] / 1e3, r[1] / 1e3, rec["k_loop_clocks_at_mfma_rate"] / 1e3,
+               r[2] / 1e3, r[3] / 1e3, rec["shader_clock_GHz"]))
+        del a, w, o, stamps, rf, ob, gain, sums
+        torch.cuda.empty_cache()
+    return out
+
+
 def run_ceilings(torch, I):
     """Sustained rates of bare loops on this GPU (libpt_ceilings.so, include/pt_ceilings.h): the matrix-core loop
     on all-zero operands and on operands distributed like the model's (N(0,1) activations against N(0,0.02)
@@ -512,6 +567,8 @@ def main():
     ap.add_argument("--mid-decode-steps", type=int, default=128)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy kernel (reference for the HBM byte counters of a rocprofv3 --pmc pass)")
+    ap.add_argument("--tile-clocks", action="store_true",
+                    help="per-phase shader clocks of the prefill GEMM's 256x256 tile at the Large shapes")
     ap.add_argument("--ceilings", action="store_true",
                     help="instead of the benchmark: sustained MFMA / HBM / LDS rates of bare loops (one JSON line)")
     ap.add_argument("--paper-sweep", action="store_true",
@@ -550,6 +607,10 @@ def main():
             raise RuntimeError("copy calibration failed")
         torch.cuda.synchronize()
         del src, dst
+    if args.tile_clocks:
+        print(json.dumps({"gemm_tile_clocks": run_tile_clocks(torch), "n_gpus": 1, "dtype": "bf16", "data": "synthetic"}),
+              flush=True)
+        return
     if args.ceilings:
         print(json.dumps({"ceilings": run_ceilings(torch, I), "n_gpus": 1, "dtype": "bf16", "data": "synthetic"}), flush=True)
         return

@@ -42,6 +42,20 @@ int pt_ceiling_hbm_copy(const void* dev_src, void* dev_dst, size_t bytes, int32_
 int pt_ceiling_lds_read(void* dev_sink, int32_t waves_per_simd, int32_t iters, int32_t reps, void* hip_stream,
                         double clock_ghz, double* bytes_per_clk_cu, double* gbs);
 
+/* Where the time of a 256 x 256 tile of the prefill GEMM goes: one launch of the forward library's tile kernel,
+ * compiled from the same source with shader-clock stamps, over batch x ([M, K] x [N, K]^T) in bf16 (M and N
+ * multiples of 256, K a multiple of 128).  epilogue: 0 fp32 store, 1 fp32 residual add in place (dev_out), 2 SwiGLU
+ * (bf16 [batch][M][N/2] into dev_out).  Optional: dev_row_factor (float [batch][M], SwiGLU: the folded RMSNorm factor),
+ * dev_out_bf16 / dev_gain / dev_row_sums (residual: the folded RMSNorm outputs, bf16 [batch][M][N], float
+ * [batch][N], float [batch][M][N/128]); all three or none.  dev_stamps: scratch of at least tiles * 4 * 8 * 8 bytes.
+ * Three unstamped launches are timed first.  out10: mean shader clocks of entry to first MFMA, K loop, barrier
+ * behind it, epilogue, whole tile; then the tile's time in ns, the launch's span in ns, tiles, wavefronts that left
+ * stamps, and ms per unstamped launch.  Allocates a host buffer for the stamps only. */
+int pt_gemm_tile_clocks(int32_t epilogue, const void* dev_a, const void* dev_w, void* dev_out, void* dev_out_bf16,
+                        const float* dev_row_factor, const float* dev_gain, float* dev_row_sums, int32_t M, int32_t N,
+                        int32_t K, int32_t batch, int64_t* dev_stamps, size_t stamp_bytes, void* hip_stream,
+                        double* out10);
+
 #ifdef __cplusplus
 }
 #endif

@@ -17,7 +17,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpt.so")
 CEILINGS_LIB = os.path.join(HERE, "libpt_ceilings.so")   # bench.py --ceilings only
-CEILINGS_SOURCES = ["bench_ceilings.hip"]
+CEILINGS_SOURCES = ["bench_ceilings.hip", "bench_gemm_tiles.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 SOURCES = [

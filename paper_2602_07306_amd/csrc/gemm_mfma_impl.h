@@ -120,6 +120,20 @@ __device__ __forceinline__ tile_coord map_tile(int id, int total, int tiles_m, i
 // RMSNorm scale that the QKV and SwiGLU epilogues apply to the accumulators of that row.
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
+// Instrumented build (the tile-clock benchmark only): every wavefront of gemm_mfma_kernel leaves shader-clock
+// stamps of its phases in pt_gemm_stamps[(workgroup * 4 + wavefront) * 8 + i]; i = 0 entry, 1 first MFMA, 2 end of
+// the K loop, 3 past the barrier, 4 end of the epilogue; 6 and 7 the constant 100 MHz counter at entry and exit.
+#ifdef PT_GEMM_STAMPS
+__device__ long long* pt_gemm_stamps = nullptr;
+#define PT_STAMP(i)                                                                                                    \
+  do {                                                                                                                 \
+    if ((threadIdx.x & 63) == 0 && pt_gemm_stamps)                                                                     \
+      pt_gemm_stamps[((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 8 + (i)] = ((i) >= 6) ? wall_clock64() : clock64(); \
+  } while (0)
+#else
+#define PT_STAMP(i) ((void)0)
+#endif
+
 // Element v of an accumulator tile.  Kernels whose accumulators fill the accumulation registers (more than 128 per
 // lane) read them with an explicit v_accvgpr_read at the point of use: left to itself, the register allocator moves
 // all of them to vector registers at once when the K loop ends, spills what does not fit to scratch memory, and the
@@ -555,6 +569,8 @@ __device__ __forceinline__ void gemm_epilogue(const pt_gemm_args& g, f32x16_t (&
 template <int BM, int BN, int WM, int WN, int BK, int EPI>
 __global__ void __launch_bounds__(WM * WN * 64, (2 * (BM + BN) * BK * 2 <= 80 * 1024 && BM * BN <= 256 * 128 && WM * WN == 4) ? 2 : 1)
 gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
+  PT_STAMP(6);
+  PT_STAMP(0);
   constexpr int NT = WM * WN * 64;
   constexpr int TM = BM / WM, TN = BN / WN, MI = TM / 32, NI = TN / 32;
   constexpr int CPR = BK / 8;        // 16-byte chunks per LDS row
@@ -732,6 +748,7 @@ gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
     for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
+  PT_STAMP(1);
   if constexpr (LATE2) {
     iteration(std::integral_constant<int, 0>{}, std::true_type{}, 0);
     iteration(std::integral_constant<int, 1>{}, std::false_type{}, 1);
@@ -740,8 +757,10 @@ gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
     iteration(std::integral_constant<int, 0>{}, std::false_type{}, kt);
     iteration(std::integral_constant<int, 1>{}, std::false_type{}, kt + 1);
   }
+  PT_STAMP(2);
   if (has_rs && tid < BM) rs_inv[tid] = rs_mine;
   __syncthreads();   // LDS is free for the staged epilogues
+  PT_STAMP(3);
 
   // ------------------------------------------------------------------ epilogue
   // LDS patch of this wavefront for the staged epilogues (the K loop is over: all of LDS is free)
@@ -753,6 +772,8 @@ gemm_mfma_kernel(const pt_gemm_args g, int tiles_m, int tiles_n) {
   const int wave_m = m0 + wm * TM;
 
   gemm_epilogue<MI, NI, EPI, STAGED, STAGE_ELEMS>(g, acc, stage, b, wave_m, wave_n, lane, has_rs ? rs_inv + wm * TM : nullptr);
+  PT_STAMP(4);
+  PT_STAMP(7);
 }
 
 // ------------------------------------------------------------------------------------------------
