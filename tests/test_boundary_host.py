@@ -37,6 +37,18 @@ def test_dynamic_symbol_table_holds_only_the_declared_functions():
     assert exported == declared_functions()
 
 
+def test_benchmark_library_exports_what_its_header_declares():
+    """libpt_ceilings.so (bare-loop ceilings and the stamped GEMM tile) loads without a GPU and exports the functions
+    of include/pt_ceilings.h."""
+    text = open(os.path.join(ROOT, "include", "pt_ceilings.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = sorted(set(re.findall(r"\b(pt_[a-z_0-9]+)\s*\(", text)))
+    assert "pt_ceiling_mfma_bf16" in names and "pt_gemm_tile_clocks" in names
+    L = C.CDLL(os.path.join(ROOT, "paper_2602_07306_amd", "libpt_ceilings.so"))
+    for n in names:
+        assert hasattr(L, n), n
+
+
 def test_tuning_knobs_are_validated():
     assert PB.lib().pt_set_tuning(99, 0) == PB.PT_ERR_INVALID_ARGUMENT
     assert "knob" in PB.pt_last_error()
