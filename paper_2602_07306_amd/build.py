@@ -6,7 +6,9 @@ Object files go to paper_2602_07306_amd/_build/, the library to paper_2602_07306
 """
 from __future__ import annotations
 
+import json
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -58,16 +60,41 @@ def _headers_mtime() -> float:
     return max(os.path.getmtime(h) for h in hs)
 
 
+def resources_path(src: str) -> str:
+    """Where the compiler's per-kernel resource report of a source file is kept (tests read it)."""
+    return os.path.join(BUILD, os.path.splitext(src)[0] + ".resources.json")
+
+
+def _kernel_resources(remarks: str) -> dict:
+    """{mangled kernel name: {"VGPRs", "AGPRs", "ScratchSize", "VGPRs Spill", "Occupancy", ...}} from the remarks of
+    -Rpass-analysis=kernel-resource-usage."""
+    out, cur = {}, None
+    for line in remarks.splitlines():
+        m = re.search(r"remark:\s+Function Name: (\S+)", line)
+        if m:
+            cur = out.setdefault(m.group(1), {})
+            continue
+        m = re.search(r"remark:\s+([A-Za-z ]+?)(?: \[[^\]]*\])?: (\S+) \[-Rpass", line)
+        if m and cur is not None:
+            v = m.group(2)
+            cur[m.group(1).strip()] = int(v) if v.isdigit() else v
+    return out
+
+
 def _compile(src: str, force: bool) -> str:
     obj = os.path.join(BUILD, os.path.splitext(src)[0] + ".o")
     path = os.path.join(CSRC, src)
-    if (not force and os.path.exists(obj)
+    is_kernel_source = src.endswith(".hip")
+    if (not force and os.path.exists(obj) and (not is_kernel_source or os.path.exists(resources_path(src)))
             and os.path.getmtime(obj) > max(os.path.getmtime(path), _headers_mtime())):
         return obj
-    cmd = [HIPCC] + COMMON + PER_FILE.get(src, []) + ["-c", path, "-o", obj]
+    cmd = [HIPCC] + COMMON + PER_FILE.get(src, []) + ["-Rpass-analysis=kernel-resource-usage", "-c", path, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (src, r.stdout, r.stderr))
+    if is_kernel_source:
+        with open(resources_path(src), "w") as f:
+            json.dump(_kernel_resources(r.stderr), f, indent=1, sort_keys=True)
     return obj
 
 
